@@ -1,0 +1,23 @@
+"""CPU oracle for the Distributed Lion optimizer sweep -- TEST INFRASTRUCTURE.
+
+Only the tests, the smoke check and the benchmark's CPU-baseline leg may import
+this package.  It shares no code with the HIP library and the product path never
+calls it.  See ``dlion_oracle.c`` for the arithmetic (Algorithm 1; Section 3.2)
+and ``dlion_oracle.py`` for the numpy-facing wrapper.
+"""
+from .dlion_oracle import (  # noqa: F401
+    AVG,
+    Oracle,
+    SOURCE,
+    VOTE,
+    aggregate_packed,
+    aggregate_signs,
+    apply,
+    build,
+    compile_source,
+    default,
+    step,
+    step_mt,
+    worker_step,
+    words_for,
+)
