@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused Distributed Lion step on one MI355X.
+
+A "step" is one pass of the whole hot path -- worker momentum and sign for all
+N workers, vote count, aggregation, weight update -- over one batch of
+synthetic gradients that already sit in HBM.  Prints ONE JSON line with the
+throughput in parameter-updates/s (d*N per step), the achieved fraction of the
+HBM roofline for the fused kernel, and the CPU oracle timed on the host cores
+on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, vendor figure
+
+
+def algorithmic_bytes_per_step(d: int, N: int, g_bytes: int) -> int:
+    """What the method must move per fused step: per update m in, m out, g in; per coordinate x in, x out."""
+    return d * N * (4 + 4 + g_bytes) + 8 * d
+
+
+def cpu_baseline(w, x, m, g, seconds_target: float = 15.0):
+    """Time the CPU oracle (as it stands) on the first coordinates of the same workload."""
+    import numpy as np
+    import torch
+
+    import oracle
+
+    cores = min(len(os.sched_getaffinity(0)), 16)
+    d_s = min(w.d, 4_000_000)
+    xs = x[:d_s].cpu().numpy().copy()
+    ms = m[:, :d_s].cpu().numpy().copy()
+    gc = g[:, :d_s].cpu().contiguous()
+    gs = gc.view(torch.int16).numpy().view(np.uint16).copy() if gc.dtype == torch.bfloat16 else gc.numpy().copy()
+    oracle.step(xs.copy(), ms.copy(), gs, w.mode, w.beta1, w.beta2, w.lr, w.lam, threads=cores)   # warm
+    t0 = time.perf_counter()
+    oracle.step(xs.copy(), ms.copy(), gs, w.mode, w.beta1, w.beta2, w.lr, w.lam, threads=cores)
+    one = max(time.perf_counter() - t0, 1e-6)
+    reps = max(1, min(200, int(seconds_target / one)))
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        oracle.step(xs, ms, gs, w.mode, w.beta1, w.beta2, w.lr, w.lam, threads=cores)
+    dt = time.perf_counter() - t0
+    return {
+        "value": d_s * w.N * reps / dt,
+        "unit": "param-updates/s",
+        "cores": cores,
+        "kind": "oracle",
+        "sample": f"first {d_s} of {w.d} coordinates x {w.N} workers, {reps} steps, {cores} threads",
+    }
+
+
+def recorded_traffic(workload: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one for this workload."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload, {}).get("bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="gpt2s_avg8")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py measures one GPU: every worker of the simulated run lives on the same device and "
+              "no collectives are built; run it with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2404_00438_amd as dl
+    from paper_2404_00438_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    dl.load_library()
+    w = wl.CONFIGS[args.workload]
+    if w.shapes is not None or w.g_dist == "packed_bernoulli":
+        print("bench.py times flat fused-step workloads", file=sys.stderr)
+        return 2
+
+    x = wl.init_x(w, dev)
+    m = wl.init_m(w, dev)
+    g = wl.make_grads(w, 0, dev)
+    torch.cuda.synchronize()
+
+    def step():
+        dl.dlion_step(x, m, g, w.mode, w.beta1, w.beta2, w.lr, w.lam)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()                      # same stream the kernels are launched on (torch's current stream)
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_ms = ev0.elapsed_time(ev1) / args.steps
+
+    g_bytes = 2 if w.g_dtype == torch.bfloat16 else 4
+    bytes_per_launch = algorithmic_bytes_per_step(w.d, w.N, g_bytes)
+    achieved = bytes_per_launch / (kernel_ms * 1e-3) / 1e9
+    out = {
+        "metric": "param-updates/s (d*N per fused step)",
+        "value": w.d * w.N * args.steps / wall,
+        "unit": "param-updates/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": w.name, "d": w.d, "workers": w.N, "aggregation": "avg" if w.mode else "vote",
+            "grad_dtype": str(w.g_dtype).replace("torch.", ""), "grad_dist": w.g_dist,
+            "state_dtype": "float32", "kernel": "dlion_step (fused, no packed/counts output)",
+        },
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": recorded_traffic(w.name),
+            "kernel_ms": kernel_ms,
+            "bytes_per_launch": bytes_per_launch,
+            "bytes_per_update": bytes_per_launch / (w.d * w.N),
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, x, m, g)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,181 @@
+/*
+ * dlion.h -- C ABI of the MI355X (gfx950) Distributed Lion optimizer sweep.
+ *
+ * One iteration of Distributed Lion (Algorithm 1; Section 3.2) for N simulated
+ * workers that all live on one GPU:
+ *
+ *   worker i :  delta_i = sign(beta1*m_i + (1-beta1)*g_i)            (1 bit / coordinate)
+ *               m_i    <- beta2*m_i + (1-beta2)*g_i                  (old m_i on the right)
+ *   server   :  S = sum_i delta_i ;  Delta = S/N  (averaging)  or  sign(S)  (majority vote)
+ *   everyone :  x <- x - lr*(Delta + lambda*x)
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ * Memory.   Every pointer is a DEVICE pointer unless its comment says "host".
+ *           The caller owns all memory; the library allocates nothing, keeps no
+ *           state between calls and is re-entrant across streams.
+ * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default
+ *           stream).  Calls only enqueue work and return; they never synchronise.
+ * Types.    x and m are fp32.  g is fp32 or bf16 (`g_dtype`); bf16 is widened
+ *           to fp32 exactly.  All arithmetic is fp32, every multiply / add /
+ *           subtract / divide rounded on its own (no fused multiply-add),
+ *           subnormals kept.  (1-beta) is formed once on the host as
+ *           `1.0f - beta` in fp32.  Expressions are evaluated exactly as written
+ *           above:  c = (beta1*m) + ((1-beta1)*g);  x' = x - (lr*(Delta + (lambda*x))).
+ * Workers.  Worker i's momentum is m + i*m_stride, its gradient g + i*g_stride,
+ *           its packed update packed + i*packed_stride; strides count ELEMENTS
+ *           of the respective type (fp32 / g_dtype / uint64) and must be
+ *           >= d (>= W for packed).  Any stride is accepted; rows whose base is
+ *           16-byte aligned with a stride that keeps it so take the 128-bit path.
+ * Sign.     The worker's sign maps 0 (and -0, and NaN) to +1, so that delta is
+ *           one bit:  bit = !(c < 0).
+ * Packing.  W = ceil(d/64) uint64 words per worker; bit (j % 64) of word (j / 64),
+ *           least significant bit first, holds coordinate j: 1 for +1, 0 for -1.
+ *           Bits past d in the last word are written as 0.
+ * Counts.   p_j = number of workers voting +1 on coordinate j, 0..N, uint16.
+ *           The sum of the +-1 votes is S_j = 2*p_j - N.
+ * Vote.     Majority vote is sign(S) with sign(0) = 0: a tie leaves only the
+ *           weight-decay term.
+ * Average.  Delta = (float)S / (float)N, one correctly rounded fp32 division.
+ * Errors.   Arguments are validated on the host before anything is enqueued;
+ *           on error nothing is launched and a dlion_status other than DLION_OK
+ *           comes back.  No call aborts or throws.  NaN/Inf inputs are not
+ *           errors: they propagate through the arithmetic.
+ * Alignment x, m, g must be aligned to their element size, packed to 8 bytes,
+ *           counts to 2 bytes (DLION_EALIGN otherwise).
+ * Aliasing. m and x are updated in place; g and packed inputs are read-only;
+ *           no two distinct arguments may overlap.
+ */
+#ifndef DLION_H
+#define DLION_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum dlion_status {
+    DLION_OK = 0,
+    DLION_EINVAL = 1,       /* a size, stride, count or enum is out of range, or a pointer is NULL */
+    DLION_EALIGN = 2,       /* a pointer is not aligned to its element type */
+    DLION_ELAUNCH = 3,      /* the HIP runtime refused the launch (hipGetLastError != success) */
+    DLION_EUNSUPPORTED = 4  /* valid request outside what this build implements */
+} dlion_status;
+
+typedef enum dlion_mode { DLION_VOTE = 0, DLION_AVG = 1 } dlion_mode;   /* Section 3.2, aggregate() */
+typedef enum dlion_dtype { DLION_F32 = 0, DLION_BF16 = 1 } dlion_dtype; /* gradient storage type */
+
+#define DLION_MAX_WORKERS 65535 /* counts are uint16 */
+
+/*
+ * Worker side of one iteration for all N workers (Section 3.2, first display;
+ * Algorithm 1, worker-side):  reads m and g, writes m in place and the packed
+ * binary updates delta_i -- the d-bit message each worker would send.
+ *   m       [N rows of d] fp32, in/out        g      [N rows of d] g_dtype, in
+ *   packed  [N rows of W] uint64, out (tail bits zero)
+ */
+dlion_status dlion_worker_step(float *m, int64_t m_stride, const void *g, int64_t g_stride,
+                               dlion_dtype g_dtype, uint64_t *packed, int64_t packed_stride,
+                               int64_t d, int32_t N, float beta1, float beta2, void *stream);
+
+/*
+ * Server side, the sum (Section 3.2: S_t = sum_i delta_i, held as the count of
+ * +1 votes):  counts[j] = sum_i bit_i(j), j < d.
+ *   packed  [N rows of W] uint64, in          counts [d] uint16, out
+ */
+dlion_status dlion_aggregate(const uint64_t *packed, int64_t packed_stride, int64_t d, int32_t N,
+                             uint16_t *counts, void *stream);
+
+/*
+ * Aggregation and weight update from counts (Section 3.2, second and third
+ * displays; Algorithm 1, server-side and the x update):
+ *   Delta_j = (2 p_j - N)/N  or  sign(2 p_j - N);   x_j <- x_j - lr*(Delta_j + lambda*x_j).
+ *   x [d] fp32, in/out                         counts [d] uint16, in
+ */
+dlion_status dlion_apply(float *x, const uint16_t *counts, int64_t d, int32_t N, dlion_mode mode,
+                         float lr, float lambda, void *stream);
+
+/*
+ * dlion_aggregate and dlion_apply in one pass over the packed streams: Delta
+ * never leaves registers.  counts_or_null, if not NULL, also receives p_j.
+ */
+dlion_status dlion_aggregate_apply(float *x, const uint64_t *packed, int64_t packed_stride,
+                                   int64_t d, int32_t N, dlion_mode mode, float lr, float lambda,
+                                   uint16_t *counts_or_null, void *stream);
+
+/*
+ * The whole iteration (Algorithm 1, one pass of the loop body) in one kernel:
+ * worker step for all N workers, vote count, aggregation and weight update.
+ * Per coordinate it moves m in, m out and g in for each worker and x in and out
+ * once.  packed_or_null / counts_or_null, if not NULL, also receive the packed
+ * updates and the counts exactly as the unfused calls would write them.
+ */
+dlion_status dlion_step(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
+                        dlion_dtype g_dtype, int64_t d, int32_t N, dlion_mode mode, float beta1,
+                        float beta2, float lr, float lambda, uint64_t *packed_or_null,
+                        int64_t packed_stride, uint16_t *counts_or_null, void *stream);
+
+/* ------------------------------------------------------------------------- *
+ * Multi-tensor form: the model is a list of K tensors instead of one flat
+ * buffer.  Every tensor is an independent flat problem whose packed bits start
+ * on a fresh uint64 word:  tensor k owns words [word_begin_k, word_begin_k +
+ * ceil(numel_k/64)) of each worker's packed row and counts
+ * [64*word_begin_k, 64*word_begin_k + numel_k) of the counts array, which has
+ * 64*W_total entries (entries between a tensor's end and its next word boundary
+ * are written as 0 by calls that write counts).
+ * ------------------------------------------------------------------------- */
+typedef struct dlion_seg {
+    float *x;           /* [numel] fp32                                             */
+    float *m;           /* worker i at m + i*m_stride                               */
+    const void *g;      /* worker i at g + i*g_stride (elements of g_dtype)         */
+    int64_t m_stride;
+    int64_t g_stride;
+    int64_t numel;      /* > 0                                                      */
+    int64_t word_begin; /* filled by dlion_mt_layout                                */
+    int64_t tile_begin; /* filled by dlion_mt_layout (256-coordinate tiles)         */
+} dlion_seg;
+
+/*
+ * Host-only helper: fills word_begin / tile_begin of segs_host[0..K) (a HOST
+ * array) and returns the total words per worker row and the total tile count.
+ * The caller then copies the table to device memory (K*sizeof(dlion_seg)
+ * bytes, 8-byte aligned) and passes both copies to the _mt calls: the host
+ * copy is what gets validated, the device copy is what the kernels read.
+ */
+dlion_status dlion_mt_layout(dlion_seg *segs_host, int32_t K, int64_t *total_words,
+                             int64_t *total_tiles);
+
+dlion_status dlion_worker_step_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev, int32_t K,
+                                  dlion_dtype g_dtype, uint64_t *packed, int64_t packed_stride,
+                                  int32_t N, float beta1, float beta2, void *stream);
+
+dlion_status dlion_aggregate_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev, int32_t K,
+                                const uint64_t *packed, int64_t packed_stride, int32_t N,
+                                uint16_t *counts, void *stream);
+
+dlion_status dlion_apply_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev, int32_t K,
+                            const uint16_t *counts, int32_t N, dlion_mode mode, float lr,
+                            float lambda, void *stream);
+
+dlion_status dlion_aggregate_apply_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev,
+                                      int32_t K, const uint64_t *packed, int64_t packed_stride,
+                                      int32_t N, dlion_mode mode, float lr, float lambda,
+                                      uint16_t *counts_or_null, void *stream);
+
+dlion_status dlion_step_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev, int32_t K,
+                           dlion_dtype g_dtype, int32_t N, dlion_mode mode, float beta1,
+                           float beta2, float lr, float lambda, uint64_t *packed_or_null,
+                           int64_t packed_stride, uint16_t *counts_or_null, void *stream);
+
+/* Text for a status code (static storage, never NULL). */
+const char *dlion_status_str(dlion_status s);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int dlion_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DLION_H */

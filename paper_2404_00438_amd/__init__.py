@@ -1,0 +1,27 @@
+"""Distributed Lion optimizer sweep for MI355X (gfx950): hand-written HIP kernels behind a C ABI.
+
+``binding`` exposes the entry points of ``include/dlion.h`` under the same
+names; it marshals torch tensors into pointers and strides and nothing else.
+``workloads`` holds the seeded synthetic input recipes (no arithmetic of the
+method).  The library is loaded on first use and the load fails loudly if
+``libdlion.so`` has not been built -- there is no fallback path.
+"""
+from .binding import (  # noqa: F401
+    AVG,
+    VOTE,
+    DlionError,
+    SegTable,
+    dlion_aggregate,
+    dlion_aggregate_apply,
+    dlion_aggregate_apply_mt,
+    dlion_aggregate_mt,
+    dlion_apply,
+    dlion_apply_mt,
+    dlion_step,
+    dlion_step_mt,
+    dlion_version,
+    dlion_worker_step,
+    dlion_worker_step_mt,
+    load_library,
+    words_for,
+)

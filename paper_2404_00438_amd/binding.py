@@ -1,0 +1,293 @@
+"""ctypes binding of ``libdlion.so``: argument marshalling only.
+
+Every function here has the name and the meaning of the C entry point it calls
+(see ``include/dlion.h``).  Tensors are torch CUDA tensors; the binding passes
+their ``data_ptr()``, their row strides and the current HIP stream.  No step of
+the method is computed in Python, and nothing falls back to another
+implementation: if the shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+VOTE = 0
+AVG = 1
+F32 = 0
+BF16 = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdlion.so")
+_lib = None
+
+EXPORTS = (
+    "dlion_worker_step", "dlion_aggregate", "dlion_apply", "dlion_aggregate_apply", "dlion_step",
+    "dlion_mt_layout", "dlion_worker_step_mt", "dlion_aggregate_mt", "dlion_apply_mt",
+    "dlion_aggregate_apply_mt", "dlion_step_mt", "dlion_status_str", "dlion_version",
+)
+
+
+class DlionError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: status {status} ({status_str(status)})")
+
+
+class Seg(ctypes.Structure):
+    """Mirror of ``dlion_seg``."""
+    _fields_ = [
+        ("x", ctypes.c_void_p), ("m", ctypes.c_void_p), ("g", ctypes.c_void_p),
+        ("m_stride", ctypes.c_int64), ("g_stride", ctypes.c_int64), ("numel", ctypes.c_int64),
+        ("word_begin", ctypes.c_int64), ("tile_begin", ctypes.c_int64),
+    ]
+
+
+def load_library(path: Optional[str] = None) -> ctypes.CDLL:
+    """Load ``libdlion.so`` and declare the prototypes; raises if it has not been built."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or LIB_PATH
+    if not os.path.exists(p):
+        raise FileNotFoundError(
+            f"{p} is missing: build it first (python -m paper_2404_00438_amd.build); "
+            "there is no fallback implementation")
+    lib = ctypes.CDLL(p)
+    vp, i64, i32, f32, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_int
+    segp = ctypes.POINTER(Seg)
+    protos = {
+        "dlion_worker_step": [vp, i64, vp, i64, ci, vp, i64, i64, i32, f32, f32, vp],
+        "dlion_aggregate": [vp, i64, i64, i32, vp, vp],
+        "dlion_apply": [vp, vp, i64, i32, ci, f32, f32, vp],
+        "dlion_aggregate_apply": [vp, vp, i64, i64, i32, ci, f32, f32, vp, vp],
+        "dlion_step": [vp, vp, i64, vp, i64, ci, i64, i32, ci, f32, f32, f32, f32, vp, i64, vp, vp],
+        "dlion_mt_layout": [segp, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)],
+        "dlion_worker_step_mt": [segp, vp, i32, ci, vp, i64, i32, f32, f32, vp],
+        "dlion_aggregate_mt": [segp, vp, i32, vp, i64, i32, vp, vp],
+        "dlion_apply_mt": [segp, vp, i32, vp, i32, ci, f32, f32, vp],
+        "dlion_aggregate_apply_mt": [segp, vp, i32, vp, i64, i32, ci, f32, f32, vp, vp],
+        "dlion_step_mt": [segp, vp, i32, ci, i32, ci, f32, f32, f32, f32, vp, i64, vp, vp],
+    }
+    for name, argtypes in protos.items():
+        fn = getattr(lib, name)
+        fn.argtypes = argtypes
+        fn.restype = ci
+    lib.dlion_status_str.argtypes = [ci]
+    lib.dlion_status_str.restype = ctypes.c_char_p
+    lib.dlion_version.argtypes = []
+    lib.dlion_version.restype = ci
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def status_str(status: int) -> str:
+    return load_library().dlion_status_str(status).decode()
+
+
+def dlion_version() -> int:
+    return load_library().dlion_version()
+
+
+def words_for(d: int) -> int:
+    return (int(d) + 63) // 64
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise DlionError(status, what)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _rows(t: torch.Tensor, name: str):
+    """``[N, d]`` tensor with unit inner stride -> (pointer, row stride in elements, N, d)."""
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError(f"{name} must be [N, d] with contiguous rows")
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    return t.data_ptr(), t.stride(0), t.shape[0], t.shape[1]
+
+
+def _flat(t: torch.Tensor, name: str, dtype: torch.dtype):
+    if t.dtype != dtype or t.dim() != 1 or (t.numel() > 1 and t.stride(0) != 1) or not t.is_cuda:
+        raise ValueError(f"{name} must be a contiguous 1-D {dtype} device tensor")
+    return t.data_ptr()
+
+
+def _gdtype(g: torch.Tensor) -> int:
+    if g.dtype == torch.float32:
+        return F32
+    if g.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("g must be float32 or bfloat16")
+
+
+def _as_u64(t: torch.Tensor, name: str):
+    """packed words are 64-bit; torch carries them as int64 (same bits)."""
+    if t.dtype not in (torch.int64, torch.uint64):
+        raise TypeError(f"{name} must be int64/uint64 (uint64 words)")
+    return t
+
+
+def _as_u16(t: torch.Tensor, name: str):
+    if t.dtype not in (torch.int16, torch.uint16):
+        raise TypeError(f"{name} must be int16/uint16 (uint16 counts)")
+    return t
+
+
+def dlion_worker_step(m, g, packed, beta1, beta2, d=None, stream=None):
+    mp, ms, N, dd = _rows(m, "m")
+    gp, gs, Ng, dg = _rows(g, "g")
+    pp, ps, Np, _ = _rows(_as_u64(packed, "packed"), "packed")
+    if m.dtype != torch.float32 or (N, dd) != (Ng, dg) or Np != N:
+        raise ValueError("m must be fp32 and m, g, packed must agree on N and d")
+    d = dd if d is None else d
+    _check(load_library().dlion_worker_step(mp, ms, gp, gs, _gdtype(g), pp, ps, d, N, beta1, beta2,
+                                            _stream(stream)), "dlion_worker_step")
+
+
+def dlion_aggregate(packed, d, counts, stream=None):
+    pp, ps, N, _ = _rows(_as_u64(packed, "packed"), "packed")
+    cp = _as_u16(counts, "counts").data_ptr()
+    _check(load_library().dlion_aggregate(pp, ps, d, N, cp, _stream(stream)), "dlion_aggregate")
+
+
+def dlion_apply(x, counts, N, mode, lr, lam, stream=None):
+    xp = _flat(x, "x", torch.float32)
+    cp = _as_u16(counts, "counts").data_ptr()
+    _check(load_library().dlion_apply(xp, cp, x.numel(), N, mode, lr, lam, _stream(stream)), "dlion_apply")
+
+
+def dlion_aggregate_apply(x, packed, mode, lr, lam, counts=None, stream=None):
+    xp = _flat(x, "x", torch.float32)
+    pp, ps, N, _ = _rows(_as_u64(packed, "packed"), "packed")
+    cp = _as_u16(counts, "counts").data_ptr() if counts is not None else None
+    _check(load_library().dlion_aggregate_apply(xp, pp, ps, x.numel(), N, mode, lr, lam, cp, _stream(stream)),
+           "dlion_aggregate_apply")
+
+
+def dlion_step(x, m, g, mode, beta1, beta2, lr, lam, packed=None, counts=None, stream=None):
+    xp = _flat(x, "x", torch.float32)
+    mp, ms, N, d = _rows(m, "m")
+    gp, gs, Ng, dg = _rows(g, "g")
+    if m.dtype != torch.float32 or (N, d) != (Ng, dg) or x.numel() != d:
+        raise ValueError("m must be fp32 and x, m, g must agree on N and d")
+    pp, ps = (None, 0)
+    if packed is not None:
+        pp, ps, Np, _ = _rows(_as_u64(packed, "packed"), "packed")
+        if Np != N:
+            raise ValueError("packed must have N rows")
+    cp = _as_u16(counts, "counts").data_ptr() if counts is not None else None
+    _check(load_library().dlion_step(xp, mp, ms, gp, gs, _gdtype(g), d, N, mode, beta1, beta2, lr, lam,
+                                     pp, ps, cp, _stream(stream)), "dlion_step")
+
+
+class SegTable:
+    """Host and device copies of a ``dlion_seg`` table for a list of tensors.
+
+    ``xs[k]`` is the flat fp32 weight tensor ``[n_k]``; ``ms[k]`` / ``gs[k]``
+    are ``[N, n_k]`` with contiguous rows.  Any of the three lists may be
+    ``None`` when the calls to be made do not touch it (``numels`` then gives
+    the sizes).  The object keeps the tensors alive.
+    """
+
+    def __init__(self, xs: Optional[Sequence[torch.Tensor]] = None, ms=None, gs=None,
+                 numels: Optional[Sequence[int]] = None, device=None):
+        lists = [l for l in (xs, ms, gs) if l is not None]
+        if numels is None:
+            if xs is not None:
+                numels = [int(t.numel()) for t in xs]
+            elif lists:
+                numels = [int(t.shape[1]) for t in lists[0]]
+            else:
+                raise ValueError("need tensors or numels")
+        self.K = len(numels)
+        self.numels = list(numels)
+        self.keep = (xs, ms, gs)
+        self.N = None
+        self.g_dtype = F32
+        arr = (Seg * self.K)()
+        for k in range(self.K):
+            s = arr[k]
+            s.numel = self.numels[k]
+            if xs is not None:
+                s.x = _flat(xs[k], "x", torch.float32)
+                if xs[k].numel() != s.numel:
+                    raise ValueError("x size mismatch")
+            if ms is not None:
+                s.m, s.m_stride, N, n = _rows(ms[k], "m")
+                if ms[k].dtype != torch.float32 or n != s.numel:
+                    raise ValueError("m must be fp32 [N, numel]")
+                self.N = N if self.N is None else self.N
+                if N != self.N:
+                    raise ValueError("all tensors must have the same N")
+            if gs is not None:
+                s.g, s.g_stride, N, n = _rows(gs[k], "g")
+                if n != s.numel:
+                    raise ValueError("g must be [N, numel]")
+                self.N = N if self.N is None else self.N
+                if N != self.N:
+                    raise ValueError("all tensors must have the same N")
+                gd = _gdtype(gs[k])
+                if k and gd != self.g_dtype:
+                    raise ValueError("all gradients must share one dtype")
+                self.g_dtype = gd
+        tw, tt = ctypes.c_int64(0), ctypes.c_int64(0)
+        _check(load_library().dlion_mt_layout(arr, self.K, ctypes.byref(tw), ctypes.byref(tt)), "dlion_mt_layout")
+        self.host = arr
+        self.total_words = tw.value
+        self.total_tiles = tt.value
+        self.word_begin = [arr[k].word_begin for k in range(self.K)]
+        if device is None:
+            device = lists[0][0].device if lists else torch.device("cuda", torch.cuda.current_device())
+        raw = torch.frombuffer(bytearray(bytes(arr)), dtype=torch.uint8)
+        self.dev = raw.to(device)
+
+    @property
+    def dev_ptr(self) -> int:
+        return self.dev.data_ptr()
+
+
+def dlion_worker_step_mt(table: SegTable, packed, beta1, beta2, stream=None):
+    pp, ps, N, _ = _rows(_as_u64(packed, "packed"), "packed")
+    _check(load_library().dlion_worker_step_mt(table.host, table.dev_ptr, table.K, table.g_dtype, pp, ps, N,
+                                               beta1, beta2, _stream(stream)), "dlion_worker_step_mt")
+
+
+def dlion_aggregate_mt(table: SegTable, packed, counts, stream=None):
+    pp, ps, N, _ = _rows(_as_u64(packed, "packed"), "packed")
+    cp = _as_u16(counts, "counts").data_ptr()
+    _check(load_library().dlion_aggregate_mt(table.host, table.dev_ptr, table.K, pp, ps, N, cp,
+                                             _stream(stream)), "dlion_aggregate_mt")
+
+
+def dlion_apply_mt(table: SegTable, counts, N, mode, lr, lam, stream=None):
+    cp = _as_u16(counts, "counts").data_ptr()
+    _check(load_library().dlion_apply_mt(table.host, table.dev_ptr, table.K, cp, N, mode, lr, lam,
+                                         _stream(stream)), "dlion_apply_mt")
+
+
+def dlion_aggregate_apply_mt(table: SegTable, packed, mode, lr, lam, counts=None, stream=None):
+    pp, ps, N, _ = _rows(_as_u64(packed, "packed"), "packed")
+    cp = _as_u16(counts, "counts").data_ptr() if counts is not None else None
+    _check(load_library().dlion_aggregate_apply_mt(table.host, table.dev_ptr, table.K, pp, ps, N, mode, lr, lam,
+                                                   cp, _stream(stream)), "dlion_aggregate_apply_mt")
+
+
+def dlion_step_mt(table: SegTable, N, mode, beta1, beta2, lr, lam, packed=None, counts=None, stream=None):
+    pp, ps = (None, 0)
+    if packed is not None:
+        pp, ps, Np, _ = _rows(_as_u64(packed, "packed"), "packed")
+        if Np != N:
+            raise ValueError("packed must have N rows")
+    cp = _as_u16(counts, "counts").data_ptr() if counts is not None else None
+    _check(load_library().dlion_step_mt(table.host, table.dev_ptr, table.K, table.g_dtype, N, mode, beta1, beta2,
+                                        lr, lam, pp, ps, cp, _stream(stream)), "dlion_step_mt")

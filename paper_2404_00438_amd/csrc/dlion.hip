@@ -1,0 +1,400 @@
+// C ABI of the Distributed Lion sweep: argument validation and kernel launches.
+// The entry points and their contracts are documented in include/dlion.h.
+#include "dlion_kernels.hpp"
+
+#include <hip/hip_runtime.h>
+
+namespace {
+
+using namespace dlion;
+
+constexpr int64_t kMaxTiles = (int64_t)0x7FFFFFFF * kWavesPerBlock;
+
+inline bool aligned_to(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+inline int64_t tiles_for(int64_t numel) { return (numel + kTile - 1) / kTile; }
+inline int64_t words_for(int64_t numel) { return (numel + 63) / 64; }
+
+inline bool power_of_two(int32_t n) { return n > 0 && (n & (n - 1)) == 0; }
+
+Hyper make_hyper(int32_t N, int mode, float beta1, float beta2, float lr, float lambda)
+{
+    Hyper h;
+    h.beta1 = beta1;
+    h.omb1 = 1.0f - beta1;
+    h.beta2 = beta2;
+    h.omb2 = 1.0f - beta2;
+    h.lr = lr;
+    h.lambda = lambda;
+    h.inv_n = power_of_two(N) ? 1.0f / static_cast<float>(N) : 0.0f;
+    h.N = N;
+    h.mode = mode;
+    return h;
+}
+
+inline dim3 grid_for(int64_t tiles) { return dim3(static_cast<uint32_t>((tiles + kWavesPerBlock - 1) / kWavesPerBlock)); }
+
+inline dlion_status launched()
+{
+    return hipGetLastError() == hipSuccess ? DLION_OK : DLION_ELAUNCH;
+}
+
+// ------------------------------------------------------------------ dispatch
+template <typename GT, int kUnroll, bool kApply, class Addr>
+dlion_status launch_step_flags(const Addr &addr, const Hyper &h, bool packed, bool counts, hipStream_t s)
+{
+    const dim3 grid = grid_for(addr.total_tiles), block(kBlock);
+    if (packed && counts)
+        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, true, true, Addr>), grid, block, 0, s, addr, h);
+    else if (packed)
+        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, true, false, Addr>), grid, block, 0, s, addr, h);
+    else if (counts)
+        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, false, true, Addr>), grid, block, 0, s, addr, h);
+    else
+        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, false, false, Addr>), grid, block, 0, s, addr, h);
+    return launched();
+}
+
+template <typename GT, bool kApply, class Addr>
+dlion_status launch_step_unroll(const Addr &addr, const Hyper &h, bool packed, bool counts, hipStream_t s)
+{
+    // Loads of kUnroll workers are issued back to back before any arithmetic.
+    if (h.N >= 8)
+        return launch_step_flags<GT, 8, kApply, Addr>(addr, h, packed, counts, s);
+    if (h.N >= 4)
+        return launch_step_flags<GT, 4, kApply, Addr>(addr, h, packed, counts, s);
+    if (h.N >= 2)
+        return launch_step_flags<GT, 2, kApply, Addr>(addr, h, packed, counts, s);
+    return launch_step_flags<GT, 1, kApply, Addr>(addr, h, packed, counts, s);
+}
+
+template <bool kApply, class Addr>
+dlion_status launch_step(const Addr &addr, const Hyper &h, dlion_dtype g_dtype, bool packed, bool counts,
+                         hipStream_t s)
+{
+    if (g_dtype == DLION_BF16)
+        return launch_step_unroll<uint16_t, kApply, Addr>(addr, h, packed, counts, s);
+    return launch_step_unroll<float, kApply, Addr>(addr, h, packed, counts, s);
+}
+
+template <class Addr>
+dlion_status launch_aggregate(const Addr &addr, const Hyper &h, bool apply, bool counts, hipStream_t s)
+{
+    const dim3 grid = grid_for(addr.total_tiles), block(kBlock);
+    if (apply && counts)
+        hipLaunchKernelGGL((aggregate_kernel<true, true, Addr>), grid, block, 0, s, addr, h);
+    else if (apply)
+        hipLaunchKernelGGL((aggregate_kernel<true, false, Addr>), grid, block, 0, s, addr, h);
+    else
+        hipLaunchKernelGGL((aggregate_kernel<false, true, Addr>), grid, block, 0, s, addr, h);
+    return launched();
+}
+
+template <class Addr> dlion_status launch_apply(const Addr &addr, const Hyper &h, hipStream_t s)
+{
+    hipLaunchKernelGGL((apply_kernel<Addr>), grid_for(addr.total_tiles), dim3(kBlock), 0, s, addr, h);
+    return launched();
+}
+
+// ------------------------------------------------------------------ validation
+dlion_status check_common(int64_t d, int32_t N)
+{
+    if (d <= 0 || N < 1 || N > DLION_MAX_WORKERS)
+        return DLION_EINVAL;
+    if (tiles_for(d) > kMaxTiles)
+        return DLION_EUNSUPPORTED;
+    return DLION_OK;
+}
+
+dlion_status check_rows(const void *p, int64_t stride, int64_t extent, int32_t N, uintptr_t elem)
+{
+    if (!p)
+        return DLION_EINVAL;
+    if (!aligned_to(p, elem))
+        return DLION_EALIGN;
+    if (N > 1 && stride < extent)
+        return DLION_EINVAL;
+    return DLION_OK;
+}
+
+inline uintptr_t grad_size(dlion_dtype t) { return t == DLION_BF16 ? 2 : 4; }
+inline bool dtype_ok(dlion_dtype t) { return t == DLION_F32 || t == DLION_BF16; }
+inline bool mode_ok(dlion_mode m) { return m == DLION_VOTE || m == DLION_AVG; }
+
+#define DLION_TRY(expr)                 \
+    do {                                \
+        const dlion_status st_ = (expr); \
+        if (st_ != DLION_OK)            \
+            return st_;                 \
+    } while (0)
+
+FlatAddr flat_addr(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride, int64_t d,
+                   uint64_t *packed, int64_t packed_stride, uint16_t *counts)
+{
+    FlatAddr a;
+    a.p.x = x;
+    a.p.m = m;
+    a.p.g = g;
+    a.p.m_stride = m_stride;
+    a.p.g_stride = g_stride;
+    a.p.numel = d;
+    a.p.packed = packed;
+    a.p.packed_stride = packed_stride;
+    a.p.counts = counts;
+    a.p.counts_end = d;
+    a.total_tiles = tiles_for(d);
+    return a;
+}
+
+// What a tensor-list call needs from each segment.
+enum SegNeeds { kNeedX = 1, kNeedM = 2, kNeedG = 4 };
+
+dlion_status check_segs(const dlion_seg *segs_host, const dlion_seg *segs_dev, int32_t K, int32_t N,
+                        int needs, dlion_dtype g_dtype, int64_t *total_words, int64_t *total_tiles)
+{
+    if (!segs_host || !segs_dev || K < 1 || N < 1 || N > DLION_MAX_WORKERS)
+        return DLION_EINVAL;
+    if (!aligned_to(segs_dev, 8))
+        return DLION_EALIGN;
+    int64_t words = 0, tiles = 0;
+    for (int32_t k = 0; k < K; ++k) {
+        const dlion_seg &s = segs_host[k];
+        if (s.numel <= 0)
+            return DLION_EINVAL;
+        if (s.word_begin != words || s.tile_begin != tiles)
+            return DLION_EINVAL;   // table was not laid out by dlion_mt_layout
+        if (needs & kNeedX) {
+            if (!s.x)
+                return DLION_EINVAL;
+            if (!aligned_to(s.x, 4))
+                return DLION_EALIGN;
+        }
+        if (needs & kNeedM)
+            DLION_TRY(check_rows(s.m, s.m_stride, s.numel, N, 4));
+        if (needs & kNeedG)
+            DLION_TRY(check_rows(s.g, s.g_stride, s.numel, N, grad_size(g_dtype)));
+        words += words_for(s.numel);
+        tiles += tiles_for(s.numel);
+        if (tiles > kMaxTiles)
+            return DLION_EUNSUPPORTED;
+    }
+    *total_words = words;
+    *total_tiles = tiles;
+    return DLION_OK;
+}
+
+SegAddr seg_addr(const dlion_seg *segs_dev, int32_t K, int64_t total_tiles, uint64_t *packed,
+                 int64_t packed_stride, uint16_t *counts)
+{
+    SegAddr a;
+    a.segs = segs_dev;
+    a.K = K;
+    a.total_tiles = total_tiles;
+    a.packed = packed;
+    a.packed_stride = packed_stride;
+    a.counts = counts;
+    return a;
+}
+
+}  // namespace
+
+extern "C" {
+
+dlion_status dlion_worker_step(float *m, int64_t m_stride, const void *g, int64_t g_stride,
+                               dlion_dtype g_dtype, uint64_t *packed, int64_t packed_stride, int64_t d,
+                               int32_t N, float beta1, float beta2, void *stream)
+{
+    DLION_TRY(check_common(d, N));
+    if (!dtype_ok(g_dtype))
+        return DLION_EINVAL;
+    DLION_TRY(check_rows(m, m_stride, d, N, 4));
+    DLION_TRY(check_rows(g, g_stride, d, N, grad_size(g_dtype)));
+    DLION_TRY(check_rows(packed, packed_stride, words_for(d), N, 8));
+    const Hyper h = make_hyper(N, DLION_VOTE, beta1, beta2, 0.0f, 0.0f);
+    const FlatAddr a = flat_addr(nullptr, m, m_stride, g, g_stride, d, packed, packed_stride, nullptr);
+    return launch_step<false>(a, h, g_dtype, true, false, static_cast<hipStream_t>(stream));
+}
+
+dlion_status dlion_aggregate(const uint64_t *packed, int64_t packed_stride, int64_t d, int32_t N,
+                             uint16_t *counts, void *stream)
+{
+    DLION_TRY(check_common(d, N));
+    DLION_TRY(check_rows(packed, packed_stride, words_for(d), N, 8));
+    if (!counts)
+        return DLION_EINVAL;
+    if (!aligned_to(counts, 2))
+        return DLION_EALIGN;
+    const Hyper h = make_hyper(N, DLION_VOTE, 0.0f, 0.0f, 0.0f, 0.0f);
+    const FlatAddr a = flat_addr(nullptr, nullptr, 0, nullptr, 0, d, const_cast<uint64_t *>(packed),
+                                 packed_stride, counts);
+    return launch_aggregate(a, h, false, true, static_cast<hipStream_t>(stream));
+}
+
+dlion_status dlion_apply(float *x, const uint16_t *counts, int64_t d, int32_t N, dlion_mode mode, float lr,
+                         float lambda, void *stream)
+{
+    DLION_TRY(check_common(d, N));
+    if (!mode_ok(mode) || !x || !counts)
+        return DLION_EINVAL;
+    if (!aligned_to(x, 4) || !aligned_to(counts, 2))
+        return DLION_EALIGN;
+    const Hyper h = make_hyper(N, mode, 0.0f, 0.0f, lr, lambda);
+    const FlatAddr a = flat_addr(x, nullptr, 0, nullptr, 0, d, nullptr, 0, const_cast<uint16_t *>(counts));
+    return launch_apply(a, h, static_cast<hipStream_t>(stream));
+}
+
+dlion_status dlion_aggregate_apply(float *x, const uint64_t *packed, int64_t packed_stride, int64_t d,
+                                   int32_t N, dlion_mode mode, float lr, float lambda,
+                                   uint16_t *counts_or_null, void *stream)
+{
+    DLION_TRY(check_common(d, N));
+    if (!mode_ok(mode) || !x)
+        return DLION_EINVAL;
+    DLION_TRY(check_rows(packed, packed_stride, words_for(d), N, 8));
+    if (!aligned_to(x, 4) || !aligned_to(counts_or_null, 2))
+        return DLION_EALIGN;
+    const Hyper h = make_hyper(N, mode, 0.0f, 0.0f, lr, lambda);
+    const FlatAddr a = flat_addr(x, nullptr, 0, nullptr, 0, d, const_cast<uint64_t *>(packed), packed_stride,
+                                 counts_or_null);
+    return launch_aggregate(a, h, true, counts_or_null != nullptr, static_cast<hipStream_t>(stream));
+}
+
+dlion_status dlion_step(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
+                        dlion_dtype g_dtype, int64_t d, int32_t N, dlion_mode mode, float beta1, float beta2,
+                        float lr, float lambda, uint64_t *packed_or_null, int64_t packed_stride,
+                        uint16_t *counts_or_null, void *stream)
+{
+    DLION_TRY(check_common(d, N));
+    if (!dtype_ok(g_dtype) || !mode_ok(mode) || !x)
+        return DLION_EINVAL;
+    if (!aligned_to(x, 4) || !aligned_to(counts_or_null, 2))
+        return DLION_EALIGN;
+    DLION_TRY(check_rows(m, m_stride, d, N, 4));
+    DLION_TRY(check_rows(g, g_stride, d, N, grad_size(g_dtype)));
+    if (packed_or_null)
+        DLION_TRY(check_rows(packed_or_null, packed_stride, words_for(d), N, 8));
+    const Hyper h = make_hyper(N, mode, beta1, beta2, lr, lambda);
+    const FlatAddr a = flat_addr(x, m, m_stride, g, g_stride, d, packed_or_null, packed_stride, counts_or_null);
+    return launch_step<true>(a, h, g_dtype, packed_or_null != nullptr, counts_or_null != nullptr,
+                             static_cast<hipStream_t>(stream));
+}
+
+// ----------------------------------------------------------------------- tensor lists
+dlion_status dlion_mt_layout(dlion_seg *segs_host, int32_t K, int64_t *total_words, int64_t *total_tiles)
+{
+    if (!segs_host || K < 1)
+        return DLION_EINVAL;
+    int64_t words = 0, tiles = 0;
+    for (int32_t k = 0; k < K; ++k) {
+        if (segs_host[k].numel <= 0)
+            return DLION_EINVAL;
+        segs_host[k].word_begin = words;
+        segs_host[k].tile_begin = tiles;
+        words += words_for(segs_host[k].numel);
+        tiles += tiles_for(segs_host[k].numel);
+    }
+    if (tiles > kMaxTiles)
+        return DLION_EUNSUPPORTED;
+    if (total_words)
+        *total_words = words;
+    if (total_tiles)
+        *total_tiles = tiles;
+    return DLION_OK;
+}
+
+dlion_status dlion_worker_step_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev, int32_t K,
+                                  dlion_dtype g_dtype, uint64_t *packed, int64_t packed_stride, int32_t N,
+                                  float beta1, float beta2, void *stream)
+{
+    if (!dtype_ok(g_dtype))
+        return DLION_EINVAL;
+    int64_t words, tiles;
+    DLION_TRY(check_segs(segs_host, segs_dev, K, N, kNeedM | kNeedG, g_dtype, &words, &tiles));
+    DLION_TRY(check_rows(packed, packed_stride, words, N, 8));
+    const Hyper h = make_hyper(N, DLION_VOTE, beta1, beta2, 0.0f, 0.0f);
+    const SegAddr a = seg_addr(segs_dev, K, tiles, packed, packed_stride, nullptr);
+    return launch_step<false>(a, h, g_dtype, true, false, static_cast<hipStream_t>(stream));
+}
+
+dlion_status dlion_aggregate_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev, int32_t K,
+                                const uint64_t *packed, int64_t packed_stride, int32_t N, uint16_t *counts,
+                                void *stream)
+{
+    int64_t words, tiles;
+    DLION_TRY(check_segs(segs_host, segs_dev, K, N, 0, DLION_F32, &words, &tiles));
+    DLION_TRY(check_rows(packed, packed_stride, words, N, 8));
+    if (!counts)
+        return DLION_EINVAL;
+    if (!aligned_to(counts, 2))
+        return DLION_EALIGN;
+    const Hyper h = make_hyper(N, DLION_VOTE, 0.0f, 0.0f, 0.0f, 0.0f);
+    const SegAddr a = seg_addr(segs_dev, K, tiles, const_cast<uint64_t *>(packed), packed_stride, counts);
+    return launch_aggregate(a, h, false, true, static_cast<hipStream_t>(stream));
+}
+
+dlion_status dlion_apply_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev, int32_t K,
+                            const uint16_t *counts, int32_t N, dlion_mode mode, float lr, float lambda,
+                            void *stream)
+{
+    if (!mode_ok(mode) || !counts)
+        return DLION_EINVAL;
+    if (!aligned_to(counts, 2))
+        return DLION_EALIGN;
+    int64_t words, tiles;
+    DLION_TRY(check_segs(segs_host, segs_dev, K, N, kNeedX, DLION_F32, &words, &tiles));
+    const Hyper h = make_hyper(N, mode, 0.0f, 0.0f, lr, lambda);
+    const SegAddr a = seg_addr(segs_dev, K, tiles, nullptr, 0, const_cast<uint16_t *>(counts));
+    return launch_apply(a, h, static_cast<hipStream_t>(stream));
+}
+
+dlion_status dlion_aggregate_apply_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev, int32_t K,
+                                      const uint64_t *packed, int64_t packed_stride, int32_t N,
+                                      dlion_mode mode, float lr, float lambda, uint16_t *counts_or_null,
+                                      void *stream)
+{
+    if (!mode_ok(mode))
+        return DLION_EINVAL;
+    if (!aligned_to(counts_or_null, 2))
+        return DLION_EALIGN;
+    int64_t words, tiles;
+    DLION_TRY(check_segs(segs_host, segs_dev, K, N, kNeedX, DLION_F32, &words, &tiles));
+    DLION_TRY(check_rows(packed, packed_stride, words, N, 8));
+    const Hyper h = make_hyper(N, mode, 0.0f, 0.0f, lr, lambda);
+    const SegAddr a = seg_addr(segs_dev, K, tiles, const_cast<uint64_t *>(packed), packed_stride, counts_or_null);
+    return launch_aggregate(a, h, true, counts_or_null != nullptr, static_cast<hipStream_t>(stream));
+}
+
+dlion_status dlion_step_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev, int32_t K,
+                           dlion_dtype g_dtype, int32_t N, dlion_mode mode, float beta1, float beta2, float lr,
+                           float lambda, uint64_t *packed_or_null, int64_t packed_stride,
+                           uint16_t *counts_or_null, void *stream)
+{
+    if (!dtype_ok(g_dtype) || !mode_ok(mode))
+        return DLION_EINVAL;
+    if (!aligned_to(counts_or_null, 2))
+        return DLION_EALIGN;
+    int64_t words, tiles;
+    DLION_TRY(check_segs(segs_host, segs_dev, K, N, kNeedX | kNeedM | kNeedG, g_dtype, &words, &tiles));
+    if (packed_or_null)
+        DLION_TRY(check_rows(packed_or_null, packed_stride, words, N, 8));
+    const Hyper h = make_hyper(N, mode, beta1, beta2, lr, lambda);
+    const SegAddr a = seg_addr(segs_dev, K, tiles, packed_or_null, packed_stride, counts_or_null);
+    return launch_step<true>(a, h, g_dtype, packed_or_null != nullptr, counts_or_null != nullptr,
+                             static_cast<hipStream_t>(stream));
+}
+
+const char *dlion_status_str(dlion_status s)
+{
+    switch (s) {
+    case DLION_OK: return "ok";
+    case DLION_EINVAL: return "invalid argument (size, stride, count, enum or null pointer)";
+    case DLION_EALIGN: return "pointer not aligned to its element type";
+    case DLION_ELAUNCH: return "HIP runtime refused the kernel launch";
+    case DLION_EUNSUPPORTED: return "request outside what this build supports";
+    }
+    return "unknown status";
+}
+
+int dlion_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,465 @@
+// Device code of the Distributed Lion sweep for gfx950 (CDNA4, 64-wide wavefronts).
+//
+// Work decomposition: the coordinate range of a tensor is cut into TILES of 256
+// coordinates (= 4 packed uint64 words).  One wavefront owns one tile and walks
+// over all N workers for it, so the vote count of a coordinate never leaves
+// the lane that owns the coordinate and no inter-wave communication, atomics
+// or barriers are needed anywhere on the worker/fused path.
+//
+// Two code paths per tile:
+//   * vector path (full tile, 16-byte aligned rows): lane l owns coordinates
+//     4l..4l+3 and moves them with one 128-bit access per stream.  Its four
+//     sign bits form a nibble; the nibbles of the 16 lanes of a DPP row are
+//     OR-combined into one canonical packed word per row.
+//   * guarded path (ragged last tile, or rows that are not 16-byte aligned):
+//     lane l owns coordinates 64k+l, k=0..3, moved with dword accesses; a
+//     64-lane ballot of the sign predicate is already a canonical packed word.
+//
+// All fp32 arithmetic goes through __fmul_rn/__fadd_rn/__fsub_rn so that no
+// multiply-add is ever fused (Section 3.2's expressions, each operation rounded
+// on its own); the sign is taken as !(c < 0), i.e. 0 votes +1.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/dlion.h"
+
+namespace dlion {
+
+constexpr int kLanes = 64;
+constexpr int kVec = 4;                 // coordinates per lane per tile on the vector path
+constexpr int kTile = kLanes * kVec;    // 256 coordinates
+constexpr int kWordsPerTile = kTile / 64;
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlock = kLanes * kWavesPerBlock;
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
+
+struct Hyper {
+    float beta1, omb1, beta2, omb2;  // omb = 1.0f - beta, formed on the host in fp32
+    float lr, lambda;
+    float inv_n;      // 1/N when N is a power of two (then S*inv_n == S/N exactly), else 0
+    int32_t N;
+    int32_t mode;     // dlion_mode
+};
+
+// One flat problem as a tile sees it.
+struct Problem {
+    float *x;
+    float *m;
+    const void *g;
+    int64_t m_stride, g_stride;
+    int64_t numel;
+    uint64_t *packed;       // worker 0, first word of this tensor (may be null)
+    int64_t packed_stride;
+    uint16_t *counts;       // first count of this tensor (may be null)
+    int64_t counts_end;     // counts[0..counts_end) may be written: numel (flat buffer) or
+                            // numel rounded up to a whole word (tensor list)
+};
+
+// ---------------------------------------------------------------- addressing
+// Flat buffer: the problem travels in the kernel arguments.
+struct FlatAddr {
+    Problem p;
+    int64_t total_tiles;
+    __device__ int64_t resolve(int64_t tile, Problem &out) const
+    {
+        out = p;
+        return tile;
+    }
+};
+
+// Tensor list: a device table of segments ordered by tile_begin; the owner of a
+// tile is found by bisection (all operands are wave-uniform, so these are
+// scalar loads).
+struct SegAddr {
+    const dlion_seg *segs;
+    int32_t K;
+    int64_t total_tiles;
+    uint64_t *packed;
+    int64_t packed_stride;
+    uint16_t *counts;
+    __device__ int64_t resolve(int64_t tile, Problem &out) const
+    {
+        int32_t lo = 0, hi = K - 1;
+        while (lo < hi) {
+            int32_t mid = (lo + hi + 1) >> 1;
+            if (segs[mid].tile_begin <= tile)
+                lo = mid;
+            else
+                hi = mid - 1;
+        }
+        const dlion_seg s = segs[lo];
+        out.x = s.x;
+        out.m = s.m;
+        out.g = s.g;
+        out.m_stride = s.m_stride;
+        out.g_stride = s.g_stride;
+        out.numel = s.numel;
+        out.packed = packed ? packed + s.word_begin : nullptr;
+        out.packed_stride = packed_stride;
+        out.counts = counts ? counts + 64 * s.word_begin : nullptr;
+        out.counts_end = ((s.numel + 63) >> 6) << 6;
+        return tile - s.tile_begin;
+    }
+};
+
+__device__ __forceinline__ int64_t wave_tile_index()
+{
+    // blockIdx and the wave number are uniform across the wavefront; say so, so
+    // that everything derived from the tile index stays in scalar registers.
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    return (int64_t)blockIdx.x * kWavesPerBlock + wave;
+}
+
+__device__ __forceinline__ bool is_aligned(const void *p, uint64_t a)
+{
+    return (reinterpret_cast<uint64_t>(p) & (a - 1)) == 0;
+}
+
+// ---------------------------------------------------------------- gradients
+template <typename GT> struct Grad;
+template <> struct Grad<float> {
+    static constexpr int kVecBytes = 16;
+    static __device__ __forceinline__ f32x4 load4(const void *g, int64_t idx)
+    {
+        return __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(static_cast<const float *>(g) + idx));
+    }
+    static __device__ __forceinline__ float load1(const void *g, int64_t idx)
+    {
+        return __builtin_nontemporal_load(static_cast<const float *>(g) + idx);
+    }
+};
+template <> struct Grad<uint16_t> {   // bf16 bit patterns; widening to fp32 is exact
+    static constexpr int kVecBytes = 8;
+    static __device__ __forceinline__ f32x4 load4(const void *g, int64_t idx)
+    {
+        const u32x2 raw = __builtin_nontemporal_load(
+            reinterpret_cast<const u32x2 *>(static_cast<const uint16_t *>(g) + idx));
+        f32x4 r;
+        r.x = __uint_as_float(raw.x << 16);
+        r.y = __uint_as_float(raw.x & 0xFFFF0000u);
+        r.z = __uint_as_float(raw.y << 16);
+        r.w = __uint_as_float(raw.y & 0xFFFF0000u);
+        return r;
+    }
+    static __device__ __forceinline__ float load1(const void *g, int64_t idx)
+    {
+        const uint16_t raw = __builtin_nontemporal_load(static_cast<const uint16_t *>(g) + idx);
+        return __uint_as_float(static_cast<uint32_t>(raw) << 16);
+    }
+};
+
+// ---------------------------------------------------------------- arithmetic
+// Worker update for one coordinate (Section 3.2, first display).  Returns the
+// vote (true = +1) and replaces m by the new momentum.
+__device__ __forceinline__ bool lion_worker(float &m, float g, const Hyper &h)
+{
+    const float c = __fadd_rn(__fmul_rn(h.beta1, m), __fmul_rn(h.omb1, g));
+    m = __fadd_rn(__fmul_rn(h.beta2, m), __fmul_rn(h.omb2, g));
+    return !(c < 0.0f);
+}
+
+// Aggregation of p votes for +1 out of N (Section 3.2, second display).
+__device__ __forceinline__ float aggregate_votes(uint32_t p, const Hyper &h)
+{
+    const int32_t S = 2 * static_cast<int32_t>(p) - h.N;
+    if (h.mode == DLION_AVG) {
+        if (h.inv_n != 0.0f)
+            return __fmul_rn(static_cast<float>(S), h.inv_n);   // exact: N is a power of two
+        return static_cast<float>(S) / static_cast<float>(h.N);
+    }
+    return static_cast<float>((S > 0) - (S < 0));
+}
+
+// Weight update (Section 3.2, third display).
+__device__ __forceinline__ float lion_apply(float x, float Delta, const Hyper &h)
+{
+    return __fsub_rn(x, __fmul_rn(h.lr, __fadd_rn(Delta, __fmul_rn(h.lambda, x))));
+}
+
+// ---------------------------------------------------------------- bit packing
+// DPP lane exchange within a row of 16 lanes.
+template <int kCtrl> __device__ __forceinline__ uint32_t dpp(uint32_t v)
+{
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), kCtrl, 0xF, 0xF, true));
+}
+
+// Each lane holds the 4 sign bits of coordinates 4l..4l+3 of a tile.  Lanes
+// 16w..16w+15 together hold word w of the tile; OR them together so that the
+// first lane of each row ends up with the canonical 64-bit word.
+__device__ __forceinline__ uint64_t row_gather_nibbles(uint32_t nibble, int lane)
+{
+    uint32_t v = nibble << ((lane & 7) * 4);          // position inside this half's dword
+    v |= dpp<0xB1>(v);                                // quad_perm [1,0,3,2]: lane ^ 1
+    v |= dpp<0x4E>(v);                                // quad_perm [2,3,0,1]: lane ^ 2
+    v |= dpp<0x141>(v);                               // row_half_mirror: other quad of the half
+    const uint32_t other = dpp<0x128>(v);             // row_ror 8: the other half of the row
+    // lanes 0..7 of a row hold the low dword, lanes 8..15 the high dword
+    return (lane & 8) ? ((static_cast<uint64_t>(v) << 32) | other)
+                      : ((static_cast<uint64_t>(other) << 32) | v);
+}
+
+// ---------------------------------------------------------------- fused / worker tile
+// kApply : read x, aggregate, write x (fused step); else worker step only.
+// kPacked: write packed words.   kCounts: write counts.
+template <typename GT, int kUnroll, bool kApply, bool kPacked, bool kCounts>
+__device__ __forceinline__ void step_tile_vector(const Problem &p, int64_t t, int lane, const Hyper &h)
+{
+    const int64_t j0 = t * kTile + lane * kVec;
+    f32x4 xv;
+    if (kApply)
+        xv = *reinterpret_cast<const f32x4 *>(p.x + j0);
+    uint32_t cnt0 = 0, cnt1 = 0, cnt2 = 0, cnt3 = 0;
+    const int N = h.N;
+
+    auto one_worker = [&](int i, f32x4 mv, f32x4 gv) {
+        float m0 = mv.x, m1 = mv.y, m2 = mv.z, m3 = mv.w;
+        const bool b0 = lion_worker(m0, gv.x, h);
+        const bool b1 = lion_worker(m1, gv.y, h);
+        const bool b2 = lion_worker(m2, gv.z, h);
+        const bool b3 = lion_worker(m3, gv.w, h);
+        mv.x = m0;
+        mv.y = m1;
+        mv.z = m2;
+        mv.w = m3;
+        __builtin_nontemporal_store(mv, reinterpret_cast<f32x4 *>(p.m + (int64_t)i * p.m_stride + j0));
+        cnt0 += b0;
+        cnt1 += b1;
+        cnt2 += b2;
+        cnt3 += b3;
+        if (kPacked) {
+            const uint32_t nib = (b0 ? 1u : 0u) | (b1 ? 2u : 0u) | (b2 ? 4u : 0u) | (b3 ? 8u : 0u);
+            const uint64_t word = row_gather_nibbles(nib, lane);
+            if ((lane & 15) == 0)
+                p.packed[(int64_t)i * p.packed_stride + t * kWordsPerTile + (lane >> 4)] = word;
+        }
+    };
+
+    int i = 0;
+    for (; i + kUnroll <= N; i += kUnroll) {
+        f32x4 mv[kUnroll], gv[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            mv[u] = __builtin_nontemporal_load(
+                reinterpret_cast<const f32x4 *>(p.m + (int64_t)(i + u) * p.m_stride + j0));
+            gv[u] = Grad<GT>::load4(p.g, (int64_t)(i + u) * p.g_stride + j0);
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+            one_worker(i + u, mv[u], gv[u]);
+    }
+    for (; i < N; ++i) {
+        const f32x4 mv = __builtin_nontemporal_load(
+            reinterpret_cast<const f32x4 *>(p.m + (int64_t)i * p.m_stride + j0));
+        const f32x4 gv = Grad<GT>::load4(p.g, (int64_t)i * p.g_stride + j0);
+        one_worker(i, mv, gv);
+    }
+
+    if (kApply) {
+        xv.x = lion_apply(xv.x, aggregate_votes(cnt0, h), h);
+        xv.y = lion_apply(xv.y, aggregate_votes(cnt1, h), h);
+        xv.z = lion_apply(xv.z, aggregate_votes(cnt2, h), h);
+        xv.w = lion_apply(xv.w, aggregate_votes(cnt3, h), h);
+        *reinterpret_cast<f32x4 *>(p.x + j0) = xv;
+    }
+    if (kCounts) {
+        u16x4 c;
+        c.x = static_cast<uint16_t>(cnt0);
+        c.y = static_cast<uint16_t>(cnt1);
+        c.z = static_cast<uint16_t>(cnt2);
+        c.w = static_cast<uint16_t>(cnt3);
+        *reinterpret_cast<u16x4 *>(p.counts + j0) = c;
+    }
+}
+
+// Guarded path: lane l owns coordinates 64k+l of the tile; every access checks
+// j < numel; a 64-lane ballot is already a canonical packed word.
+template <typename GT, bool kApply, bool kPacked, bool kCounts>
+__device__ __forceinline__ void step_tile_guarded(const Problem &p, int64_t t, int lane, const Hyper &h)
+{
+    const int64_t W = (p.numel + 63) >> 6;
+#pragma unroll 1
+    for (int k = 0; k < kWordsPerTile; ++k) {
+        const int64_t w = t * kWordsPerTile + k;
+        if (w >= W)
+            break;                                   // uniform: whole wave leaves together
+        const int64_t j = w * 64 + lane;
+        const bool valid = j < p.numel;
+        uint32_t cnt = 0;
+        for (int i = 0; i < h.N; ++i) {
+            bool plus = false;
+            if (valid) {
+                float *mp = p.m + (int64_t)i * p.m_stride + j;
+                float mv = *mp;
+                const float gv = Grad<GT>::load1(p.g, (int64_t)i * p.g_stride + j);
+                plus = lion_worker(mv, gv, h);
+                *mp = mv;
+            }
+            cnt += plus;
+            if (kPacked) {
+                const uint64_t word = __ballot(plus);   // invalid lanes contribute 0: tail bits zero
+                if (lane == 0)
+                    p.packed[(int64_t)i * p.packed_stride + w] = word;
+            }
+        }
+        if (kApply && valid)
+            p.x[j] = lion_apply(p.x[j], aggregate_votes(cnt, h), h);
+        if (kCounts && j < p.counts_end)
+            p.counts[j] = static_cast<uint16_t>(cnt);   // 0 past numel (tensor-list padding)
+    }
+}
+
+template <typename GT, int kUnroll, bool kApply, bool kPacked, bool kCounts, class Addr>
+__global__ __launch_bounds__(kBlock) void step_kernel(Addr addr, Hyper h)
+{
+    const int64_t tile = wave_tile_index();
+    if (tile >= addr.total_tiles)
+        return;
+    const int lane = threadIdx.x & 63;
+    Problem p;
+    const int64_t t = addr.resolve(tile, p);
+    bool vec = (t + 1) * kTile <= p.numel && is_aligned(p.m, 16) && (p.m_stride & 3) == 0 &&
+               is_aligned(p.g, Grad<GT>::kVecBytes) && (p.g_stride & 3) == 0;
+    if (kApply)
+        vec = vec && is_aligned(p.x, 16);
+    if (kCounts)
+        vec = vec && is_aligned(p.counts, 8);
+    if (vec)
+        step_tile_vector<GT, kUnroll, kApply, kPacked, kCounts>(p, t, lane, h);
+    else
+        step_tile_guarded<GT, kApply, kPacked, kCounts>(p, t, lane, h);
+}
+
+// ---------------------------------------------------------------- server side from packed words
+// Vector path: lane l owns coordinates 4l..4l+3 = nibble (l & 15) of word (l >> 4) of the
+// tile.  Votes are accumulated four at a time in the bytes of one register (a nibble is
+// spread to one bit per byte by a multiply), flushed to 32-bit counters every 255 workers.
+template <bool kApply, bool kCounts>
+__device__ __forceinline__ void agg_tile_vector(const Problem &p, int64_t t, int lane, const Hyper &h)
+{
+    const uint32_t *half = reinterpret_cast<const uint32_t *>(p.packed + t * kWordsPerTile + (lane >> 4)) +
+                           ((lane >> 3) & 1);
+    const int shift = (lane & 7) * 4;
+    const int64_t stride32 = p.packed_stride * 2;
+    uint32_t cnt0 = 0, cnt1 = 0, cnt2 = 0, cnt3 = 0;
+    const int N = h.N;
+    for (int base = 0; base < N; base += 255) {
+        const int end = (N - base < 255) ? N : base + 255;
+        uint32_t acc = 0;
+        int i = base;
+        for (; i + 8 <= end; i += 8) {
+            uint32_t v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                v[u] = half[(int64_t)(i + u) * stride32];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                acc += (((v[u] >> shift) & 0xFu) * 0x00204081u) & 0x01010101u;
+        }
+        for (; i < end; ++i)
+            acc += (((half[(int64_t)i * stride32] >> shift) & 0xFu) * 0x00204081u) & 0x01010101u;
+        cnt0 += acc & 0xFFu;
+        cnt1 += (acc >> 8) & 0xFFu;
+        cnt2 += (acc >> 16) & 0xFFu;
+        cnt3 += acc >> 24;
+    }
+    const int64_t j0 = t * kTile + lane * kVec;
+    if (kApply) {
+        f32x4 xv = *reinterpret_cast<const f32x4 *>(p.x + j0);
+        xv.x = lion_apply(xv.x, aggregate_votes(cnt0, h), h);
+        xv.y = lion_apply(xv.y, aggregate_votes(cnt1, h), h);
+        xv.z = lion_apply(xv.z, aggregate_votes(cnt2, h), h);
+        xv.w = lion_apply(xv.w, aggregate_votes(cnt3, h), h);
+        *reinterpret_cast<f32x4 *>(p.x + j0) = xv;
+    }
+    if (kCounts) {
+        u16x4 c;
+        c.x = static_cast<uint16_t>(cnt0);
+        c.y = static_cast<uint16_t>(cnt1);
+        c.z = static_cast<uint16_t>(cnt2);
+        c.w = static_cast<uint16_t>(cnt3);
+        *reinterpret_cast<u16x4 *>(p.counts + j0) = c;
+    }
+}
+
+// Guarded path: lane l owns bit l of word 4t+k.
+template <bool kApply, bool kCounts>
+__device__ __forceinline__ void agg_tile_guarded(const Problem &p, int64_t t, int lane, const Hyper &h)
+{
+    const int64_t W = (p.numel + 63) >> 6;
+#pragma unroll 1
+    for (int k = 0; k < kWordsPerTile; ++k) {
+        const int64_t w = t * kWordsPerTile + k;
+        if (w >= W)
+            break;
+        const int64_t j = w * 64 + lane;
+        const bool valid = j < p.numel;
+        uint32_t cnt = 0;
+        for (int i = 0; i < h.N; ++i) {
+            const uint64_t word = p.packed[(int64_t)i * p.packed_stride + w];
+            cnt += static_cast<uint32_t>((word >> lane) & 1u);
+        }
+        if (!valid)
+            cnt = 0;                      // tail bits are zero by contract; do not rely on it
+        if (kApply && valid)
+            p.x[j] = lion_apply(p.x[j], aggregate_votes(cnt, h), h);
+        if (kCounts && j < p.counts_end)
+            p.counts[j] = static_cast<uint16_t>(cnt);
+    }
+}
+
+template <bool kApply, bool kCounts, class Addr>
+__global__ __launch_bounds__(kBlock) void aggregate_kernel(Addr addr, Hyper h)
+{
+    const int64_t tile = wave_tile_index();
+    if (tile >= addr.total_tiles)
+        return;
+    const int lane = threadIdx.x & 63;
+    Problem p;
+    const int64_t t = addr.resolve(tile, p);
+    bool vec = (t + 1) * kTile <= p.numel;
+    if (kApply)
+        vec = vec && is_aligned(p.x, 16);
+    if (kCounts)
+        vec = vec && is_aligned(p.counts, 8);
+    if (vec)
+        agg_tile_vector<kApply, kCounts>(p, t, lane, h);
+    else
+        agg_tile_guarded<kApply, kCounts>(p, t, lane, h);
+}
+
+// ---------------------------------------------------------------- apply from counts
+template <class Addr>
+__global__ __launch_bounds__(kBlock) void apply_kernel(Addr addr, Hyper h)
+{
+    const int64_t tile = wave_tile_index();
+    if (tile >= addr.total_tiles)
+        return;
+    const int lane = threadIdx.x & 63;
+    Problem p;
+    const int64_t t = addr.resolve(tile, p);
+    const bool vec = (t + 1) * kTile <= p.numel && is_aligned(p.x, 16) && is_aligned(p.counts, 8);
+    if (vec) {
+        const int64_t j0 = t * kTile + lane * kVec;
+        const u16x4 c = *reinterpret_cast<const u16x4 *>(p.counts + j0);
+        f32x4 xv = *reinterpret_cast<const f32x4 *>(p.x + j0);
+        xv.x = lion_apply(xv.x, aggregate_votes(c.x, h), h);
+        xv.y = lion_apply(xv.y, aggregate_votes(c.y, h), h);
+        xv.z = lion_apply(xv.z, aggregate_votes(c.z, h), h);
+        xv.w = lion_apply(xv.w, aggregate_votes(c.w, h), h);
+        *reinterpret_cast<f32x4 *>(p.x + j0) = xv;
+    } else {
+#pragma unroll 1
+        for (int k = 0; k < kWordsPerTile; ++k) {
+            const int64_t j = (t * kWordsPerTile + k) * 64 + lane;
+            if (j < p.numel)
+                p.x[j] = lion_apply(p.x[j], aggregate_votes(p.counts[j], h), h);
+        }
+    }
+}
+
+}  // namespace dlion

@@ -1,0 +1,124 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, rejects bad arguments before touching the device, and lays out tensor lists."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2404_00438_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return binding.load_library()
+
+
+def declared_symbols():
+    with open(os.path.join(ROOT, "include", "dlion.h")) as f:
+        text = f.read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dlion_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings(lib):
+    assert lib.dlion_version() >= 100
+    seen = {lib.dlion_status_str(s) for s in range(5)}
+    assert len(seen) == 5 and all(seen)
+    assert lib.dlion_status_str(99) == b"unknown status"
+
+
+A = 0x7F0000000000   # a 256-byte aligned fake device address; never dereferenced by validation
+
+
+def test_bad_arguments_are_rejected_on_the_host(lib):
+    EINVAL, EALIGN = 1, 2
+    ws = lib.dlion_worker_step
+    assert ws(A, 128, A, 128, 0, A, 2, 0, 4, 0.9, 0.99, None) == EINVAL          # d = 0
+    assert ws(A, 128, A, 128, 0, A, 2, -5, 4, 0.9, 0.99, None) == EINVAL         # d < 0
+    assert ws(A, 128, A, 128, 0, A, 2, 128, 0, 0.9, 0.99, None) == EINVAL        # N = 0
+    assert ws(A, 128, A, 128, 0, A, 2, 128, 65536, 0.9, 0.99, None) == EINVAL    # N too large
+    assert ws(None, 128, A, 128, 0, A, 2, 128, 4, 0.9, 0.99, None) == EINVAL     # null m
+    assert ws(A, 128, None, 128, 0, A, 2, 128, 4, 0.9, 0.99, None) == EINVAL     # null g
+    assert ws(A, 128, A, 128, 0, None, 2, 128, 4, 0.9, 0.99, None) == EINVAL     # null packed
+    assert ws(A, 127, A, 128, 0, A, 2, 128, 4, 0.9, 0.99, None) == EINVAL        # m stride < d
+    assert ws(A, 128, A, 100, 0, A, 2, 128, 4, 0.9, 0.99, None) == EINVAL        # g stride < d
+    assert ws(A, 128, A, 128, 0, A, 1, 128, 4, 0.9, 0.99, None) == EINVAL        # packed stride < W
+    assert ws(A, 128, A, 128, 7, A, 2, 128, 4, 0.9, 0.99, None) == EINVAL        # dtype enum
+    assert ws(A + 2, 128, A, 128, 0, A, 2, 128, 4, 0.9, 0.99, None) == EALIGN    # m not 4-aligned
+    assert ws(A, 128, A + 1, 128, 1, A, 2, 128, 4, 0.9, 0.99, None) == EALIGN    # bf16 g not 2-aligned
+    assert ws(A, 128, A, 128, 0, A + 4, 2, 128, 4, 0.9, 0.99, None) == EALIGN    # packed not 8-aligned
+
+    ag = lib.dlion_aggregate
+    assert ag(A, 2, 128, 4, None, None) == EINVAL
+    assert ag(A, 2, 128, 4, A + 1, None) == EALIGN
+    assert ag(None, 2, 128, 4, A, None) == EINVAL
+    assert ag(A, 1, 128, 4, A, None) == EINVAL
+
+    ap = lib.dlion_apply
+    assert ap(None, A, 128, 4, 0, 1e-4, 0.1, None) == EINVAL
+    assert ap(A, None, 128, 4, 0, 1e-4, 0.1, None) == EINVAL
+    assert ap(A, A, 128, 4, 2, 1e-4, 0.1, None) == EINVAL                         # mode enum
+    assert ap(A + 1, A, 128, 4, 0, 1e-4, 0.1, None) == EALIGN
+
+    aa = lib.dlion_aggregate_apply
+    assert aa(None, A, 2, 128, 4, 0, 1e-4, 0.1, None, None) == EINVAL
+    assert aa(A, A, 2, 128, 4, 3, 1e-4, 0.1, None, None) == EINVAL
+    assert aa(A, A, 1, 128, 4, 0, 1e-4, 0.1, None, None) == EINVAL
+
+    st = lib.dlion_step
+    assert st(None, A, 128, A, 128, 0, 128, 4, 0, 0.9, 0.99, 1e-4, 0.1, None, 0, None, None) == EINVAL
+    assert st(A, A, 128, A, 128, 0, 128, 4, 5, 0.9, 0.99, 1e-4, 0.1, None, 0, None, None) == EINVAL
+    assert st(A, A, 128, A, 128, 0, 128, 4, 0, 0.9, 0.99, 1e-4, 0.1, A, 1, None, None) == EINVAL
+    assert st(A, A, 128, A, 128, 0, 128, 4, 0, 0.9, 0.99, 1e-4, 0.1, None, 0, A + 1, None) == EALIGN
+    assert st(A, A, 64, A, 128, 0, 128, 4, 0, 0.9, 0.99, 1e-4, 0.1, None, 0, None, None) == EINVAL
+
+
+def test_tensor_list_layout_and_validation(lib):
+    EINVAL = 1
+    K = 5
+    numels = [64, 1000, 5, 256, 257]
+    arr = (binding.Seg * K)()
+    for k, n in enumerate(numels):
+        arr[k].x = A
+        arr[k].m = A
+        arr[k].g = A
+        arr[k].m_stride = n
+        arr[k].g_stride = n
+        arr[k].numel = n
+    tw, tt = ctypes.c_int64(), ctypes.c_int64()
+    assert lib.dlion_mt_layout(arr, K, ctypes.byref(tw), ctypes.byref(tt)) == 0
+    words = [(n + 63) // 64 for n in numels]
+    tiles = [(n + 255) // 256 for n in numels]
+    assert tw.value == sum(words) and tt.value == sum(tiles)
+    assert [arr[k].word_begin for k in range(K)] == [sum(words[:k]) for k in range(K)]
+    assert [arr[k].tile_begin for k in range(K)] == [sum(tiles[:k]) for k in range(K)]
+    # a table that was not laid out, or tampered with, is refused before any launch
+    arr[3].word_begin += 1
+    assert lib.dlion_step_mt(arr, A, K, 0, 4, 0, 0.9, 0.99, 1e-4, 0.1, None, 0, None, None) == EINVAL
+    arr[3].word_begin -= 1
+    arr[2].numel = 0
+    assert lib.dlion_mt_layout(arr, K, None, None) == EINVAL
+    assert lib.dlion_step_mt(arr, A, K, 0, 4, 0, 0.9, 0.99, 1e-4, 0.1, None, 0, None, None) == EINVAL
+    arr[2].numel = 5
+    assert lib.dlion_step_mt(arr, None, K, 0, 4, 0, 0.9, 0.99, 1e-4, 0.1, None, 0, None, None) == EINVAL
+    assert lib.dlion_step_mt(None, A, K, 0, 4, 0, 0.9, 0.99, 1e-4, 0.1, None, 0, None, None) == EINVAL
+    assert lib.dlion_step_mt(arr, A, 0, 0, 4, 0, 0.9, 0.99, 1e-4, 0.1, None, 0, None, None) == EINVAL
+    arr[1].m = None
+    assert lib.dlion_step_mt(arr, A, K, 0, 4, 0, 0.9, 0.99, 1e-4, 0.1, None, 0, None, None) == EINVAL
+    assert lib.dlion_aggregate_mt(arr, A, K, A, 2, 4, A, None) == EINVAL      # packed stride < total words
+    assert lib.dlion_mt_layout(None, K, None, None) == EINVAL
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    with pytest.raises(FileNotFoundError):
+        binding.load_library(os.path.join(tmp_path, "libdlion.so"))

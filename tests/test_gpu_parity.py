@@ -1,0 +1,292 @@
+"""GPU parity: the HIP path against the CPU oracle, element by element, through the C ABI.
+
+Packed words and vote counts must be bit-exact; fp32 momentum and weights must
+agree within max relative error 1e-6 (they are expected to be bit-identical,
+which is reported but the stated bar is what is asserted).
+"""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2404_00438_amd as dl
+from paper_2404_00438_amd import workloads as wl
+from helpers import assert_f32_equal, strided_rows, to_np
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+HYP = dict(beta1=0.9, beta2=0.99, lr=3e-4, lam=0.1)
+
+
+def announce(*what):
+    print("[case]", *what, flush=True)
+
+
+def draw_state(rng, N, d, g_dtype, m_stride=None, g_stride=None, scale=1e-3):
+    """Random x, m, g on the device, rows optionally padded to a given stride."""
+    m_stride = d if m_stride is None else m_stride
+    g_stride = d if g_stride is None else g_stride
+    x = torch.from_numpy(rng.normal(0, 0.02, d).astype(np.float32)).to(DEV)
+    m = strided_rows(N, d, m_stride, torch.float32, DEV)
+    m.copy_(torch.from_numpy(rng.normal(0, scale, (N, d)).astype(np.float32)))
+    g = strided_rows(N, d, g_stride, g_dtype, DEV)
+    g.copy_(torch.from_numpy(rng.standard_t(3, (N, d)).astype(np.float32) * scale).to(g_dtype))
+    return x, m, g
+
+
+def oracle_step(x, m, g, mode, hyp):
+    xn, mn, gn = to_np(x), to_np(m), to_np(g)
+    packed, counts = oracle.step(xn, mn, gn, mode, hyp["beta1"], hyp["beta2"], hyp["lr"], hyp["lam"])
+    return xn, mn, packed, counts
+
+
+def compare_all(tag, x, m, packed, counts, xn, mn, pn, cn):
+    if packed is not None:
+        assert np.array_equal(to_np(packed), pn), f"{tag}: packed words differ"
+    if counts is not None:
+        assert np.array_equal(to_np(counts)[: cn.shape[0]], cn), f"{tag}: counts differ"
+    assert_f32_equal(to_np(m), mn, f"{tag}: m")
+    assert_f32_equal(to_np(x), xn, f"{tag}: x")
+
+
+SIZES = [1, 63, 64, 65, 255, 256, 257, 1000, 4096 + 3, 70_001]
+WORKERS = [1, 2, 3, 4, 5, 7, 8, 9, 16, 17, 33]
+
+
+@pytest.mark.parametrize("g_dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("mode", [dl.VOTE, dl.AVG], ids=["vote", "avg"])
+def test_fused_step_matches_oracle(g_dtype, mode):
+    rng = np.random.default_rng(1234)
+    for d, N in itertools.product(SIZES, WORKERS):
+        if d > 5000 and N not in (4, 8, 17):
+            continue
+        for aligned in (True, False):
+            # aligned rows: stride rounded up to 64 elements; unaligned: odd stride (dword path)
+            stride = ((d + 63) // 64) * 64 if aligned else d + (1 if d % 2 == 0 else 2)
+            announce("fused", g_dtype, mode, "d", d, "N", N, "stride", stride)
+            x, m, g = draw_state(rng, N, d, g_dtype, stride, stride)
+            W = dl.words_for(d)
+            packed = strided_rows(N, W, W + 3, torch.int64, DEV)
+            counts = torch.full((d,), -1, dtype=torch.int16, device=DEV)
+            for step in range(3):
+                xn, mn, pn, cn = oracle_step(x, m, g, mode, HYP)
+                dl.dlion_step(x, m, g, mode, HYP["beta1"], HYP["beta2"], HYP["lr"], HYP["lam"],
+                              packed=packed, counts=counts)
+                torch.cuda.synchronize()
+                compare_all(f"d={d} N={N} step={step}", x, m, packed, counts, xn, mn, pn, cn)
+            # padding of strided buffers untouched
+            assert torch.isnan(m._base[:, d:]).all() if stride > d else True
+            assert (packed._base[:, W:] == -1).all()
+
+
+@pytest.mark.parametrize("g_dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_output_flags_do_not_change_state(g_dtype):
+    """The bench configuration (no packed, no counts) gives the same x, m as the instrumented one."""
+    rng = np.random.default_rng(99)
+    for d, N, mode in ((70_001, 8, dl.AVG), (4096, 5, dl.VOTE), (300, 2, dl.AVG)):
+        announce("flags", g_dtype, d, N, mode)
+        stride = ((d + 63) // 64) * 64
+        x0, m0, g = draw_state(rng, N, d, g_dtype, stride, stride)
+        xn, mn, pn, cn = oracle_step(x0, m0, g, mode, HYP)
+        for want_p, want_c in itertools.product((False, True), repeat=2):
+            x, m = x0.clone(), m0.clone()
+            packed = torch.zeros((N, dl.words_for(d)), dtype=torch.int64, device=DEV) if want_p else None
+            counts = torch.zeros(d, dtype=torch.int16, device=DEV) if want_c else None
+            dl.dlion_step(x, m, g, mode, HYP["beta1"], HYP["beta2"], HYP["lr"], HYP["lam"],
+                          packed=packed, counts=counts)
+            torch.cuda.synchronize()
+            compare_all(f"flags p={want_p} c={want_c}", x, m, packed, counts, xn, mn, pn, cn)
+
+
+@pytest.mark.parametrize("g_dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_unfused_pipeline_matches_oracle(g_dtype):
+    """worker_step -> aggregate -> apply, and worker_step -> aggregate_apply."""
+    rng = np.random.default_rng(4321)
+    for (d, N), mode in itertools.product(((1, 1), (65, 3), (256, 4), (1000, 8), (70_001, 5), (8192, 16),
+                                           (5000, 300)), (dl.VOTE, dl.AVG)):
+        for aligned in (True, False):
+            stride = ((d + 63) // 64) * 64 if aligned else d + (1 if d % 2 == 0 else 2)
+            announce("unfused", g_dtype, d, N, mode, stride)
+            x, m, g = draw_state(rng, N, d, g_dtype, stride, stride)
+            x2 = x.clone()
+            W = dl.words_for(d)
+            xn, mn, pn, cn = oracle_step(x, m, g, mode, HYP)
+            packed = torch.full((N, W), -1, dtype=torch.int64, device=DEV)
+            counts = torch.full((d,), -1, dtype=torch.int16, device=DEV)
+            dl.dlion_worker_step(m, g, packed, HYP["beta1"], HYP["beta2"])
+            dl.dlion_aggregate(packed, d, counts)
+            dl.dlion_apply(x, counts, N, mode, HYP["lr"], HYP["lam"])
+            counts2 = torch.full((d,), -1, dtype=torch.int16, device=DEV)
+            dl.dlion_aggregate_apply(x2, packed, mode, HYP["lr"], HYP["lam"], counts=counts2)
+            x3 = x2.clone()
+            torch.cuda.synchronize()
+            compare_all("unfused", x, m, packed, counts, xn, mn, pn, cn)
+            compare_all("aggregate_apply", x2, m, packed, counts2, xn, mn, pn, cn)
+            # and without the optional counts output (applied a second time, on x3 = x after 1 step)
+            xn2 = xn.copy()
+            oracle.apply(xn2, cn, N, mode, HYP["lr"], HYP["lam"])
+            dl.dlion_aggregate_apply(x3, packed, mode, HYP["lr"], HYP["lam"])
+            torch.cuda.synchronize()
+            assert_f32_equal(to_np(x3), xn2, "aggregate_apply (no counts): x")
+
+
+def test_special_values():
+    """Zeros, negative zeros, subnormals, infinities and NaNs: sign(0)=+1, subnormals kept."""
+    N, d = 4, 512
+    tiny = np.float32(1e-45)             # smallest subnormal
+    vals = np.array([0.0, -0.0, tiny, -tiny, 1e-39, -1e-39, 1.1754944e-38, -1.1754944e-38, 1.0, -1.0,
+                     np.inf, -np.inf, np.nan, 3.4e38, -3.4e38, 1e-30], dtype=np.float32)
+    rng = np.random.default_rng(5)
+    for g_dtype in (torch.float32, torch.bfloat16):
+        for mode in (dl.VOTE, dl.AVG):
+            announce("special", g_dtype, mode)
+            mv = rng.choice(vals, size=(N, d)).astype(np.float32)
+            gv = rng.choice(vals, size=(N, d)).astype(np.float32)
+            xv = rng.choice(vals, size=d).astype(np.float32)
+            x = torch.from_numpy(xv).to(DEV)
+            m = torch.from_numpy(mv).to(DEV)
+            g = torch.from_numpy(gv).to(DEV).to(g_dtype)
+            packed = torch.zeros((N, dl.words_for(d)), dtype=torch.int64, device=DEV)
+            counts = torch.zeros(d, dtype=torch.int16, device=DEV)
+            xn, mn, pn, cn = oracle_step(x, m, g, mode, dict(beta1=0.9, beta2=0.99, lr=0.5, lam=0.5))
+            dl.dlion_step(x, m, g, mode, 0.9, 0.99, 0.5, 0.5, packed=packed, counts=counts)
+            torch.cuda.synchronize()
+            compare_all("special", x, m, packed, counts, xn, mn, pn, cn)
+            # subnormal momentum must survive: 0.99 * 1e-39 is subnormal and must not flush to 0
+            sub = (np.abs(mn) > 0) & (np.abs(mn) < 1.1754944e-38)
+            assert sub.any()
+            assert np.array_equal(to_np(m)[sub].view(np.uint32), mn[sub].view(np.uint32))
+
+
+def test_average_division_every_count():
+    """Averaging must be one correctly rounded fp32 division for every N, every count p."""
+    for N in (1, 2, 3, 5, 6, 7, 9, 10, 11, 13, 24, 31, 33, 100, 255, 256, 257, 1000, 4097, 65535):
+        announce("avg division N", N)
+        d = N + 1
+        counts_np = np.arange(d, dtype=np.uint16)
+        xv = np.linspace(-1, 1, d).astype(np.float32)
+        x = torch.from_numpy(xv.copy()).to(DEV)
+        counts = torch.from_numpy(counts_np.view(np.int16).copy()).to(DEV)
+        for mode in (dl.VOTE, dl.AVG):
+            xn = to_np(x)
+            oracle.apply(xn, counts_np, N, mode, 0.25, 0.5)
+            dl.dlion_apply(x, counts, N, mode, 0.25, 0.5)
+            torch.cuda.synchronize()
+            assert np.array_equal(to_np(x).view(np.uint32), xn.view(np.uint32)), f"N={N} mode={mode}"
+
+
+def test_sign_without_fma_on_device():
+    """Pairs (m, g) where the individually rounded sum is exactly 0 but a fused multiply-add
+    would give a negative number: the device must vote +1 like the oracle."""
+    b1 = np.float32(0.9)
+    omb1 = np.float32(1) - b1
+    rng = np.random.default_rng(5)
+    ms, gs = [], []
+    while len(ms) < 4096:
+        g = np.float32(rng.normal())
+        b = omb1 * g
+        mm = np.float32(-b / b1)
+        for cand in (mm, np.nextafter(mm, np.float32(10)), np.nextafter(mm, np.float32(-10))):
+            if np.float32(b1 * cand + b) == 0 and (float(b1) * float(cand) + float(b)) != 0:
+                ms.append(cand)
+                gs.append(g)
+    d = len(ms)
+    m = torch.tensor(np.array(ms, np.float32)[None, :]).to(DEV)
+    g = torch.tensor(np.array(gs, np.float32)[None, :]).to(DEV)
+    mn, gn = to_np(m), to_np(g)
+    want = oracle.worker_step(mn, gn, 0.9, 0.99)
+    packed = torch.zeros((1, dl.words_for(d)), dtype=torch.int64, device=DEV)
+    dl.dlion_worker_step(m, g, packed, 0.9, 0.99)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(packed), want)
+    assert (want == np.uint64(0xFFFFFFFFFFFFFFFF)).all()
+
+
+def make_list(rng, numels, N, g_dtype):
+    xs = [torch.from_numpy(rng.normal(0, 0.02, n).astype(np.float32)).to(DEV) for n in numels]
+    ms = [torch.from_numpy(rng.normal(0, 1e-3, (N, n)).astype(np.float32)).to(DEV) for n in numels]
+    gs = [torch.from_numpy(rng.normal(0, 1e-3, (N, n)).astype(np.float32)).to(DEV).to(g_dtype) for n in numels]
+    return xs, ms, gs
+
+
+def unpad_counts(counts, table):
+    c = to_np(counts)
+    return np.concatenate([c[64 * wb: 64 * wb + n] for wb, n in zip(table.word_begin, table.numels)])
+
+
+@pytest.mark.parametrize("g_dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("mode", [dl.VOTE, dl.AVG], ids=["vote", "avg"])
+def test_tensor_list_matches_oracle(g_dtype, mode):
+    rng = np.random.default_rng(777)
+    numels = [1000, 5, 64, 256, 768, 257, 1, 2304 * 8, 4097, 63]
+    hyp = dict(beta1=0.9, beta2=0.99, lr=1e-4, lam=10.0)
+    for N in (1, 4, 16, 5):
+        announce("tensor list", g_dtype, mode, "N", N)
+        xs, ms, gs = make_list(rng, numels, N, g_dtype)
+        table = dl.SegTable(xs, ms, gs)
+        Wt = table.total_words
+        assert Wt == sum((n + 63) // 64 for n in numels)
+        packed = torch.full((N, Wt), -1, dtype=torch.int64, device=DEV)
+        counts = torch.full((64 * Wt,), -1, dtype=torch.int16, device=DEV)
+        for step in range(2):
+            xn = [to_np(t) for t in xs]
+            mn = [to_np(t) for t in ms]
+            gn = [to_np(t) for t in gs]
+            pn, cn = oracle.step_mt(xn, mn, gn, mode, hyp["beta1"], hyp["beta2"], hyp["lr"], hyp["lam"])
+            # unfused on copies first
+            xs_u = [t.clone() for t in xs]
+            ms_u = [t.clone() for t in ms]
+            tab_u = dl.SegTable(xs_u, ms_u, gs)
+            packed_u = torch.full((N, Wt), -1, dtype=torch.int64, device=DEV)
+            counts_u = torch.full((64 * Wt,), -1, dtype=torch.int16, device=DEV)
+            dl.dlion_worker_step_mt(tab_u, packed_u, hyp["beta1"], hyp["beta2"])
+            dl.dlion_aggregate_mt(tab_u, packed_u, counts_u)
+            dl.dlion_apply_mt(tab_u, counts_u, N, mode, hyp["lr"], hyp["lam"])
+            xs_a = [t.clone() for t in xs]
+            tab_a = dl.SegTable(xs_a, None, None)
+            dl.dlion_aggregate_apply_mt(tab_a, packed_u, mode, hyp["lr"], hyp["lam"])
+            # fused in place
+            dl.dlion_step_mt(table, N, mode, hyp["beta1"], hyp["beta2"], hyp["lr"], hyp["lam"],
+                             packed=packed, counts=counts)
+            torch.cuda.synchronize()
+            for tag, P, C, X, M in (("fused", packed, counts, xs, ms), ("unfused", packed_u, counts_u, xs_u, ms_u)):
+                assert np.array_equal(to_np(P), pn), f"{tag}: packed"
+                assert np.array_equal(unpad_counts(C, table), cn), f"{tag}: counts"
+                # padding between tensors is written as 0
+                cfull = to_np(C)
+                for wb, n in zip(table.word_begin, table.numels):
+                    assert not cfull[64 * wb + n: 64 * (wb + (n + 63) // 64)].any()
+                for k in range(len(numels)):
+                    assert_f32_equal(to_np(X[k]), xn[k], f"{tag}: x[{k}]")
+                    assert_f32_equal(to_np(M[k]), mn[k], f"{tag}: m[{k}]")
+            for k in range(len(numels)):
+                assert_f32_equal(to_np(xs_a[k]), xn[k], f"aggregate_apply_mt: x[{k}]")
+
+
+def test_tiny_config_full_run():
+    """Config 'tiny' exactly as stated: d = 1,000,003, N = 4, vote, fp32 N(0,1) gradients, 10 steps."""
+    w = wl.CONFIGS["tiny"]
+    x = wl.init_x(w, DEV)
+    for stride in (w.d, ((w.d + 63) // 64) * 64):
+        announce("tiny", "stride", stride)
+        x = wl.init_x(w, DEV)
+        m = wl.init_m(w, DEV, row_stride=stride)
+        xn, mn = to_np(x), to_np(m)
+        packed = torch.zeros((w.N, dl.words_for(w.d)), dtype=torch.int64, device=DEV)
+        counts = torch.zeros(w.d, dtype=torch.int16, device=DEV)
+        exact = True
+        for t in range(w.steps):
+            g = wl.make_grads(w, t, DEV)
+            pn, cn = oracle.step(xn, mn, to_np(g), w.mode, w.beta1, w.beta2, w.lr, w.lam, threads=8)
+            dl.dlion_step(x, m, g, w.mode, w.beta1, w.beta2, w.lr, w.lam, packed=packed, counts=counts)
+            torch.cuda.synchronize()
+            assert np.array_equal(to_np(packed), pn), f"step {t}: packed"
+            assert np.array_equal(to_np(counts), cn), f"step {t}: counts"
+            exact &= assert_f32_equal(to_np(m), mn, f"step {t}: m")
+            exact &= assert_f32_equal(to_np(x), xn, f"step {t}: x")
+        # last word: only 3 valid bits
+        assert (to_np(packed)[:, -1] >> np.uint64(3) == 0).all()
+        print("tiny: bit-identical fp32 state:", exact, flush=True)
