@@ -134,7 +134,7 @@ typedef struct dlion_seg {
     int64_t g_stride;
     int64_t numel;      /* > 0                                                      */
     int64_t word_begin; /* filled by dlion_mt_layout                                */
-    int64_t tile_begin; /* filled by dlion_mt_layout (256-coordinate tiles)         */
+    int64_t tile_begin; /* filled by dlion_mt_layout (first wave-tile of the tensor)*/
 } dlion_seg;
 
 /*

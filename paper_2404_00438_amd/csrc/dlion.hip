@@ -4,6 +4,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 namespace {
 
 using namespace dlion;
@@ -39,33 +41,84 @@ inline dlion_status launched()
     return hipGetLastError() == hipSuccess ? DLION_OK : DLION_ELAUNCH;
 }
 
+// ------------------------------------------------------------------ launch shape
+// HBM delivers the most when the chip keeps only a modest, compact window of
+// addresses in flight: roughly 24 KB of outstanding loads per compute unit.
+// A wave of the fused kernel has `unroll` workers' loads outstanding at once,
+// so the number of resident waves per compute unit is capped accordingly.  The
+// cap is applied by reserving (unused) dynamic LDS per workgroup: a compute
+// unit has 160 KB, so a reservation of 160 KB / k admits k workgroups.
+struct LaunchShape {
+    int unroll;          // workers whose loads are issued back to back (8, 4, 2 or 1)
+    int blocks_per_cu;   // resident workgroups per compute unit (0: no cap)
+};
+
+constexpr size_t kLdsPerCu = 160 * 1024;
+constexpr size_t kMaxDynamicLds = 64 * 1024;
+
+inline size_t lds_reservation(int blocks_per_cu)
+{
+    if (blocks_per_cu <= 0)
+        return 0;
+    size_t bytes = (kLdsPerCu / static_cast<size_t>(blocks_per_cu)) & ~static_cast<size_t>(1023);
+    return bytes > kMaxDynamicLds ? kMaxDynamicLds : bytes;
+}
+
+// Environment overrides for tuning runs, read once: DLION_UNROLL, DLION_BLOCKS_PER_CU.
+inline int env_int(const char *name)
+{
+    const char *v = std::getenv(name);
+    return v ? std::atoi(v) : -1;
+}
+
+LaunchShape step_shape(int32_t N, size_t bytes_per_worker_per_wave)
+{
+    static const int env_unroll = env_int("DLION_UNROLL");
+    static const int env_blocks = env_int("DLION_BLOCKS_PER_CU");
+    LaunchShape s;
+    s.unroll = env_unroll > 0 ? env_unroll : 2;
+    while (s.unroll > N)
+        s.unroll >>= 1;
+    if (s.unroll < 1)
+        s.unroll = 1;
+    if (env_blocks >= 0) {
+        s.blocks_per_cu = env_blocks;
+    } else {
+        const size_t in_flight = bytes_per_worker_per_wave * static_cast<size_t>(s.unroll) * kWavesPerBlock;
+        int k = static_cast<int>((24 * 1024 + in_flight / 2) / in_flight);
+        s.blocks_per_cu = k < 3 ? 3 : (k > 32 ? 0 : k);
+    }
+    return s;
+}
+
 // ------------------------------------------------------------------ dispatch
 template <typename GT, int kUnroll, bool kApply, class Addr>
-dlion_status launch_step_flags(const Addr &addr, const Hyper &h, bool packed, bool counts, hipStream_t s)
+dlion_status launch_step_flags(const Addr &addr, const Hyper &h, bool packed, bool counts, size_t lds,
+                               hipStream_t s)
 {
     const dim3 grid = grid_for(addr.total_tiles), block(kBlock);
     if (packed && counts)
-        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, true, true, Addr>), grid, block, 0, s, addr, h);
+        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, true, true, Addr>), grid, block, lds, s, addr, h);
     else if (packed)
-        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, true, false, Addr>), grid, block, 0, s, addr, h);
+        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, true, false, Addr>), grid, block, lds, s, addr, h);
     else if (counts)
-        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, false, true, Addr>), grid, block, 0, s, addr, h);
+        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, false, true, Addr>), grid, block, lds, s, addr, h);
     else
-        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, false, false, Addr>), grid, block, 0, s, addr, h);
+        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, false, false, Addr>), grid, block, lds, s, addr, h);
     return launched();
 }
 
 template <typename GT, bool kApply, class Addr>
 dlion_status launch_step_unroll(const Addr &addr, const Hyper &h, bool packed, bool counts, hipStream_t s)
 {
-    // Loads of kUnroll workers are issued back to back before any arithmetic.
-    if (h.N >= 8)
-        return launch_step_flags<GT, 8, kApply, Addr>(addr, h, packed, counts, s);
-    if (h.N >= 4)
-        return launch_step_flags<GT, 4, kApply, Addr>(addr, h, packed, counts, s);
-    if (h.N >= 2)
-        return launch_step_flags<GT, 2, kApply, Addr>(addr, h, packed, counts, s);
-    return launch_step_flags<GT, 1, kApply, Addr>(addr, h, packed, counts, s);
+    const LaunchShape shape = step_shape(h.N, kSubs * kLanes * (16 + Grad<GT>::kVecBytes));
+    const size_t lds = lds_reservation(shape.blocks_per_cu);
+    switch (shape.unroll) {
+    case 8: return launch_step_flags<GT, 8, kApply, Addr>(addr, h, packed, counts, lds, s);
+    case 4: return launch_step_flags<GT, 4, kApply, Addr>(addr, h, packed, counts, lds, s);
+    case 2: return launch_step_flags<GT, 2, kApply, Addr>(addr, h, packed, counts, lds, s);
+    default: return launch_step_flags<GT, 1, kApply, Addr>(addr, h, packed, counts, lds, s);
+    }
 }
 
 template <bool kApply, class Addr>

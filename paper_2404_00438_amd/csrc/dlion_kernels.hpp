@@ -27,12 +27,41 @@
 
 namespace dlion {
 
+// Launch-shape knobs (compile-time; the defaults are the measured best on MI355X).
+#ifndef DLION_SUBTILES
+#define DLION_SUBTILES 1        // 256-coordinate sub-tiles a wave handles together
+#endif
+#ifndef DLION_WAVES_PER_BLOCK
+#define DLION_WAVES_PER_BLOCK 1
+#endif
+#ifndef DLION_NT_LOAD
+#define DLION_NT_LOAD 1         // streaming (non-temporal) loads of m and g
+#endif
+#ifndef DLION_NT_STORE
+#define DLION_NT_STORE 1        // streaming stores of m
+#endif
+#ifndef DLION_MAX_WAVES_PER_EU
+#define DLION_MAX_WAVES_PER_EU 0   // cap on resident waves per SIMD for the streaming kernels (0: no cap)
+#endif
+#ifndef DLION_XCD_REMAP
+#define DLION_XCD_REMAP 0       // give each of the 8 XCDs one contiguous range of tiles
+#endif
+
 constexpr int kLanes = 64;
-constexpr int kVec = 4;                 // coordinates per lane per tile on the vector path
-constexpr int kTile = kLanes * kVec;    // 256 coordinates
-constexpr int kWordsPerTile = kTile / 64;
-constexpr int kWavesPerBlock = 4;
+constexpr int kVec = 4;                       // coordinates per lane per sub-tile on the vector path
+constexpr int kSubTile = kLanes * kVec;       // 256 coordinates = 4 packed words
+constexpr int kWordsPerSub = kSubTile / 64;
+constexpr int kSubs = DLION_SUBTILES;
+constexpr int kTile = kSubTile * kSubs;       // coordinates one wave owns
+constexpr int kWavesPerBlock = DLION_WAVES_PER_BLOCK;
 constexpr int kBlock = kLanes * kWavesPerBlock;
+constexpr int kXcds = 8;
+
+#if DLION_MAX_WAVES_PER_EU > 0
+#define DLION_OCCUPANCY __attribute__((amdgpu_waves_per_eu(1, DLION_MAX_WAVES_PER_EU)))
+#else
+#define DLION_OCCUPANCY
+#endif
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -112,7 +141,31 @@ __device__ __forceinline__ int64_t wave_tile_index()
     // blockIdx and the wave number are uniform across the wavefront; say so, so
     // that everything derived from the tile index stays in scalar registers.
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    return (int64_t)blockIdx.x * kWavesPerBlock + wave;
+    uint32_t block = blockIdx.x;
+#if DLION_XCD_REMAP
+    // Workgroups are handed to the 8 XCDs round-robin (block b runs on XCD b % 8).
+    // Renumber them so that XCD x walks one contiguous range of tiles.
+    const uint32_t G = gridDim.x, q = G / kXcds, r = G % kXcds, xcd = block % kXcds;
+    block = xcd * q + (xcd < r ? xcd : r) + block / kXcds;
+#endif
+    return (int64_t)block * kWavesPerBlock + wave;
+}
+
+template <typename T> __device__ __forceinline__ T stream_load(const T *p)
+{
+#if DLION_NT_LOAD
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
+template <typename T> __device__ __forceinline__ void stream_store(T v, T *p)
+{
+#if DLION_NT_STORE
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
 }
 
 __device__ __forceinline__ bool is_aligned(const void *p, uint64_t a)
@@ -126,19 +179,18 @@ template <> struct Grad<float> {
     static constexpr int kVecBytes = 16;
     static __device__ __forceinline__ f32x4 load4(const void *g, int64_t idx)
     {
-        return __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(static_cast<const float *>(g) + idx));
+        return stream_load(reinterpret_cast<const f32x4 *>(static_cast<const float *>(g) + idx));
     }
     static __device__ __forceinline__ float load1(const void *g, int64_t idx)
     {
-        return __builtin_nontemporal_load(static_cast<const float *>(g) + idx);
+        return stream_load(static_cast<const float *>(g) + idx);
     }
 };
 template <> struct Grad<uint16_t> {   // bf16 bit patterns; widening to fp32 is exact
     static constexpr int kVecBytes = 8;
     static __device__ __forceinline__ f32x4 load4(const void *g, int64_t idx)
     {
-        const u32x2 raw = __builtin_nontemporal_load(
-            reinterpret_cast<const u32x2 *>(static_cast<const uint16_t *>(g) + idx));
+        const u32x2 raw = stream_load(reinterpret_cast<const u32x2 *>(static_cast<const uint16_t *>(g) + idx));
         f32x4 r;
         r.x = __uint_as_float(raw.x << 16);
         r.y = __uint_as_float(raw.x & 0xFFFF0000u);
@@ -148,7 +200,7 @@ template <> struct Grad<uint16_t> {   // bf16 bit patterns; widening to fp32 is 
     }
     static __device__ __forceinline__ float load1(const void *g, int64_t idx)
     {
-        const uint16_t raw = __builtin_nontemporal_load(static_cast<const uint16_t *>(g) + idx);
+        const uint16_t raw = stream_load(static_cast<const uint16_t *>(g) + idx);
         return __uint_as_float(static_cast<uint32_t>(raw) << 16);
     }
 };
@@ -206,17 +258,25 @@ __device__ __forceinline__ uint64_t row_gather_nibbles(uint32_t nibble, int lane
 // ---------------------------------------------------------------- fused / worker tile
 // kApply : read x, aggregate, write x (fused step); else worker step only.
 // kPacked: write packed words.   kCounts: write counts.
-template <typename GT, int kUnroll, bool kApply, bool kPacked, bool kCounts>
-__device__ __forceinline__ void step_tile_vector(const Problem &p, int64_t t, int lane, const Hyper &h)
+// Vector path over kR full sub-tiles starting at sub-tile `t`: the loads of kUnroll workers
+// x kR sub-tiles are issued back to back before any arithmetic.
+template <typename GT, int kUnroll, int kR, bool kApply, bool kPacked, bool kCounts>
+__device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t, int lane, const Hyper &h)
 {
-    const int64_t j0 = t * kTile + lane * kVec;
-    f32x4 xv;
-    if (kApply)
-        xv = *reinterpret_cast<const f32x4 *>(p.x + j0);
-    uint32_t cnt0 = 0, cnt1 = 0, cnt2 = 0, cnt3 = 0;
+    const int64_t j0 = t * kSubTile + lane * kVec;
+    f32x4 xv[kR];
+    if (kApply) {
+#pragma unroll
+        for (int r = 0; r < kR; ++r)
+            xv[r] = *reinterpret_cast<const f32x4 *>(p.x + j0 + r * kSubTile);
+    }
+    uint32_t cnt[kR][4];
+#pragma unroll
+    for (int r = 0; r < kR; ++r)
+        cnt[r][0] = cnt[r][1] = cnt[r][2] = cnt[r][3] = 0;
     const int N = h.N;
 
-    auto one_worker = [&](int i, f32x4 mv, f32x4 gv) {
+    auto one_worker = [&](int i, int r, f32x4 mv, f32x4 gv) {
         float m0 = mv.x, m1 = mv.y, m2 = mv.z, m3 = mv.w;
         const bool b0 = lion_worker(m0, gv.x, h);
         const bool b1 = lion_worker(m1, gv.y, h);
@@ -226,65 +286,79 @@ __device__ __forceinline__ void step_tile_vector(const Problem &p, int64_t t, in
         mv.y = m1;
         mv.z = m2;
         mv.w = m3;
-        __builtin_nontemporal_store(mv, reinterpret_cast<f32x4 *>(p.m + (int64_t)i * p.m_stride + j0));
-        cnt0 += b0;
-        cnt1 += b1;
-        cnt2 += b2;
-        cnt3 += b3;
+        stream_store(mv, reinterpret_cast<f32x4 *>(p.m + (int64_t)i * p.m_stride + j0 + r * kSubTile));
+        cnt[r][0] += b0;
+        cnt[r][1] += b1;
+        cnt[r][2] += b2;
+        cnt[r][3] += b3;
         if (kPacked) {
             const uint32_t nib = (b0 ? 1u : 0u) | (b1 ? 2u : 0u) | (b2 ? 4u : 0u) | (b3 ? 8u : 0u);
             const uint64_t word = row_gather_nibbles(nib, lane);
             if ((lane & 15) == 0)
-                p.packed[(int64_t)i * p.packed_stride + t * kWordsPerTile + (lane >> 4)] = word;
+                p.packed[(int64_t)i * p.packed_stride + (t + r) * kWordsPerSub + (lane >> 4)] = word;
         }
     };
 
     int i = 0;
     for (; i + kUnroll <= N; i += kUnroll) {
-        f32x4 mv[kUnroll], gv[kUnroll];
+        f32x4 mv[kUnroll][kR], gv[kUnroll][kR];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            mv[u] = __builtin_nontemporal_load(
-                reinterpret_cast<const f32x4 *>(p.m + (int64_t)(i + u) * p.m_stride + j0));
-            gv[u] = Grad<GT>::load4(p.g, (int64_t)(i + u) * p.g_stride + j0);
+#pragma unroll
+            for (int r = 0; r < kR; ++r) {
+                mv[u][r] = stream_load(
+                    reinterpret_cast<const f32x4 *>(p.m + (int64_t)(i + u) * p.m_stride + j0 + r * kSubTile));
+                gv[u][r] = Grad<GT>::load4(p.g, (int64_t)(i + u) * p.g_stride + j0 + r * kSubTile);
+            }
         }
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u)
-            one_worker(i + u, mv[u], gv[u]);
+        for (int u = 0; u < kUnroll; ++u) {
+#pragma unroll
+            for (int r = 0; r < kR; ++r)
+                one_worker(i + u, r, mv[u][r], gv[u][r]);
+        }
     }
     for (; i < N; ++i) {
-        const f32x4 mv = __builtin_nontemporal_load(
-            reinterpret_cast<const f32x4 *>(p.m + (int64_t)i * p.m_stride + j0));
-        const f32x4 gv = Grad<GT>::load4(p.g, (int64_t)i * p.g_stride + j0);
-        one_worker(i, mv, gv);
+        f32x4 mv[kR], gv[kR];
+#pragma unroll
+        for (int r = 0; r < kR; ++r) {
+            mv[r] = stream_load(reinterpret_cast<const f32x4 *>(p.m + (int64_t)i * p.m_stride + j0 + r * kSubTile));
+            gv[r] = Grad<GT>::load4(p.g, (int64_t)i * p.g_stride + j0 + r * kSubTile);
+        }
+#pragma unroll
+        for (int r = 0; r < kR; ++r)
+            one_worker(i, r, mv[r], gv[r]);
     }
 
-    if (kApply) {
-        xv.x = lion_apply(xv.x, aggregate_votes(cnt0, h), h);
-        xv.y = lion_apply(xv.y, aggregate_votes(cnt1, h), h);
-        xv.z = lion_apply(xv.z, aggregate_votes(cnt2, h), h);
-        xv.w = lion_apply(xv.w, aggregate_votes(cnt3, h), h);
-        *reinterpret_cast<f32x4 *>(p.x + j0) = xv;
-    }
-    if (kCounts) {
-        u16x4 c;
-        c.x = static_cast<uint16_t>(cnt0);
-        c.y = static_cast<uint16_t>(cnt1);
-        c.z = static_cast<uint16_t>(cnt2);
-        c.w = static_cast<uint16_t>(cnt3);
-        *reinterpret_cast<u16x4 *>(p.counts + j0) = c;
+#pragma unroll
+    for (int r = 0; r < kR; ++r) {
+        if (kApply) {
+            xv[r].x = lion_apply(xv[r].x, aggregate_votes(cnt[r][0], h), h);
+            xv[r].y = lion_apply(xv[r].y, aggregate_votes(cnt[r][1], h), h);
+            xv[r].z = lion_apply(xv[r].z, aggregate_votes(cnt[r][2], h), h);
+            xv[r].w = lion_apply(xv[r].w, aggregate_votes(cnt[r][3], h), h);
+            *reinterpret_cast<f32x4 *>(p.x + j0 + r * kSubTile) = xv[r];
+        }
+        if (kCounts) {
+            u16x4 c;
+            c.x = static_cast<uint16_t>(cnt[r][0]);
+            c.y = static_cast<uint16_t>(cnt[r][1]);
+            c.z = static_cast<uint16_t>(cnt[r][2]);
+            c.w = static_cast<uint16_t>(cnt[r][3]);
+            *reinterpret_cast<u16x4 *>(p.counts + j0 + r * kSubTile) = c;
+        }
     }
 }
 
 // Guarded path: lane l owns coordinates 64k+l of the tile; every access checks
 // j < numel; a 64-lane ballot is already a canonical packed word.
 template <typename GT, bool kApply, bool kPacked, bool kCounts>
-__device__ __forceinline__ void step_tile_guarded(const Problem &p, int64_t t, int lane, const Hyper &h)
+__device__ __forceinline__ void step_subtile_guarded(const Problem &p, int64_t t, int lane, const Hyper &h)
 {
     const int64_t W = (p.numel + 63) >> 6;
 #pragma unroll 1
-    for (int k = 0; k < kWordsPerTile; ++k) {
-        const int64_t w = t * kWordsPerTile + k;
+    for (int k = 0; k < kWordsPerSub; ++k) {
+        const int64_t w = t * kWordsPerSub + k;
         if (w >= W)
             break;                                   // uniform: whole wave leaves together
         const int64_t j = w * 64 + lane;
@@ -314,24 +388,35 @@ __device__ __forceinline__ void step_tile_guarded(const Problem &p, int64_t t, i
 }
 
 template <typename GT, int kUnroll, bool kApply, bool kPacked, bool kCounts, class Addr>
-__global__ __launch_bounds__(kBlock) void step_kernel(Addr addr, Hyper h)
+__global__ __launch_bounds__(kBlock) DLION_OCCUPANCY void step_kernel(Addr addr, Hyper h)
 {
     const int64_t tile = wave_tile_index();
     if (tile >= addr.total_tiles)
         return;
     const int lane = threadIdx.x & 63;
     Problem p;
-    const int64_t t = addr.resolve(tile, p);
-    bool vec = (t + 1) * kTile <= p.numel && is_aligned(p.m, 16) && (p.m_stride & 3) == 0 &&
-               is_aligned(p.g, Grad<GT>::kVecBytes) && (p.g_stride & 3) == 0;
+    const int64_t t = addr.resolve(tile, p) * kSubs;      // first sub-tile of this wave
+    bool aligned = is_aligned(p.m, 16) && (p.m_stride & 3) == 0 && is_aligned(p.g, Grad<GT>::kVecBytes) &&
+                   (p.g_stride & 3) == 0;
     if (kApply)
-        vec = vec && is_aligned(p.x, 16);
+        aligned = aligned && is_aligned(p.x, 16);
     if (kCounts)
-        vec = vec && is_aligned(p.counts, 8);
-    if (vec)
-        step_tile_vector<GT, kUnroll, kApply, kPacked, kCounts>(p, t, lane, h);
-    else
-        step_tile_guarded<GT, kApply, kPacked, kCounts>(p, t, lane, h);
+        aligned = aligned && is_aligned(p.counts, 8);
+    if (aligned && (t + kSubs) * kSubTile <= p.numel) {
+        step_subtiles_vector<GT, kUnroll, kSubs, kApply, kPacked, kCounts>(p, t, lane, h);
+        return;
+    }
+    // ragged end of a tensor, or rows that cannot take 128-bit accesses
+#pragma unroll 1
+    for (int r = 0; r < kSubs; ++r) {
+        const int64_t sub = t + r;
+        if (sub * kSubTile >= p.numel)
+            break;
+        if (kSubs > 1 && aligned && (sub + 1) * kSubTile <= p.numel)
+            step_subtiles_vector<GT, kUnroll, 1, kApply, kPacked, kCounts>(p, sub, lane, h);
+        else
+            step_subtile_guarded<GT, kApply, kPacked, kCounts>(p, sub, lane, h);
+    }
 }
 
 // ---------------------------------------------------------------- server side from packed words
@@ -339,9 +424,9 @@ __global__ __launch_bounds__(kBlock) void step_kernel(Addr addr, Hyper h)
 // tile.  Votes are accumulated four at a time in the bytes of one register (a nibble is
 // spread to one bit per byte by a multiply), flushed to 32-bit counters every 255 workers.
 template <bool kApply, bool kCounts>
-__device__ __forceinline__ void agg_tile_vector(const Problem &p, int64_t t, int lane, const Hyper &h)
+__device__ __forceinline__ void agg_subtile_vector(const Problem &p, int64_t t, int lane, const Hyper &h)
 {
-    const uint32_t *half = reinterpret_cast<const uint32_t *>(p.packed + t * kWordsPerTile + (lane >> 4)) +
+    const uint32_t *half = reinterpret_cast<const uint32_t *>(p.packed + t * kWordsPerSub + (lane >> 4)) +
                            ((lane >> 3) & 1);
     const int shift = (lane & 7) * 4;
     const int64_t stride32 = p.packed_stride * 2;
@@ -367,7 +452,7 @@ __device__ __forceinline__ void agg_tile_vector(const Problem &p, int64_t t, int
         cnt2 += (acc >> 16) & 0xFFu;
         cnt3 += acc >> 24;
     }
-    const int64_t j0 = t * kTile + lane * kVec;
+    const int64_t j0 = t * kSubTile + lane * kVec;
     if (kApply) {
         f32x4 xv = *reinterpret_cast<const f32x4 *>(p.x + j0);
         xv.x = lion_apply(xv.x, aggregate_votes(cnt0, h), h);
@@ -388,12 +473,12 @@ __device__ __forceinline__ void agg_tile_vector(const Problem &p, int64_t t, int
 
 // Guarded path: lane l owns bit l of word 4t+k.
 template <bool kApply, bool kCounts>
-__device__ __forceinline__ void agg_tile_guarded(const Problem &p, int64_t t, int lane, const Hyper &h)
+__device__ __forceinline__ void agg_subtile_guarded(const Problem &p, int64_t t, int lane, const Hyper &h)
 {
     const int64_t W = (p.numel + 63) >> 6;
 #pragma unroll 1
-    for (int k = 0; k < kWordsPerTile; ++k) {
-        const int64_t w = t * kWordsPerTile + k;
+    for (int k = 0; k < kWordsPerSub; ++k) {
+        const int64_t w = t * kWordsPerSub + k;
         if (w >= W)
             break;
         const int64_t j = w * 64 + lane;
@@ -420,16 +505,22 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(Addr addr, Hyper h)
         return;
     const int lane = threadIdx.x & 63;
     Problem p;
-    const int64_t t = addr.resolve(tile, p);
-    bool vec = (t + 1) * kTile <= p.numel;
+    const int64_t t = addr.resolve(tile, p) * kSubs;
+    bool aligned = true;
     if (kApply)
-        vec = vec && is_aligned(p.x, 16);
+        aligned = aligned && is_aligned(p.x, 16);
     if (kCounts)
-        vec = vec && is_aligned(p.counts, 8);
-    if (vec)
-        agg_tile_vector<kApply, kCounts>(p, t, lane, h);
-    else
-        agg_tile_guarded<kApply, kCounts>(p, t, lane, h);
+        aligned = aligned && is_aligned(p.counts, 8);
+#pragma unroll 1
+    for (int r = 0; r < kSubs; ++r) {
+        const int64_t sub = t + r;
+        if (sub * kSubTile >= p.numel)
+            break;
+        if (aligned && (sub + 1) * kSubTile <= p.numel)
+            agg_subtile_vector<kApply, kCounts>(p, sub, lane, h);
+        else
+            agg_subtile_guarded<kApply, kCounts>(p, sub, lane, h);
+    }
 }
 
 // ---------------------------------------------------------------- apply from counts
@@ -441,23 +532,29 @@ __global__ __launch_bounds__(kBlock) void apply_kernel(Addr addr, Hyper h)
         return;
     const int lane = threadIdx.x & 63;
     Problem p;
-    const int64_t t = addr.resolve(tile, p);
-    const bool vec = (t + 1) * kTile <= p.numel && is_aligned(p.x, 16) && is_aligned(p.counts, 8);
-    if (vec) {
-        const int64_t j0 = t * kTile + lane * kVec;
-        const u16x4 c = *reinterpret_cast<const u16x4 *>(p.counts + j0);
-        f32x4 xv = *reinterpret_cast<const f32x4 *>(p.x + j0);
-        xv.x = lion_apply(xv.x, aggregate_votes(c.x, h), h);
-        xv.y = lion_apply(xv.y, aggregate_votes(c.y, h), h);
-        xv.z = lion_apply(xv.z, aggregate_votes(c.z, h), h);
-        xv.w = lion_apply(xv.w, aggregate_votes(c.w, h), h);
-        *reinterpret_cast<f32x4 *>(p.x + j0) = xv;
-    } else {
+    const int64_t t = addr.resolve(tile, p) * kSubs;
+    const bool aligned = is_aligned(p.x, 16) && is_aligned(p.counts, 8);
 #pragma unroll 1
-        for (int k = 0; k < kWordsPerTile; ++k) {
-            const int64_t j = (t * kWordsPerTile + k) * 64 + lane;
-            if (j < p.numel)
-                p.x[j] = lion_apply(p.x[j], aggregate_votes(p.counts[j], h), h);
+    for (int r = 0; r < kSubs; ++r) {
+        const int64_t sub = t + r;
+        if (sub * kSubTile >= p.numel)
+            break;
+        if (aligned && (sub + 1) * kSubTile <= p.numel) {
+            const int64_t j0 = sub * kSubTile + lane * kVec;
+            const u16x4 c = *reinterpret_cast<const u16x4 *>(p.counts + j0);
+            f32x4 xv = *reinterpret_cast<const f32x4 *>(p.x + j0);
+            xv.x = lion_apply(xv.x, aggregate_votes(c.x, h), h);
+            xv.y = lion_apply(xv.y, aggregate_votes(c.y, h), h);
+            xv.z = lion_apply(xv.z, aggregate_votes(c.z, h), h);
+            xv.w = lion_apply(xv.w, aggregate_votes(c.w, h), h);
+            *reinterpret_cast<f32x4 *>(p.x + j0) = xv;
+        } else {
+#pragma unroll 1
+            for (int k = 0; k < kWordsPerSub; ++k) {
+                const int64_t j = (sub * kWordsPerSub + k) * 64 + lane;
+                if (j < p.numel)
+                    p.x[j] = lion_apply(p.x[j], aggregate_votes(p.counts[j], h), h);
+            }
         }
     }
 }
