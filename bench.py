@@ -60,12 +60,20 @@ def cpu_baseline(w, x, m, g, seconds_target: float = 15.0):
 
 
 def recorded_traffic(workload: str):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one for this workload."""
-    path = os.path.join(ROOT, "profiles", "traffic.json")
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload, if there is one.
+
+    The counters cannot be read from inside this process; the figure is the one
+    measured with ``rocprofv3 --pmc FETCH_SIZE`` / ``WRITE_SIZE`` over this very
+    script and written into ``profiles/dlion_step_<workload>.md``.
+    """
+    import re
+
+    path = os.path.join(ROOT, "profiles", f"dlion_step_{workload}.md")
     try:
         with open(path) as f:
-            return json.load(f).get(workload, {}).get("bytes_per_launch")
-    except (OSError, ValueError):
+            m = re.search(r"traffic_bytes_per_launch:\s*(\d+)", f.read())
+        return int(m.group(1)) if m else None
+    except OSError:
         return None
 
 
@@ -76,6 +84,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="gpt2s_avg8")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain device copy of known size (1 GiB in, 1 GiB out, 5 times) so that "
+                         "hardware counters collected over this run can be scaled against it")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -154,6 +165,13 @@ def main() -> int:
             "bytes_per_update": bytes_per_launch / (w.d * w.N),
         },
     }
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_calibration"] = {"bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "launches": 5}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, x, m, g)
     print(json.dumps(out), flush=True)
