@@ -1,0 +1,208 @@
+"""GPU parity at the full sizes of the stated workloads, in the launch configuration bench.py times.
+
+The CPU oracle cannot run 10^9..10^10 updates per step in seconds, but every
+coordinate is independent of every other (apart from sharing a 64-bit packed
+word with its neighbours), so the oracle is run on SAMPLED word-aligned chunks
+of the full problem -- always including the first words and the ragged end --
+fed with the very same initial state and gradients the GPU sees, step after
+step.  Whole-array properties that hold at any size complete the check.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2404_00438_amd as dl
+from paper_2404_00438_amd import workloads as wl
+from helpers import assert_f32_equal, to_np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+CHUNK = 2048            # coordinates per sampled chunk (32 packed words)
+
+
+def announce(*what):
+    print("[case]", *what, flush=True)
+
+
+def sample_chunks(d: int, n_chunks: int, seed: int):
+    """Word-aligned [start, stop) ranges: the first chunk, random ones, and the one ending at d."""
+    rng = np.random.default_rng(seed)
+    W = (d + 63) // 64
+    words_per_chunk = CHUNK // 64
+    starts = {0}
+    while len(starts) < n_chunks - 1:
+        starts.add(int(rng.integers(0, max(1, W - words_per_chunk))) * 64)
+    ranges = sorted((s, min(s + CHUNK, d)) for s in starts)
+    last_start = max(0, (W - words_per_chunk)) * 64
+    ranges = [r for r in ranges if r[1] <= last_start] + [(last_start, d)]   # ragged end goes last
+    return ranges
+
+
+def gather(t: torch.Tensor, ranges) -> torch.Tensor:
+    """Concatenate the sampled coordinate ranges along the last axis."""
+    return torch.cat([t[..., a:b] for a, b in ranges], dim=-1).contiguous()
+
+
+def gather_words(t: torch.Tensor, ranges) -> torch.Tensor:
+    return torch.cat([t[..., a // 64:(b + 63) // 64] for a, b in ranges], dim=-1).contiguous()
+
+
+def popcount64_total(t: torch.Tensor) -> int:
+    """Total number of set bits of an int64 tensor (SWAR, row by row to bound temporaries)."""
+    total = 0
+    flat = t.reshape(-1)
+    step = 1 << 26
+    for i in range(0, flat.numel(), step):
+        v = flat[i:i + step].clone()
+        lo = (v & 0xFFFFFFFF)
+        hi = (v >> 32) & 0xFFFFFFFF
+        for h in (lo, hi):
+            h = h - ((h >> 1) & 0x55555555)
+            h = (h & 0x33333333) + ((h >> 2) & 0x33333333)
+            h = (h + (h >> 4)) & 0x0F0F0F0F
+            h = (h * 0x01010101 >> 24) & 0xFF
+            total += int(h.sum().item())
+    return total
+
+
+def run_flat_workload(w: wl.Workload, n_chunks: int = 24, steps=None):
+    steps = w.steps if steps is None else steps
+    d, N = w.d, w.N
+    announce(w.name, "d", d, "N", N, "mode", w.mode, "steps", steps)
+    ranges = sample_chunks(d, n_chunks, seed=d % 9973)
+    x = wl.init_x(w, DEV)
+    m = wl.init_m(w, DEV)
+    g = torch.empty((N, d), dtype=w.g_dtype, device=DEV)
+    xh, mh = to_np(gather(x, ranges)), to_np(gather(m, ranges))
+    W = dl.words_for(d)
+    exact = True
+    for t in range(steps):
+        wl.make_grads(w, t, DEV, out=g)
+        gh = to_np(gather(g, ranges))
+        ph, ch = oracle.step(xh, mh, gh, w.mode, w.beta1, w.beta2, w.lr, w.lam)
+        last = t == steps - 1
+        if last:
+            # the instrumented variant on the last step: packed words and counts at full size
+            packed = torch.empty((N, W), dtype=torch.int64, device=DEV)
+            counts = torch.empty(d, dtype=torch.int16, device=DEV)
+            dl.dlion_step(x, m, g, w.mode, w.beta1, w.beta2, w.lr, w.lam, packed=packed, counts=counts)
+        else:
+            # exactly what bench.py launches
+            dl.dlion_step(x, m, g, w.mode, w.beta1, w.beta2, w.lr, w.lam)
+        torch.cuda.synchronize()
+        exact &= assert_f32_equal(to_np(gather(m, ranges)), mh, f"{w.name} step {t}: m")
+        exact &= assert_f32_equal(to_np(gather(x, ranges)), xh, f"{w.name} step {t}: x")
+        print(f"  step {t} ok", flush=True)
+    assert np.array_equal(to_np(gather_words(packed, ranges)), ph), f"{w.name}: packed words differ"
+    assert np.array_equal(to_np(gather(counts, ranges)), ch), f"{w.name}: counts differ"
+    # properties of the whole arrays
+    c32 = counts.to(torch.int32) & 0xFFFF
+    assert int(c32.max().item()) <= N and int(c32.min().item()) >= 0
+    assert popcount64_total(packed) == int(c32.sum(dtype=torch.int64).item())
+    tail = d - 64 * (W - 1)
+    if tail < 64:
+        assert int(((packed[:, W - 1] >> tail) != 0).sum().item()) == 0, "bits past d must be zero"
+    assert bool(torch.isfinite(x).all()) and bool(torch.isfinite(m).all())
+    print(f"{w.name}: sampled {sum(b - a for a, b in ranges)} coordinates per step, "
+          f"fp32 state bit-identical: {exact}", flush=True)
+    del packed, counts, g, m, x
+    torch.cuda.empty_cache()
+
+
+def test_gpt2_small_avg8_full_size():
+    """Benchmark workload: d = 124 M flat, N = 8, averaging, bf16 Student-t gradients, 20 steps."""
+    run_flat_workload(wl.CONFIGS["gpt2s_avg8"])
+
+
+def test_gpt350m_32_workers_vote_then_avg_full_size():
+    """d = 350 M, N = 32, bf16 gradients with outliers: majority vote, then averaging on the same gradients."""
+    run_flat_workload(wl.CONFIGS["gpt350m_vote32"])
+    run_flat_workload(wl.CONFIGS["gpt350m_avg32"])
+
+
+def test_stress_1p3b_full_size():
+    """d = 1.3 B, N = 8: offsets beyond 2^32 bytes within one stream and 2^33 elements overall."""
+    run_flat_workload(wl.CONFIGS["stress1p3b_vote8"], steps=3)
+
+
+def test_vit_b16_tensor_list_full_size():
+    """ViT-B/16-shaped list of 148 tensors, N = 16, majority vote, fp32 gradients, 10 steps."""
+    w = wl.CONFIGS["vitb16_vote16"]
+    numels = w.numels()
+    N = w.N
+    announce(w.name, "tensors", len(numels), "d", w.d, "N", N)
+    xs = [wl.init_x(w, DEV, tensor=k) for k in range(len(numels))]
+    ms = [wl.init_m(w, DEV, numel=n) for n in numels]
+    gs = [torch.empty((N, n), dtype=w.g_dtype, device=DEV) for n in numels]
+    table = dl.SegTable(xs, ms, gs)
+    Wt = table.total_words
+    # every small tensor in full, and sampled chunks of the big ones
+    rng = np.random.default_rng(3)
+    picks = []
+    for k, n in enumerate(numels):
+        if n <= 4096:
+            picks.append((k, 0, n))
+        elif rng.random() < 0.25:
+            s = int(rng.integers(0, (n - CHUNK) // 64)) * 64
+            picks.append((k, s, s + CHUNK))
+            picks.append((k, n - CHUNK, n))
+    xh = [to_np(xs[k][a:b]) for k, a, b in picks]
+    mh = [to_np(ms[k][:, a:b]) for k, a, b in picks]
+    exact = True
+    for t in range(w.steps):
+        for k in range(len(numels)):
+            wl.make_grads(w, t, DEV, tensor=k, out=gs[k])
+        gh = [to_np(gs[k][:, a:b]) for k, a, b in picks]
+        ph, ch = oracle.step_mt(xh, mh, gh, w.mode, w.beta1, w.beta2, w.lr, w.lam)
+        last = t == w.steps - 1
+        if last:
+            packed = torch.empty((N, Wt), dtype=torch.int64, device=DEV)
+            counts = torch.empty(64 * Wt, dtype=torch.int16, device=DEV)
+            dl.dlion_step_mt(table, N, w.mode, w.beta1, w.beta2, w.lr, w.lam, packed=packed, counts=counts)
+        else:
+            dl.dlion_step_mt(table, N, w.mode, w.beta1, w.beta2, w.lr, w.lam)
+        torch.cuda.synchronize()
+        for i, (k, a, b) in enumerate(picks):
+            exact &= assert_f32_equal(to_np(ms[k][:, a:b]), mh[i], f"step {t} tensor {k}: m")
+            exact &= assert_f32_equal(to_np(xs[k][a:b]), xh[i], f"step {t} tensor {k}: x")
+        print(f"  step {t} ok", flush=True)
+    got_p = torch.cat([packed[:, table.word_begin[k] + a // 64: table.word_begin[k] + (b + 63) // 64]
+                       for k, a, b in picks], dim=1)
+    got_c = torch.cat([counts[64 * table.word_begin[k] + a: 64 * table.word_begin[k] + b] for k, a, b in picks])
+    assert np.array_equal(to_np(got_p), ph)
+    assert np.array_equal(to_np(got_c), ch)
+    c32 = counts.to(torch.int32) & 0xFFFF
+    assert int(c32.max().item()) <= N
+    assert popcount64_total(packed) == int(c32.sum(dtype=torch.int64).item())
+    print(f"{w.name}: {len(picks)} sampled ranges, fp32 state bit-identical: {exact}", flush=True)
+
+
+def test_vote_only_256_streams_full_size():
+    """Vote-only pass over N = 256 pre-packed random sign streams at d = 1.0 B."""
+    w = wl.CONFIGS["packed256_1b"]
+    d, N = w.d, w.N
+    W = dl.words_for(d)
+    announce(w.name, "d", d, "N", N, "W", W)
+    packed = wl.random_packed(N, W, DEV, seed=w.seed)
+    counts = torch.empty(d, dtype=torch.int16, device=DEV)
+    dl.dlion_aggregate(packed, d, counts)
+    torch.cuda.synchronize()
+    ranges = sample_chunks(d, 16, seed=11)
+    ph = to_np(gather_words(packed, ranges))
+    want = oracle.aggregate_packed(ph, ph.shape[1] * 64)
+    assert np.array_equal(to_np(gather(counts, ranges)), want)
+    c32 = counts.to(torch.int32) & 0xFFFF
+    assert int(c32.max().item()) <= N
+    assert popcount64_total(packed) == int(c32.sum(dtype=torch.int64).item())
+    # fused vote + apply on weights, both modes, against the oracle on the same chunks
+    for mode in (dl.VOTE, dl.AVG):
+        x = wl.init_x(w, DEV)
+        xh = to_np(gather(x, ranges))
+        oracle.apply(xh, want, N, mode, w.lr, w.lam)
+        dl.dlion_aggregate_apply(x, packed, mode, w.lr, w.lam)
+        torch.cuda.synchronize()
+        assert_f32_equal(to_np(gather(x, ranges)), xh, f"aggregate_apply mode {mode}: x")
+        del x
+    print(f"{w.name}: counts bit-exact on {sum(b - a for a, b in ranges)} sampled coordinates; "
+          f"sum(counts) equals the popcount of all {N * W} words", flush=True)
