@@ -143,6 +143,47 @@ dlion_status launch_aggregate(const Addr &addr, const Hyper &h, bool apply, bool
     return launched();
 }
 
+// Bit-sliced counting for many workers (flat buffers): planes = bits needed for a count 0..N.
+template <int kPlanes>
+dlion_status launch_sliced_planes(const FlatAddr &addr, const Hyper &h, bool apply, bool counts, size_t lds,
+                                  hipStream_t s)
+{
+    const int64_t W = words_for(addr.p.numel);
+    const dim3 grid(static_cast<uint32_t>((W + kSlicedWords - 1) / kSlicedWords)), block(kLanes);
+    if (apply && counts)
+        hipLaunchKernelGGL((aggregate_sliced_kernel<kPlanes, true, true>), grid, block, lds, s, addr, h);
+    else if (apply)
+        hipLaunchKernelGGL((aggregate_sliced_kernel<kPlanes, true, false>), grid, block, lds, s, addr, h);
+    else
+        hipLaunchKernelGGL((aggregate_sliced_kernel<kPlanes, false, true>), grid, block, lds, s, addr, h);
+    return launched();
+}
+
+constexpr int kSlicedMinWorkers = 16;   // below this the per-nibble kernel is cheaper
+
+inline bool use_sliced(int32_t N)
+{
+    static const int env_min = env_int("DLION_SLICED_MIN_WORKERS");
+    return N >= (env_min >= 0 ? env_min : kSlicedMinWorkers);
+}
+
+dlion_status launch_sliced(const FlatAddr &addr, const Hyper &h, bool apply, bool counts, hipStream_t s)
+{
+    static const int env_blocks = env_int("DLION_SLICED_BLOCKS_PER_CU");
+    const int blocks = env_blocks >= 0 ? env_blocks : 6;
+    // the kernel's own LDS (planes x 512 B) counts towards the reservation
+    const size_t lds = lds_reservation(blocks);
+    if (h.N < 32)
+        return launch_sliced_planes<5>(addr, h, apply, counts, lds > 5 * 512 ? lds - 5 * 512 : 0, s);
+    if (h.N < 128)
+        return launch_sliced_planes<7>(addr, h, apply, counts, lds > 7 * 512 ? lds - 7 * 512 : 0, s);
+    if (h.N < 512)
+        return launch_sliced_planes<9>(addr, h, apply, counts, lds > 9 * 512 ? lds - 9 * 512 : 0, s);
+    if (h.N < 4096)
+        return launch_sliced_planes<12>(addr, h, apply, counts, lds > 12 * 512 ? lds - 12 * 512 : 0, s);
+    return launch_sliced_planes<16>(addr, h, apply, counts, lds > 16 * 512 ? lds - 16 * 512 : 0, s);
+}
+
 template <class Addr> dlion_status launch_apply(const Addr &addr, const Hyper &h, hipStream_t s)
 {
     hipLaunchKernelGGL((apply_kernel<Addr>), grid_for(addr.total_tiles), dim3(kBlock), 0, s, addr, h);
@@ -280,6 +321,8 @@ dlion_status dlion_aggregate(const uint64_t *packed, int64_t packed_stride, int6
     const Hyper h = make_hyper(N, DLION_VOTE, 0.0f, 0.0f, 0.0f, 0.0f);
     const FlatAddr a = flat_addr(nullptr, nullptr, 0, nullptr, 0, d, const_cast<uint64_t *>(packed),
                                  packed_stride, counts);
+    if (use_sliced(N))
+        return launch_sliced(a, h, false, true, static_cast<hipStream_t>(stream));
     return launch_aggregate(a, h, false, true, static_cast<hipStream_t>(stream));
 }
 
@@ -309,6 +352,8 @@ dlion_status dlion_aggregate_apply(float *x, const uint64_t *packed, int64_t pac
     const Hyper h = make_hyper(N, mode, 0.0f, 0.0f, lr, lambda);
     const FlatAddr a = flat_addr(x, nullptr, 0, nullptr, 0, d, const_cast<uint64_t *>(packed), packed_stride,
                                  counts_or_null);
+    if (use_sliced(N))
+        return launch_sliced(a, h, true, counts_or_null != nullptr, static_cast<hipStream_t>(stream));
     return launch_aggregate(a, h, true, counts_or_null != nullptr, static_cast<hipStream_t>(stream));
 }
 

@@ -523,6 +523,146 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(Addr addr, Hyper h)
     }
 }
 
+// ---------------------------------------------------------------- server side, many workers
+// Bit-sliced ("vertical") counting for large N.  One wave owns 64 consecutive packed words
+// (4096 coordinates); lane l reads word l of every stream (512 contiguous bytes per load
+// instruction) and adds the N words into kPlanes bit-planes with carry-save adders: after the
+// loop, bit c of plane b in lane l is bit b of the vote count of coordinate 64*l + c.  About
+// 7 bitwise operations per input word replace 64 extract-and-add steps.  The planes are then
+// staged through LDS so that the lanes can switch from "one word each" to "four consecutive
+// coordinates each" and write counts / update x with full-width accesses.
+__device__ __forceinline__ void csa(uint64_t &carry, uint64_t &sum, uint64_t a, uint64_t b, uint64_t c)
+{
+    const uint64_t u = a ^ b;
+    carry = (a & b) | (u & c);
+    sum = u ^ c;
+}
+
+constexpr int kSlicedWords = 64;                       // words per wave
+constexpr int kSlicedCoords = kSlicedWords * 64;       // 4096
+
+template <int kPlanes, bool kApply, bool kCounts>
+__global__ __launch_bounds__(kLanes) void aggregate_sliced_kernel(FlatAddr addr, Hyper h)
+{
+    static_assert(kPlanes >= 5 && kPlanes <= 16, "planes");
+    __shared__ uint32_t lds[kPlanes][2 * kSlicedWords];
+    const Problem &p = addr.p;
+    const int lane = threadIdx.x;
+    const int64_t W = (p.numel + 63) >> 6;
+    const int64_t w0 = (int64_t)blockIdx.x * kSlicedWords;
+    const bool have = w0 + lane < W;
+    const uint64_t *src = p.packed + (have ? w0 + lane : 0);   // an in-bounds address also when idle
+    const int N = h.N;
+
+    uint64_t ones = 0, twos = 0, fours = 0, eights = 0;
+    uint64_t hi[kPlanes - 4];                                   // planes 4.. (sixteens and up)
+#pragma unroll
+    for (int b = 0; b < kPlanes - 4; ++b)
+        hi[b] = 0;
+
+    for (int i = 0; i < N; i += 16) {
+        uint64_t v[16];
+        if (i + 16 <= N) {
+#pragma unroll
+            for (int k = 0; k < 16; ++k)
+                v[k] = have ? stream_load(src + (int64_t)(i + k) * p.packed_stride) : 0;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 16; ++k)
+                v[k] = (have && i + k < N) ? stream_load(src + (int64_t)(i + k) * p.packed_stride) : 0;
+        }
+        uint64_t t0, t1, t2, t3, t4, t5, t6, t7, f0, f1, f2, f3, e0, e1, s16;
+        csa(t0, ones, ones, v[0], v[1]);
+        csa(t1, ones, ones, v[2], v[3]);
+        csa(t2, ones, ones, v[4], v[5]);
+        csa(t3, ones, ones, v[6], v[7]);
+        csa(t4, ones, ones, v[8], v[9]);
+        csa(t5, ones, ones, v[10], v[11]);
+        csa(t6, ones, ones, v[12], v[13]);
+        csa(t7, ones, ones, v[14], v[15]);
+        csa(f0, twos, twos, t0, t1);
+        csa(f1, twos, twos, t2, t3);
+        csa(f2, twos, twos, t4, t5);
+        csa(f3, twos, twos, t6, t7);
+        csa(e0, fours, fours, f0, f1);
+        csa(e1, fours, fours, f2, f3);
+        csa(s16, eights, eights, e0, e1);
+        // ripple the weight-16 carry into the upper planes
+#pragma unroll
+        for (int b = 0; b < kPlanes - 4; ++b) {
+            const uint64_t c = hi[b] & s16;
+            hi[b] ^= s16;
+            s16 = c;
+        }
+    }
+
+    // stage: lds[b][2*l], lds[b][2*l+1] = low / high dword of plane b of word l
+    auto put = [&](int b, uint64_t plane) {
+        lds[b][2 * lane] = static_cast<uint32_t>(plane);
+        lds[b][2 * lane + 1] = static_cast<uint32_t>(plane >> 32);
+    };
+    put(0, ones);
+    put(1, twos);
+    put(2, fours);
+    put(3, eights);
+#pragma unroll
+    for (int b = 0; b < kPlanes - 4; ++b)
+        put(4 + b, hi[b]);
+    __syncthreads();
+
+    const bool vec_x = !kApply || is_aligned(p.x, 16);
+    const bool vec_c = !kCounts || is_aligned(p.counts, 8);
+    // now lane l owns coordinates 4*(l&15).. of word 4*s + (l>>4), s = 0..15
+#pragma unroll 1
+    for (int s = 0; s < kSlicedWords / kWordsPerSub; ++s) {
+        const int wl = s * kWordsPerSub + (lane >> 4);          // word within the group
+        const int64_t j0 = (w0 + wl) * 64 + (lane & 15) * kVec;
+        if (j0 >= p.numel)
+            continue;
+        const int dword = 2 * wl + ((lane >> 3) & 1);
+        const int shift = (lane & 7) * 4;
+        uint32_t c01 = 0, c23 = 0;                               // two 16-bit counters each
+#pragma unroll
+        for (int b = 0; b < kPlanes; ++b) {
+            const uint32_t nib = (lds[b][dword] >> shift) & 0xFu;
+            c01 += ((nib & 1u) | ((nib & 2u) << 15)) << b;
+            c23 += (((nib >> 2) & 1u) | ((nib & 8u) << 13)) << b;
+        }
+        const uint32_t cnt[4] = {c01 & 0xFFFFu, c01 >> 16, c23 & 0xFFFFu, c23 >> 16};
+        const bool full = j0 + kVec <= p.numel;
+        if (kApply) {
+            if (full && vec_x) {
+                f32x4 xv = *reinterpret_cast<const f32x4 *>(p.x + j0);
+                xv.x = lion_apply(xv.x, aggregate_votes(cnt[0], h), h);
+                xv.y = lion_apply(xv.y, aggregate_votes(cnt[1], h), h);
+                xv.z = lion_apply(xv.z, aggregate_votes(cnt[2], h), h);
+                xv.w = lion_apply(xv.w, aggregate_votes(cnt[3], h), h);
+                *reinterpret_cast<f32x4 *>(p.x + j0) = xv;
+            } else {
+#pragma unroll
+                for (int k = 0; k < kVec; ++k)
+                    if (j0 + k < p.numel)
+                        p.x[j0 + k] = lion_apply(p.x[j0 + k], aggregate_votes(cnt[k], h), h);
+            }
+        }
+        if (kCounts) {
+            if (full && vec_c) {
+                u16x4 c;
+                c.x = static_cast<uint16_t>(cnt[0]);
+                c.y = static_cast<uint16_t>(cnt[1]);
+                c.z = static_cast<uint16_t>(cnt[2]);
+                c.w = static_cast<uint16_t>(cnt[3]);
+                *reinterpret_cast<u16x4 *>(p.counts + j0) = c;
+            } else {
+#pragma unroll
+                for (int k = 0; k < kVec; ++k)
+                    if (j0 + k < p.numel)
+                        p.counts[j0 + k] = static_cast<uint16_t>(cnt[k]);
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------- apply from counts
 template <class Addr>
 __global__ __launch_bounds__(kBlock) void apply_kernel(Addr addr, Hyper h)

@@ -290,3 +290,45 @@ def test_tiny_config_full_run():
         # last word: only 3 valid bits
         assert (to_np(packed)[:, -1] >> np.uint64(3) == 0).all()
         print("tiny: bit-identical fp32 state:", exact, flush=True)
+
+
+def test_many_worker_aggregate_matches_oracle():
+    """The bit-sliced server-side kernel (many workers): counts bit-exact, apply within the bar."""
+    rng = np.random.default_rng(2024)
+    cases = [(16, 4096), (17, 4097), (31, 1), (32, 63), (33, 10_000), (64, 8192 + 5), (127, 4095),
+             (128, 70_001), (255, 5000), (256, 12_345), (257, 4096 * 3), (511, 300), (512, 4096),
+             (1000, 9000), (4095, 700), (4096, 130), (5000, 4100), (65535, 130)]
+    for N, d in cases:
+        W = dl.words_for(d)
+        for p_one, pad in ((0.5, 0), (0.9, 3), (1.0, 1)):
+            announce("sliced", "N", N, "d", d, "p", p_one, "row pad", pad)
+            if p_one == 1.0:
+                words = np.full((N, W), np.uint64(0xFFFFFFFFFFFFFFFF))
+            else:
+                bits = rng.random((N, W * 64)) < p_one
+                words = np.packbits(bits, axis=1, bitorder="little").view("<u8")
+            tail = d - 64 * (W - 1)
+            if tail < 64:
+                words[:, W - 1] &= np.uint64((1 << tail) - 1)
+            packed = strided_rows(N, W, W + pad, torch.int64, DEV)
+            packed.copy_(torch.from_numpy(words.view(np.int64)))
+            want = oracle.aggregate_packed(np.ascontiguousarray(words), d)
+            counts = torch.full((d,), -1, dtype=torch.int16, device=DEV)
+            dl.dlion_aggregate(packed, d, counts)
+            torch.cuda.synchronize()
+            assert np.array_equal(to_np(counts), want), f"N={N} d={d}: counts"
+            for mode in (dl.VOTE, dl.AVG):
+                xv = rng.normal(0, 0.02, d).astype(np.float32)
+                # odd offset into a larger buffer: x not 16-byte aligned on every other case
+                off = 1 if (N + d) % 2 else 0
+                xbuf = torch.zeros(d + 1, dtype=torch.float32, device=DEV)
+                x = xbuf[off:off + d]
+                x.copy_(torch.from_numpy(xv))
+                xn = xv.copy()
+                oracle.apply(xn, want, N, mode, 0.25, 0.5)
+                counts2 = torch.full((d,), -1, dtype=torch.int16, device=DEV)
+                dl.dlion_aggregate_apply(x, packed, mode, 0.25, 0.5, counts=counts2 if mode == dl.AVG else None)
+                torch.cuda.synchronize()
+                assert_f32_equal(to_np(x), xn, f"N={N} d={d} mode={mode}: x")
+                if mode == dl.AVG:
+                    assert np.array_equal(to_np(counts2), want)
