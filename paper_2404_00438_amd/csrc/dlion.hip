@@ -31,8 +31,13 @@ Hyper make_hyper(int32_t N, int mode, float beta1, float beta2, float lr, float 
     h.inv_n = power_of_two(N) ? 1.0f / static_cast<float>(N) : 0.0f;
     h.N = N;
     h.mode = mode;
+    h.stream_counts = 0;
     return h;
 }
+
+// The memory-side cache holds 256 MB; a counts array (2 B per coordinate) well below that is
+// still there when the next call reads it.
+inline int32_t counts_exceed_cache(int64_t coords) { return coords * 2 > (int64_t)192 << 20; }
 
 inline dim3 grid_for(int64_t tiles) { return dim3(static_cast<uint32_t>((tiles + kWavesPerBlock - 1) / kWavesPerBlock)); }
 
@@ -159,7 +164,7 @@ dlion_status launch_sliced_planes(const FlatAddr &addr, const Hyper &h, bool app
     return launched();
 }
 
-constexpr int kSlicedMinWorkers = 16;   // below this the per-nibble kernel is cheaper
+constexpr int kSlicedMinWorkers = 8;    // below this the per-nibble kernel is cheaper
 
 inline bool use_sliced(int32_t N)
 {
@@ -170,18 +175,18 @@ inline bool use_sliced(int32_t N)
 dlion_status launch_sliced(const FlatAddr &addr, const Hyper &h, bool apply, bool counts, hipStream_t s)
 {
     static const int env_blocks = env_int("DLION_SLICED_BLOCKS_PER_CU");
-    const int blocks = env_blocks >= 0 ? env_blocks : 6;
+    const int blocks = env_blocks >= 0 ? env_blocks : 0;   // measured best: no cap
     // the kernel's own LDS (planes x 512 B) counts towards the reservation
     const size_t lds = lds_reservation(blocks);
     if (h.N < 32)
-        return launch_sliced_planes<5>(addr, h, apply, counts, lds > 5 * 512 ? lds - 5 * 512 : 0, s);
+        return launch_sliced_planes<5>(addr, h, apply, counts, lds > 5 * 8 * kSlicedWords ? lds - 5 * 8 * kSlicedWords : 0, s);
     if (h.N < 128)
-        return launch_sliced_planes<7>(addr, h, apply, counts, lds > 7 * 512 ? lds - 7 * 512 : 0, s);
+        return launch_sliced_planes<7>(addr, h, apply, counts, lds > 7 * 8 * kSlicedWords ? lds - 7 * 8 * kSlicedWords : 0, s);
     if (h.N < 512)
-        return launch_sliced_planes<9>(addr, h, apply, counts, lds > 9 * 512 ? lds - 9 * 512 : 0, s);
+        return launch_sliced_planes<9>(addr, h, apply, counts, lds > 9 * 8 * kSlicedWords ? lds - 9 * 8 * kSlicedWords : 0, s);
     if (h.N < 4096)
-        return launch_sliced_planes<12>(addr, h, apply, counts, lds > 12 * 512 ? lds - 12 * 512 : 0, s);
-    return launch_sliced_planes<16>(addr, h, apply, counts, lds > 16 * 512 ? lds - 16 * 512 : 0, s);
+        return launch_sliced_planes<12>(addr, h, apply, counts, lds > 12 * 8 * kSlicedWords ? lds - 12 * 8 * kSlicedWords : 0, s);
+    return launch_sliced_planes<16>(addr, h, apply, counts, lds > 16 * 8 * kSlicedWords ? lds - 16 * 8 * kSlicedWords : 0, s);
 }
 
 template <class Addr> dlion_status launch_apply(const Addr &addr, const Hyper &h, hipStream_t s)
@@ -318,7 +323,8 @@ dlion_status dlion_aggregate(const uint64_t *packed, int64_t packed_stride, int6
         return DLION_EINVAL;
     if (!aligned_to(counts, 2))
         return DLION_EALIGN;
-    const Hyper h = make_hyper(N, DLION_VOTE, 0.0f, 0.0f, 0.0f, 0.0f);
+    Hyper h = make_hyper(N, DLION_VOTE, 0.0f, 0.0f, 0.0f, 0.0f);
+    h.stream_counts = counts_exceed_cache(d);
     const FlatAddr a = flat_addr(nullptr, nullptr, 0, nullptr, 0, d, const_cast<uint64_t *>(packed),
                                  packed_stride, counts);
     if (use_sliced(N))
@@ -349,7 +355,8 @@ dlion_status dlion_aggregate_apply(float *x, const uint64_t *packed, int64_t pac
     DLION_TRY(check_rows(packed, packed_stride, words_for(d), N, 8));
     if (!aligned_to(x, 4) || !aligned_to(counts_or_null, 2))
         return DLION_EALIGN;
-    const Hyper h = make_hyper(N, mode, 0.0f, 0.0f, lr, lambda);
+    Hyper h = make_hyper(N, mode, 0.0f, 0.0f, lr, lambda);
+    h.stream_counts = counts_or_null ? counts_exceed_cache(d) : 0;
     const FlatAddr a = flat_addr(x, nullptr, 0, nullptr, 0, d, const_cast<uint64_t *>(packed), packed_stride,
                                  counts_or_null);
     if (use_sliced(N))
@@ -371,7 +378,8 @@ dlion_status dlion_step(float *x, float *m, int64_t m_stride, const void *g, int
     DLION_TRY(check_rows(g, g_stride, d, N, grad_size(g_dtype)));
     if (packed_or_null)
         DLION_TRY(check_rows(packed_or_null, packed_stride, words_for(d), N, 8));
-    const Hyper h = make_hyper(N, mode, beta1, beta2, lr, lambda);
+    Hyper h = make_hyper(N, mode, beta1, beta2, lr, lambda);
+    h.stream_counts = counts_or_null ? counts_exceed_cache(d) : 0;
     const FlatAddr a = flat_addr(x, m, m_stride, g, g_stride, d, packed_or_null, packed_stride, counts_or_null);
     return launch_step<true>(a, h, g_dtype, packed_or_null != nullptr, counts_or_null != nullptr,
                              static_cast<hipStream_t>(stream));
@@ -425,7 +433,8 @@ dlion_status dlion_aggregate_mt(const dlion_seg *segs_host, const dlion_seg *seg
         return DLION_EINVAL;
     if (!aligned_to(counts, 2))
         return DLION_EALIGN;
-    const Hyper h = make_hyper(N, DLION_VOTE, 0.0f, 0.0f, 0.0f, 0.0f);
+    Hyper h = make_hyper(N, DLION_VOTE, 0.0f, 0.0f, 0.0f, 0.0f);
+    h.stream_counts = counts_exceed_cache(64 * words);
     const SegAddr a = seg_addr(segs_dev, K, tiles, const_cast<uint64_t *>(packed), packed_stride, counts);
     return launch_aggregate(a, h, false, true, static_cast<hipStream_t>(stream));
 }
@@ -457,7 +466,8 @@ dlion_status dlion_aggregate_apply_mt(const dlion_seg *segs_host, const dlion_se
     int64_t words, tiles;
     DLION_TRY(check_segs(segs_host, segs_dev, K, N, kNeedX, DLION_F32, &words, &tiles));
     DLION_TRY(check_rows(packed, packed_stride, words, N, 8));
-    const Hyper h = make_hyper(N, mode, 0.0f, 0.0f, lr, lambda);
+    Hyper h = make_hyper(N, mode, 0.0f, 0.0f, lr, lambda);
+    h.stream_counts = counts_or_null ? counts_exceed_cache(64 * words) : 0;
     const SegAddr a = seg_addr(segs_dev, K, tiles, const_cast<uint64_t *>(packed), packed_stride, counts_or_null);
     return launch_aggregate(a, h, true, counts_or_null != nullptr, static_cast<hipStream_t>(stream));
 }
@@ -475,7 +485,8 @@ dlion_status dlion_step_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev
     DLION_TRY(check_segs(segs_host, segs_dev, K, N, kNeedX | kNeedM | kNeedG, g_dtype, &words, &tiles));
     if (packed_or_null)
         DLION_TRY(check_rows(packed_or_null, packed_stride, words, N, 8));
-    const Hyper h = make_hyper(N, mode, beta1, beta2, lr, lambda);
+    Hyper h = make_hyper(N, mode, beta1, beta2, lr, lambda);
+    h.stream_counts = counts_or_null ? counts_exceed_cache(64 * words) : 0;
     const SegAddr a = seg_addr(segs_dev, K, tiles, packed_or_null, packed_stride, counts_or_null);
     return launch_step<true>(a, h, g_dtype, packed_or_null != nullptr, counts_or_null != nullptr,
                              static_cast<hipStream_t>(stream));

@@ -73,6 +73,7 @@ struct Hyper {
     float inv_n;      // 1/N when N is a power of two (then S*inv_n == S/N exactly), else 0
     int32_t N;
     int32_t mode;     // dlion_mode
+    int32_t stream_counts;   // counts array too large to stay cached: write it with streaming stores
 };
 
 // One flat problem as a tile sees it.
@@ -150,6 +151,29 @@ __device__ __forceinline__ int64_t wave_tile_index()
 #endif
     return (int64_t)block * kWavesPerBlock + wave;
 }
+
+// Cache policy of the small per-coordinate arrays.  x is touched once per step: streaming
+// (non-temporal) accesses, +14 % on the apply kernel.  counts written by one call are read by
+// the next (aggregate -> apply) and up to ~250 MB of them stay in the memory-side cache, so
+// they use ordinary accesses unless the array is too large for that (h.stream_counts).
+#ifndef DLION_NT_X
+#define DLION_NT_X 1
+#endif
+#define C_STORE(v, p)                              \
+    do {                                           \
+        if (h.stream_counts)                       \
+            __builtin_nontemporal_store(v, p);     \
+        else                                       \
+            *(p) = (v);                            \
+    } while (0)
+#define C_LOAD(p) (*(p))
+#if DLION_NT_X
+#define X_STORE(v, p) __builtin_nontemporal_store(v, p)
+#define X_LOAD(p) __builtin_nontemporal_load(p)
+#else
+#define X_STORE(v, p) (*(p) = (v))
+#define X_LOAD(p) (*(p))
+#endif
 
 template <typename T> __device__ __forceinline__ T stream_load(const T *p)
 {
@@ -268,7 +292,7 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
     if (kApply) {
 #pragma unroll
         for (int r = 0; r < kR; ++r)
-            xv[r] = *reinterpret_cast<const f32x4 *>(p.x + j0 + r * kSubTile);
+            xv[r] = X_LOAD(reinterpret_cast<const f32x4 *>(p.x + j0 + r * kSubTile));
     }
     uint32_t cnt[kR][4];
 #pragma unroll
@@ -337,7 +361,7 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
             xv[r].y = lion_apply(xv[r].y, aggregate_votes(cnt[r][1], h), h);
             xv[r].z = lion_apply(xv[r].z, aggregate_votes(cnt[r][2], h), h);
             xv[r].w = lion_apply(xv[r].w, aggregate_votes(cnt[r][3], h), h);
-            *reinterpret_cast<f32x4 *>(p.x + j0 + r * kSubTile) = xv[r];
+            X_STORE(xv[r], reinterpret_cast<f32x4 *>(p.x + j0 + r * kSubTile));
         }
         if (kCounts) {
             u16x4 c;
@@ -345,7 +369,7 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
             c.y = static_cast<uint16_t>(cnt[r][1]);
             c.z = static_cast<uint16_t>(cnt[r][2]);
             c.w = static_cast<uint16_t>(cnt[r][3]);
-            *reinterpret_cast<u16x4 *>(p.counts + j0 + r * kSubTile) = c;
+            C_STORE(c, reinterpret_cast<u16x4 *>(p.counts + j0 + r * kSubTile));
         }
     }
 }
@@ -419,6 +443,12 @@ __global__ __launch_bounds__(kBlock) DLION_OCCUPANCY void step_kernel(Addr addr,
     }
 }
 
+// A nibble's four bits, one per byte (bit 0 of each byte): 24-bit multiply, full rate.
+__device__ __forceinline__ uint32_t nibble_to_bytes(uint32_t nib)
+{
+    return __umul24(nib, 0x00204081u) & 0x01010101u;
+}
+
 // ---------------------------------------------------------------- server side from packed words
 // Vector path: lane l owns coordinates 4l..4l+3 = nibble (l & 15) of word (l >> 4) of the
 // tile.  Votes are accumulated four at a time in the bytes of one register (a nibble is
@@ -440,13 +470,13 @@ __device__ __forceinline__ void agg_subtile_vector(const Problem &p, int64_t t, 
             uint32_t v[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u)
-                v[u] = half[(int64_t)(i + u) * stride32];
+                v[u] = stream_load(half + (int64_t)(i + u) * stride32);
 #pragma unroll
             for (int u = 0; u < 8; ++u)
-                acc += (((v[u] >> shift) & 0xFu) * 0x00204081u) & 0x01010101u;
+                acc += nibble_to_bytes((v[u] >> shift) & 0xFu);
         }
         for (; i < end; ++i)
-            acc += (((half[(int64_t)i * stride32] >> shift) & 0xFu) * 0x00204081u) & 0x01010101u;
+            acc += nibble_to_bytes((stream_load(half + (int64_t)i * stride32) >> shift) & 0xFu);
         cnt0 += acc & 0xFFu;
         cnt1 += (acc >> 8) & 0xFFu;
         cnt2 += (acc >> 16) & 0xFFu;
@@ -454,12 +484,12 @@ __device__ __forceinline__ void agg_subtile_vector(const Problem &p, int64_t t, 
     }
     const int64_t j0 = t * kSubTile + lane * kVec;
     if (kApply) {
-        f32x4 xv = *reinterpret_cast<const f32x4 *>(p.x + j0);
+        f32x4 xv = X_LOAD(reinterpret_cast<const f32x4 *>(p.x + j0));
         xv.x = lion_apply(xv.x, aggregate_votes(cnt0, h), h);
         xv.y = lion_apply(xv.y, aggregate_votes(cnt1, h), h);
         xv.z = lion_apply(xv.z, aggregate_votes(cnt2, h), h);
         xv.w = lion_apply(xv.w, aggregate_votes(cnt3, h), h);
-        *reinterpret_cast<f32x4 *>(p.x + j0) = xv;
+        X_STORE(xv, reinterpret_cast<f32x4 *>(p.x + j0));
     }
     if (kCounts) {
         u16x4 c;
@@ -467,7 +497,7 @@ __device__ __forceinline__ void agg_subtile_vector(const Problem &p, int64_t t, 
         c.y = static_cast<uint16_t>(cnt1);
         c.z = static_cast<uint16_t>(cnt2);
         c.w = static_cast<uint16_t>(cnt3);
-        *reinterpret_cast<u16x4 *>(p.counts + j0) = c;
+        C_STORE(c, reinterpret_cast<u16x4 *>(p.counts + j0));
     }
 }
 
@@ -524,96 +554,136 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(Addr addr, Hyper h)
 }
 
 // ---------------------------------------------------------------- server side, many workers
-// Bit-sliced ("vertical") counting for large N.  One wave owns 64 consecutive packed words
-// (4096 coordinates); lane l reads word l of every stream (512 contiguous bytes per load
-// instruction) and adds the N words into kPlanes bit-planes with carry-save adders: after the
-// loop, bit c of plane b in lane l is bit b of the vote count of coordinate 64*l + c.  About
-// 7 bitwise operations per input word replace 64 extract-and-add steps.  The planes are then
-// staged through LDS so that the lanes can switch from "one word each" to "four consecutive
-// coordinates each" and write counts / update x with full-width accesses.
-__device__ __forceinline__ void csa(uint64_t &carry, uint64_t &sum, uint64_t a, uint64_t b, uint64_t c)
-{
-    const uint64_t u = a ^ b;
-    carry = (a & b) | (u & c);
-    sum = u ^ c;
-}
+// Bit-sliced ("vertical") counting.  One wave owns kSlicedWords consecutive packed words;
+// lane l reads kWpl consecutive words of every stream (1 KB contiguous per load instruction)
+// and adds the N words into kPlanes bit-planes with carry-save adders: after the loop, bit c
+// of plane b of a word is bit b of the vote count of that word's coordinate c.  About one
+// bitwise operation per 32 coordinates and input word replaces 32 extract-and-add steps.  The planes
+// are then staged through LDS so that the lanes can switch from "kWpl words each" to "four
+// consecutive coordinates each" and write counts / update x with full-width accesses.
+#ifndef DLION_SLICED_WORDS_PER_LANE
+#define DLION_SLICED_WORDS_PER_LANE 2      // consecutive words of each stream a lane reads (1 or 2)
+#endif
+constexpr int kWpl = DLION_SLICED_WORDS_PER_LANE;
+constexpr int kSlices = 2 * kWpl;                      // 32-bit slices a lane carries
+constexpr int kSlicedWords = kLanes * kWpl;            // words per wave
+constexpr int kSlicedCoords = kSlicedWords * 64;
 
-constexpr int kSlicedWords = 64;                       // words per wave
-constexpr int kSlicedCoords = kSlicedWords * 64;       // 4096
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// carry-save adder on 32 independent bit positions: a + b + c = 2*carry + sum.  gfx950 has a
+// three-input boolean instruction, so each output is one operation (truth tables: majority
+// 0xE8, parity 0x96; both symmetric in their operands).
+__device__ __forceinline__ void csa(uint32_t &carry, uint32_t &sum, uint32_t a, uint32_t b, uint32_t c)
+{
+    carry = __builtin_amdgcn_bitop3_b32(a, b, c, 0xE8);
+    sum = __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
 
 template <int kPlanes, bool kApply, bool kCounts>
 __global__ __launch_bounds__(kLanes) void aggregate_sliced_kernel(FlatAddr addr, Hyper h)
 {
     static_assert(kPlanes >= 5 && kPlanes <= 16, "planes");
-    __shared__ uint32_t lds[kPlanes][2 * kSlicedWords];
+    static_assert(kWpl == 1 || kWpl == 2, "words per lane");
+    __shared__ uint32_t lds[kPlanes][kLanes * kSlices];
     const Problem &p = addr.p;
     const int lane = threadIdx.x;
     const int64_t W = (p.numel + 63) >> 6;
-    const int64_t w0 = (int64_t)blockIdx.x * kSlicedWords;
-    const bool have = w0 + lane < W;
-    const uint64_t *src = p.packed + (have ? w0 + lane : 0);   // an in-bounds address also when idle
+    const int64_t w0 = (int64_t)blockIdx.x * kSlicedWords;      // first word of the wave
+    const int64_t wl0 = w0 + (int64_t)lane * kWpl;              // first word of the lane
+    const bool vec = (p.packed_stride % kWpl) == 0 && is_aligned(p.packed, 8 * kWpl);
+    // whole group inside the word range and rows that allow full-width loads: no per-lane guards
+    const bool fast = vec && w0 + kSlicedWords <= W;
     const int N = h.N;
 
-    uint64_t ones = 0, twos = 0, fours = 0, eights = 0;
-    uint64_t hi[kPlanes - 4];                                   // planes 4.. (sixteens and up)
+    uint32_t ones[kSlices], twos[kSlices], fours[kSlices], eights[kSlices];
+    uint32_t hi[kPlanes - 4][kSlices];                          // planes 4.. (sixteens and up)
 #pragma unroll
-    for (int b = 0; b < kPlanes - 4; ++b)
-        hi[b] = 0;
+    for (int q = 0; q < kSlices; ++q) {
+        ones[q] = twos[q] = fours[q] = eights[q] = 0;
+#pragma unroll
+        for (int b = 0; b < kPlanes - 4; ++b)
+            hi[b][q] = 0;
+    }
 
     for (int i = 0; i < N; i += 16) {
-        uint64_t v[16];
-        if (i + 16 <= N) {
+        uint32_t v[16][kSlices];
+        if (fast && i + 16 <= N) {
 #pragma unroll
-            for (int k = 0; k < 16; ++k)
-                v[k] = have ? stream_load(src + (int64_t)(i + k) * p.packed_stride) : 0;
+            for (int k = 0; k < 16; ++k) {
+                // uniform row base + small per-lane offset
+                const uint64_t *row = p.packed + (int64_t)(i + k) * p.packed_stride + w0;
+                if (kWpl == 2) {
+                    const u32x4 r = stream_load(reinterpret_cast<const u32x4 *>(row) + lane);
+                    v[k][0] = r.x;
+                    v[k][1] = r.y;
+                    v[k][kSlices - 2] = r.z;
+                    v[k][kSlices - 1] = r.w;
+                } else {
+                    const u32x2 r = stream_load(reinterpret_cast<const u32x2 *>(row) + lane);
+                    v[k][0] = r.x;
+                    v[k][1] = r.y;
+                }
+            }
         } else {
 #pragma unroll
-            for (int k = 0; k < 16; ++k)
-                v[k] = (have && i + k < N) ? stream_load(src + (int64_t)(i + k) * p.packed_stride) : 0;
-        }
-        uint64_t t0, t1, t2, t3, t4, t5, t6, t7, f0, f1, f2, f3, e0, e1, s16;
-        csa(t0, ones, ones, v[0], v[1]);
-        csa(t1, ones, ones, v[2], v[3]);
-        csa(t2, ones, ones, v[4], v[5]);
-        csa(t3, ones, ones, v[6], v[7]);
-        csa(t4, ones, ones, v[8], v[9]);
-        csa(t5, ones, ones, v[10], v[11]);
-        csa(t6, ones, ones, v[12], v[13]);
-        csa(t7, ones, ones, v[14], v[15]);
-        csa(f0, twos, twos, t0, t1);
-        csa(f1, twos, twos, t2, t3);
-        csa(f2, twos, twos, t4, t5);
-        csa(f3, twos, twos, t6, t7);
-        csa(e0, fours, fours, f0, f1);
-        csa(e1, fours, fours, f2, f3);
-        csa(s16, eights, eights, e0, e1);
-        // ripple the weight-16 carry into the upper planes
+            for (int k = 0; k < 16; ++k) {
 #pragma unroll
-        for (int b = 0; b < kPlanes - 4; ++b) {
-            const uint64_t c = hi[b] & s16;
-            hi[b] ^= s16;
-            s16 = c;
+                for (int q = 0; q < kWpl; ++q) {
+                    uint64_t word = 0;
+                    if (i + k < N && wl0 + q < W)
+                        word = stream_load(p.packed + (int64_t)(i + k) * p.packed_stride + wl0 + q);
+                    v[k][2 * q] = static_cast<uint32_t>(word);
+                    v[k][2 * q + 1] = static_cast<uint32_t>(word >> 32);
+                }
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < kSlices; ++q) {
+            uint32_t t0, t1, t2, t3, t4, t5, t6, t7, f0, f1, f2, f3, e0, e1, s16;
+            csa(t0, ones[q], ones[q], v[0][q], v[1][q]);
+            csa(t1, ones[q], ones[q], v[2][q], v[3][q]);
+            csa(t2, ones[q], ones[q], v[4][q], v[5][q]);
+            csa(t3, ones[q], ones[q], v[6][q], v[7][q]);
+            csa(t4, ones[q], ones[q], v[8][q], v[9][q]);
+            csa(t5, ones[q], ones[q], v[10][q], v[11][q]);
+            csa(t6, ones[q], ones[q], v[12][q], v[13][q]);
+            csa(t7, ones[q], ones[q], v[14][q], v[15][q]);
+            csa(f0, twos[q], twos[q], t0, t1);
+            csa(f1, twos[q], twos[q], t2, t3);
+            csa(f2, twos[q], twos[q], t4, t5);
+            csa(f3, twos[q], twos[q], t6, t7);
+            csa(e0, fours[q], fours[q], f0, f1);
+            csa(e1, fours[q], fours[q], f2, f3);
+            csa(s16, eights[q], eights[q], e0, e1);
+            // ripple the weight-16 carry into the upper planes
+#pragma unroll
+            for (int b = 0; b < kPlanes - 4; ++b) {
+                const uint32_t c = hi[b][q] & s16;
+                hi[b][q] ^= s16;
+                s16 = c;
+            }
         }
     }
 
-    // stage: lds[b][2*l], lds[b][2*l+1] = low / high dword of plane b of word l
-    auto put = [&](int b, uint64_t plane) {
-        lds[b][2 * lane] = static_cast<uint32_t>(plane);
-        lds[b][2 * lane + 1] = static_cast<uint32_t>(plane >> 32);
-    };
-    put(0, ones);
-    put(1, twos);
-    put(2, fours);
-    put(3, eights);
+    // stage: lds[b][2*wl + half] = low / high dword of plane b of word wl of the group
 #pragma unroll
-    for (int b = 0; b < kPlanes - 4; ++b)
-        put(4 + b, hi[b]);
+    for (int q = 0; q < kSlices; ++q) {
+        const int at = lane * kSlices + q;
+        lds[0][at] = ones[q];
+        lds[1][at] = twos[q];
+        lds[2][at] = fours[q];
+        lds[3][at] = eights[q];
+#pragma unroll
+        for (int b = 0; b < kPlanes - 4; ++b)
+            lds[4 + b][at] = hi[b][q];
+    }
     __syncthreads();
 
     const bool vec_x = !kApply || is_aligned(p.x, 16);
     const bool vec_c = !kCounts || is_aligned(p.counts, 8);
-    // now lane l owns coordinates 4*(l&15).. of word 4*s + (l>>4), s = 0..15
-#pragma unroll 1
+    // now lane l owns coordinates 4*(l&15).. of word 4*s + (l>>4), s = 0..kSlicedWords/4-1
+#pragma unroll 2
     for (int s = 0; s < kSlicedWords / kWordsPerSub; ++s) {
         const int wl = s * kWordsPerSub + (lane >> 4);          // word within the group
         const int64_t j0 = (w0 + wl) * 64 + (lane & 15) * kVec;
@@ -621,23 +691,29 @@ __global__ __launch_bounds__(kLanes) void aggregate_sliced_kernel(FlatAddr addr,
             continue;
         const int dword = 2 * wl + ((lane >> 3) & 1);
         const int shift = (lane & 7) * 4;
-        uint32_t c01 = 0, c23 = 0;                               // two 16-bit counters each
+        // byte k of lo / hi collects bits 0..7 / 8..15 of the count of coordinate j0 + k
+        uint32_t lo = 0, up = 0;
 #pragma unroll
         for (int b = 0; b < kPlanes; ++b) {
-            const uint32_t nib = (lds[b][dword] >> shift) & 0xFu;
-            c01 += ((nib & 1u) | ((nib & 2u) << 15)) << b;
-            c23 += (((nib >> 2) & 1u) | ((nib & 8u) << 13)) << b;
+            const uint32_t bytes = nibble_to_bytes((lds[b][dword] >> shift) & 0xFu);
+            if (b < 8)
+                lo += bytes << b;
+            else
+                up += bytes << (b - 8);
         }
-        const uint32_t cnt[4] = {c01 & 0xFFFFu, c01 >> 16, c23 & 0xFFFFu, c23 >> 16};
+        uint32_t cnt[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            cnt[k] = ((lo >> (8 * k)) & 0xFFu) | (kPlanes > 8 ? ((up >> (8 * k)) & 0xFFu) << 8 : 0u);
         const bool full = j0 + kVec <= p.numel;
         if (kApply) {
             if (full && vec_x) {
-                f32x4 xv = *reinterpret_cast<const f32x4 *>(p.x + j0);
+                f32x4 xv = X_LOAD(reinterpret_cast<const f32x4 *>(p.x + j0));
                 xv.x = lion_apply(xv.x, aggregate_votes(cnt[0], h), h);
                 xv.y = lion_apply(xv.y, aggregate_votes(cnt[1], h), h);
                 xv.z = lion_apply(xv.z, aggregate_votes(cnt[2], h), h);
                 xv.w = lion_apply(xv.w, aggregate_votes(cnt[3], h), h);
-                *reinterpret_cast<f32x4 *>(p.x + j0) = xv;
+                X_STORE(xv, reinterpret_cast<f32x4 *>(p.x + j0));
             } else {
 #pragma unroll
                 for (int k = 0; k < kVec; ++k)
@@ -652,7 +728,7 @@ __global__ __launch_bounds__(kLanes) void aggregate_sliced_kernel(FlatAddr addr,
                 c.y = static_cast<uint16_t>(cnt[1]);
                 c.z = static_cast<uint16_t>(cnt[2]);
                 c.w = static_cast<uint16_t>(cnt[3]);
-                *reinterpret_cast<u16x4 *>(p.counts + j0) = c;
+                C_STORE(c, reinterpret_cast<u16x4 *>(p.counts + j0));
             } else {
 #pragma unroll
                 for (int k = 0; k < kVec; ++k)
@@ -681,13 +757,13 @@ __global__ __launch_bounds__(kBlock) void apply_kernel(Addr addr, Hyper h)
             break;
         if (aligned && (sub + 1) * kSubTile <= p.numel) {
             const int64_t j0 = sub * kSubTile + lane * kVec;
-            const u16x4 c = *reinterpret_cast<const u16x4 *>(p.counts + j0);
-            f32x4 xv = *reinterpret_cast<const f32x4 *>(p.x + j0);
+            const u16x4 c = C_LOAD(reinterpret_cast<const u16x4 *>(p.counts + j0));
+            f32x4 xv = X_LOAD(reinterpret_cast<const f32x4 *>(p.x + j0));
             xv.x = lion_apply(xv.x, aggregate_votes(c.x, h), h);
             xv.y = lion_apply(xv.y, aggregate_votes(c.y, h), h);
             xv.z = lion_apply(xv.z, aggregate_votes(c.z, h), h);
             xv.w = lion_apply(xv.w, aggregate_votes(c.w, h), h);
-            *reinterpret_cast<f32x4 *>(p.x + j0) = xv;
+            X_STORE(xv, reinterpret_cast<f32x4 *>(p.x + j0));
         } else {
 #pragma unroll 1
             for (int k = 0; k < kWordsPerSub; ++k) {
