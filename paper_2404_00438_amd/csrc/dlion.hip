@@ -10,7 +10,7 @@ namespace {
 
 using namespace dlion;
 
-constexpr int64_t kMaxTiles = (int64_t)0x7FFFFFFF * kWavesPerBlock;
+constexpr int64_t kMaxTiles = (int64_t)0x7FFFFFFF;   // one-wave workgroups: one tile per workgroup
 
 inline bool aligned_to(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
@@ -47,19 +47,29 @@ inline dlion_status launched()
 }
 
 // ------------------------------------------------------------------ launch shape
-// HBM delivers the most when the chip keeps only a modest, compact window of
-// addresses in flight: roughly 24 KB of outstanding loads per compute unit.
-// A wave of the fused kernel has `unroll` workers' loads outstanding at once,
-// so the number of resident waves per compute unit is capped accordingly.  The
-// cap is applied by reserving (unused) dynamic LDS per workgroup: a compute
-// unit has 160 KB, so a reservation of 160 KB / k admits k workgroups.
+// Two measured properties of the memory system decide the launch shape of the streaming kernels.
+//
+// (1) HBM delivers the most when the chip keeps only a modest, compact window of addresses in
+//     flight: roughly 24 KB of outstanding loads per compute unit.  A wave of the fused kernel
+//     has `unroll` workers' loads outstanding at once, so the number of resident waves per
+//     compute unit is capped accordingly.  The cap is applied by reserving (unused) dynamic LDS
+//     per workgroup: a compute unit has 160 KB, so a reservation of 160 KB / k admits k
+//     workgroups.
+// (2) Every worker adds three pages (m read/write, g) to what a wave touches.  With one-wave
+//     workgroups the waves of a compute unit drift apart; beyond roughly 16 workers their
+//     pages no longer fit the per-CU translation cache (N = 32: 84 M misses per launch against
+//     36 K at N = 8).  For many workers the kernel therefore runs 16-wave workgroups that
+//     walk over the workers in lockstep.
 struct LaunchShape {
     int unroll;          // workers whose loads are issued back to back (8, 4, 2 or 1)
+    int waves;           // waves per workgroup: 1, or 16 in lockstep
     int blocks_per_cu;   // resident workgroups per compute unit (0: no cap)
 };
 
 constexpr size_t kLdsPerCu = 160 * 1024;
 constexpr size_t kMaxDynamicLds = 64 * 1024;
+constexpr int kLockstepWaves = 16;
+constexpr int kLockstepMinWorkers = 24;
 
 inline size_t lds_reservation(int blocks_per_cu)
 {
@@ -69,7 +79,8 @@ inline size_t lds_reservation(int blocks_per_cu)
     return bytes > kMaxDynamicLds ? kMaxDynamicLds : bytes;
 }
 
-// Environment overrides for tuning runs, read once: DLION_UNROLL, DLION_BLOCKS_PER_CU.
+// Environment overrides for tuning runs, read once:
+// DLION_UNROLL, DLION_WAVES (1 or 16), DLION_BLOCKS_PER_CU.
 inline int env_int(const char *name)
 {
     const char *v = std::getenv(name);
@@ -79,6 +90,7 @@ inline int env_int(const char *name)
 LaunchShape step_shape(int32_t N, size_t bytes_per_worker_per_wave)
 {
     static const int env_unroll = env_int("DLION_UNROLL");
+    static const int env_waves = env_int("DLION_WAVES");
     static const int env_blocks = env_int("DLION_BLOCKS_PER_CU");
     LaunchShape s;
     s.unroll = env_unroll > 0 ? env_unroll : 2;
@@ -86,10 +98,16 @@ LaunchShape step_shape(int32_t N, size_t bytes_per_worker_per_wave)
         s.unroll >>= 1;
     if (s.unroll < 1)
         s.unroll = 1;
+    if (env_waves > 0)
+        s.waves = env_waves >= kLockstepWaves ? kLockstepWaves : 1;
+    else
+        s.waves = (N >= kLockstepMinWorkers) ? kLockstepWaves : 1;
     if (env_blocks >= 0) {
         s.blocks_per_cu = env_blocks;
+    } else if (s.waves > 1) {
+        s.blocks_per_cu = 1;
     } else {
-        const size_t in_flight = bytes_per_worker_per_wave * static_cast<size_t>(s.unroll) * kWavesPerBlock;
+        const size_t in_flight = bytes_per_worker_per_wave * static_cast<size_t>(s.unroll);
         int k = static_cast<int>((24 * 1024 + in_flight / 2) / in_flight);
         s.blocks_per_cu = k < 3 ? 3 : (k > 32 ? 0 : k);
     }
@@ -97,19 +115,19 @@ LaunchShape step_shape(int32_t N, size_t bytes_per_worker_per_wave)
 }
 
 // ------------------------------------------------------------------ dispatch
-template <typename GT, int kUnroll, bool kApply, class Addr>
+template <typename GT, int kUnroll, int kWaves, bool kApply, class Addr>
 dlion_status launch_step_flags(const Addr &addr, const Hyper &h, bool packed, bool counts, size_t lds,
                                hipStream_t s)
 {
-    const dim3 grid = grid_for(addr.total_tiles), block(kBlock);
+    const dim3 grid(static_cast<uint32_t>((addr.total_tiles + kWaves - 1) / kWaves)), block(kLanes * kWaves);
     if (packed && counts)
-        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, true, true, Addr>), grid, block, lds, s, addr, h);
+        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kWaves, kApply, true, true, Addr>), grid, block, lds, s, addr, h);
     else if (packed)
-        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, true, false, Addr>), grid, block, lds, s, addr, h);
+        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kWaves, kApply, true, false, Addr>), grid, block, lds, s, addr, h);
     else if (counts)
-        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, false, true, Addr>), grid, block, lds, s, addr, h);
+        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kWaves, kApply, false, true, Addr>), grid, block, lds, s, addr, h);
     else
-        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, false, false, Addr>), grid, block, lds, s, addr, h);
+        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kWaves, kApply, false, false, Addr>), grid, block, lds, s, addr, h);
     return launched();
 }
 
@@ -118,11 +136,19 @@ dlion_status launch_step_unroll(const Addr &addr, const Hyper &h, bool packed, b
 {
     const LaunchShape shape = step_shape(h.N, kSubs * kLanes * (16 + Grad<GT>::kVecBytes));
     const size_t lds = lds_reservation(shape.blocks_per_cu);
+    if (shape.waves > 1) {
+        switch (shape.unroll) {
+        case 8:
+        case 4: return launch_step_flags<GT, 4, kLockstepWaves, kApply, Addr>(addr, h, packed, counts, lds, s);
+        case 2: return launch_step_flags<GT, 2, kLockstepWaves, kApply, Addr>(addr, h, packed, counts, lds, s);
+        default: return launch_step_flags<GT, 1, kLockstepWaves, kApply, Addr>(addr, h, packed, counts, lds, s);
+        }
+    }
     switch (shape.unroll) {
-    case 8: return launch_step_flags<GT, 8, kApply, Addr>(addr, h, packed, counts, lds, s);
-    case 4: return launch_step_flags<GT, 4, kApply, Addr>(addr, h, packed, counts, lds, s);
-    case 2: return launch_step_flags<GT, 2, kApply, Addr>(addr, h, packed, counts, lds, s);
-    default: return launch_step_flags<GT, 1, kApply, Addr>(addr, h, packed, counts, lds, s);
+    case 8: return launch_step_flags<GT, 8, 1, kApply, Addr>(addr, h, packed, counts, lds, s);
+    case 4: return launch_step_flags<GT, 4, 1, kApply, Addr>(addr, h, packed, counts, lds, s);
+    case 2: return launch_step_flags<GT, 2, 1, kApply, Addr>(addr, h, packed, counts, lds, s);
+    default: return launch_step_flags<GT, 1, 1, kApply, Addr>(addr, h, packed, counts, lds, s);
     }
 }
 

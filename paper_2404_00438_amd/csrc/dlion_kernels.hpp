@@ -137,7 +137,7 @@ struct SegAddr {
     }
 };
 
-__device__ __forceinline__ int64_t wave_tile_index()
+template <int kWaves = kWavesPerBlock> __device__ __forceinline__ int64_t wave_tile_index()
 {
     // blockIdx and the wave number are uniform across the wavefront; say so, so
     // that everything derived from the tile index stays in scalar registers.
@@ -149,7 +149,7 @@ __device__ __forceinline__ int64_t wave_tile_index()
     const uint32_t G = gridDim.x, q = G / kXcds, r = G % kXcds, xcd = block % kXcds;
     block = xcd * q + (xcd < r ? xcd : r) + block / kXcds;
 #endif
-    return (int64_t)block * kWavesPerBlock + wave;
+    return (int64_t)block * kWaves + wave;
 }
 
 // Cache policy of the small per-coordinate arrays.  x is touched once per step: streaming
@@ -284,7 +284,7 @@ __device__ __forceinline__ uint64_t row_gather_nibbles(uint32_t nibble, int lane
 // kPacked: write packed words.   kCounts: write counts.
 // Vector path over kR full sub-tiles starting at sub-tile `t`: the loads of kUnroll workers
 // x kR sub-tiles are issued back to back before any arithmetic.
-template <typename GT, int kUnroll, int kR, bool kApply, bool kPacked, bool kCounts>
+template <typename GT, int kUnroll, int kR, bool kApply, bool kPacked, bool kCounts, bool kLockstep = false>
 __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t, int lane, const Hyper &h)
 {
     const int64_t j0 = t * kSubTile + lane * kVec;
@@ -341,6 +341,8 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
             for (int r = 0; r < kR; ++r)
                 one_worker(i + u, r, mv[u][r], gv[u][r]);
         }
+        if (kLockstep)
+            __builtin_amdgcn_s_barrier();     // keep the waves of the workgroup on the same workers
     }
     for (; i < N; ++i) {
         f32x4 mv[kR], gv[kR];
@@ -411,10 +413,17 @@ __device__ __forceinline__ void step_subtile_guarded(const Problem &p, int64_t t
     }
 }
 
-template <typename GT, int kUnroll, bool kApply, bool kPacked, bool kCounts, class Addr>
-__global__ __launch_bounds__(kBlock) DLION_OCCUPANCY void step_kernel(Addr addr, Hyper h)
+// kWaves waves per workgroup.  With more than one, the waves of a workgroup walk over the
+// workers in lockstep (a barrier per batch of workers): with many workers, waves that drift
+// apart touch 3 pages per worker each and thrash the per-CU address-translation cache; kept
+// together, the compute unit works inside a handful of pages at any time.  A wave that takes
+// the guarded path, or has no tile, simply terminates; the barrier only waits for waves that
+// are still alive, and every surviving wave executes the same number of barriers (N is the
+// same for every tile).
+template <typename GT, int kUnroll, int kWaves, bool kApply, bool kPacked, bool kCounts, class Addr>
+__global__ __launch_bounds__(kLanes * kWaves) DLION_OCCUPANCY void step_kernel(Addr addr, Hyper h)
 {
-    const int64_t tile = wave_tile_index();
+    const int64_t tile = wave_tile_index<kWaves>();
     if (tile >= addr.total_tiles)
         return;
     const int lane = threadIdx.x & 63;
@@ -427,7 +436,7 @@ __global__ __launch_bounds__(kBlock) DLION_OCCUPANCY void step_kernel(Addr addr,
     if (kCounts)
         aligned = aligned && is_aligned(p.counts, 8);
     if (aligned && (t + kSubs) * kSubTile <= p.numel) {
-        step_subtiles_vector<GT, kUnroll, kSubs, kApply, kPacked, kCounts>(p, t, lane, h);
+        step_subtiles_vector<GT, kUnroll, kSubs, kApply, kPacked, kCounts, (kWaves > 1)>(p, t, lane, h);
         return;
     }
     // ragged end of a tensor, or rows that cannot take 128-bit accesses
