@@ -67,7 +67,7 @@ struct LaunchShape {
 };
 
 constexpr size_t kLdsPerCu = 160 * 1024;
-constexpr size_t kMaxDynamicLds = 64 * 1024;
+constexpr size_t kMaxDynamicLds = 160 * 1024;
 constexpr int kLockstepWaves = 16;
 constexpr int kLockstepMinWorkers = 24;
 
@@ -105,7 +105,7 @@ LaunchShape step_shape(int32_t N, size_t bytes_per_worker_per_wave)
     if (env_blocks >= 0) {
         s.blocks_per_cu = env_blocks;
     } else if (s.waves > 1) {
-        s.blocks_per_cu = 1;
+        s.blocks_per_cu = 2;
     } else {
         const size_t in_flight = bytes_per_worker_per_wave * static_cast<size_t>(s.unroll);
         int k = static_cast<int>((24 * 1024 + in_flight / 2) / in_flight);
@@ -174,23 +174,26 @@ dlion_status launch_aggregate(const Addr &addr, const Hyper &h, bool apply, bool
     return launched();
 }
 
-// Bit-sliced counting for many workers (flat buffers): planes = bits needed for a count 0..N.
-template <int kPlanes>
-dlion_status launch_sliced_planes(const FlatAddr &addr, const Hyper &h, bool apply, bool counts, size_t lds,
-                                  hipStream_t s)
+// Bit-sliced counting (flat buffers): planes = bits needed for a count 0..N; waves per
+// workgroup is 1, or as many (up to 16) as fit the 160 KB of LDS with one region per wave.
+template <int kPlanes, int kWaves>
+dlion_status launch_sliced_shape(const FlatAddr &addr, const Hyper &h, bool apply, bool counts, hipStream_t s)
 {
     const int64_t W = words_for(addr.p.numel);
-    const dim3 grid(static_cast<uint32_t>((W + kSlicedWords - 1) / kSlicedWords)), block(kLanes);
+    const int64_t groups = (W + kSlicedWords - 1) / kSlicedWords;
+    const dim3 grid(static_cast<uint32_t>((groups + kWaves - 1) / kWaves)), block(kLanes * kWaves);
+    const size_t lds = static_cast<size_t>(kWaves) * kPlanes * kSlicedLdsPerPlane * sizeof(uint32_t);
     if (apply && counts)
-        hipLaunchKernelGGL((aggregate_sliced_kernel<kPlanes, true, true>), grid, block, lds, s, addr, h);
+        hipLaunchKernelGGL((aggregate_sliced_kernel<kPlanes, kWaves, true, true>), grid, block, lds, s, addr, h);
     else if (apply)
-        hipLaunchKernelGGL((aggregate_sliced_kernel<kPlanes, true, false>), grid, block, lds, s, addr, h);
+        hipLaunchKernelGGL((aggregate_sliced_kernel<kPlanes, kWaves, true, false>), grid, block, lds, s, addr, h);
     else
-        hipLaunchKernelGGL((aggregate_sliced_kernel<kPlanes, false, true>), grid, block, lds, s, addr, h);
+        hipLaunchKernelGGL((aggregate_sliced_kernel<kPlanes, kWaves, false, true>), grid, block, lds, s, addr, h);
     return launched();
 }
 
 constexpr int kSlicedMinWorkers = 8;    // below this the per-nibble kernel is cheaper
+constexpr int kSlicedLockstepMinWorkers = 64;   // measured: 1 wave wins at N = 32, 8 waves at N = 256
 
 inline bool use_sliced(int32_t N)
 {
@@ -198,21 +201,29 @@ inline bool use_sliced(int32_t N)
     return N >= (env_min >= 0 ? env_min : kSlicedMinWorkers);
 }
 
+template <int kPlanes, bool kAllow16>
+dlion_status launch_sliced_planes(const FlatAddr &addr, const Hyper &h, bool apply, bool counts, hipStream_t s)
+{
+    static const int env_waves = env_int("DLION_SLICED_WAVES");   // tuning: 1, 8 or 16
+    const int waves = env_waves > 0 ? env_waves : (h.N >= kSlicedLockstepMinWorkers ? 8 : 1);
+    if (waves >= 16 && kAllow16)
+        return launch_sliced_shape<kPlanes, kAllow16 ? 16 : 8>(addr, h, apply, counts, s);
+    if (waves >= 8)
+        return launch_sliced_shape<kPlanes, 8>(addr, h, apply, counts, s);
+    return launch_sliced_shape<kPlanes, 1>(addr, h, apply, counts, s);
+}
+
 dlion_status launch_sliced(const FlatAddr &addr, const Hyper &h, bool apply, bool counts, hipStream_t s)
 {
-    static const int env_blocks = env_int("DLION_SLICED_BLOCKS_PER_CU");
-    const int blocks = env_blocks >= 0 ? env_blocks : 0;   // measured best: no cap
-    // the kernel's own LDS (planes x 512 B) counts towards the reservation
-    const size_t lds = lds_reservation(blocks);
     if (h.N < 32)
-        return launch_sliced_planes<5>(addr, h, apply, counts, lds > 5 * 8 * kSlicedWords ? lds - 5 * 8 * kSlicedWords : 0, s);
+        return launch_sliced_planes<5, true>(addr, h, apply, counts, s);
     if (h.N < 128)
-        return launch_sliced_planes<7>(addr, h, apply, counts, lds > 7 * 8 * kSlicedWords ? lds - 7 * 8 * kSlicedWords : 0, s);
+        return launch_sliced_planes<7, true>(addr, h, apply, counts, s);
     if (h.N < 512)
-        return launch_sliced_planes<9>(addr, h, apply, counts, lds > 9 * 8 * kSlicedWords ? lds - 9 * 8 * kSlicedWords : 0, s);
+        return launch_sliced_planes<9, true>(addr, h, apply, counts, s);
     if (h.N < 4096)
-        return launch_sliced_planes<12>(addr, h, apply, counts, lds > 12 * 8 * kSlicedWords ? lds - 12 * 8 * kSlicedWords : 0, s);
-    return launch_sliced_planes<16>(addr, h, apply, counts, lds > 16 * 8 * kSlicedWords ? lds - 16 * 8 * kSlicedWords : 0, s);
+        return launch_sliced_planes<12, false>(addr, h, apply, counts, s);
+    return launch_sliced_planes<16, false>(addr, h, apply, counts, s);
 }
 
 template <class Addr> dlion_status launch_apply(const Addr &addr, const Hyper &h, hipStream_t s)

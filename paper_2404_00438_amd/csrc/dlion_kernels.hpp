@@ -589,16 +589,30 @@ __device__ __forceinline__ void csa(uint32_t &carry, uint32_t &sum, uint32_t a, 
     sum = __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
 }
 
-template <int kPlanes, bool kApply, bool kCounts>
-__global__ __launch_bounds__(kLanes) void aggregate_sliced_kernel(FlatAddr addr, Hyper h)
+//
+// kWaves waves per workgroup, each with its own word group and its own LDS region.  With more
+// than one, the waves walk over the streams in lockstep (a barrier per batch of 16 streams,
+// so that the compute unit works inside 16 pages at a time instead of up to N), and they start
+// writing their results together: the memory system handles a few large bursts of writes much
+// better than a trickle of small ones between reads.  A wave without words terminates at once;
+// barriers only wait for waves that are alive, and all of those run the same number of batches.
+constexpr int kSlicedLdsPerPlane = kLanes * kSlices;   // dwords per wave and plane
+
+template <int kPlanes, int kWaves, bool kApply, bool kCounts>
+__global__ __launch_bounds__(kLanes * kWaves) void aggregate_sliced_kernel(FlatAddr addr, Hyper h)
 {
     static_assert(kPlanes >= 5 && kPlanes <= 16, "planes");
     static_assert(kWpl == 1 || kWpl == 2, "words per lane");
-    __shared__ uint32_t lds[kPlanes][kLanes * kSlices];
+    extern __shared__ uint32_t sliced_lds[];                    // [kWaves][kPlanes][kSlicedLdsPerPlane]
     const Problem &p = addr.p;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint32_t(*lds)[kSlicedLdsPerPlane] =
+        reinterpret_cast<uint32_t(*)[kSlicedLdsPerPlane]>(sliced_lds + wave * kPlanes * kSlicedLdsPerPlane);
     const int64_t W = (p.numel + 63) >> 6;
-    const int64_t w0 = (int64_t)blockIdx.x * kSlicedWords;      // first word of the wave
+    const int64_t w0 = ((int64_t)blockIdx.x * kWaves + wave) * kSlicedWords;   // first word of the wave
+    if (w0 >= W)
+        return;
     const int64_t wl0 = w0 + (int64_t)lane * kWpl;              // first word of the lane
     const bool vec = (p.packed_stride % kWpl) == 0 && is_aligned(p.packed, 8 * kWpl);
     // whole group inside the word range and rows that allow full-width loads: no per-lane guards
@@ -673,6 +687,8 @@ __global__ __launch_bounds__(kLanes) void aggregate_sliced_kernel(FlatAddr addr,
                 s16 = c;
             }
         }
+        if (kWaves > 1)
+            __builtin_amdgcn_s_barrier();
     }
 
     // stage: lds[b][2*wl + half] = low / high dword of plane b of word wl of the group
