@@ -13,11 +13,16 @@ from .dlion_oracle import (  # noqa: F401
     aggregate_packed,
     aggregate_signs,
     apply,
+    apply_encoded,
     build,
     compile_source,
     default,
+    delta_planes,
+    encode_delta,
+    global_lion_step,
     step,
     step_mt,
     worker_step,
+    worker_step_pw,
     words_for,
 )

@@ -248,3 +248,158 @@ int oracle_step_threads(float *x, float *m, int64_t m_stride, const void *g, int
     free(started);
     return rc;
 }
+
+/* ------------------------------------------------------------------------- *
+ * Server -> worker message for Delta ("Communication Cost" paragraph; Table 1).
+ *
+ * The aggregated update is sent as bit-planes over the same 64-coordinate
+ * words as the workers' messages (bit j%64 of word j/64 = coordinate j):
+ *   majority vote : plane 0 ("plus")  bit = 1 iff S > 0;
+ *                   plane 1 ("tie")   bit = 1 iff S == 0, present only when N
+ *                   is even (an odd N cannot tie), so the message is d bits
+ *                   for odd N as in Table 1 and 2d bits for even N (the
+ *                   price of reading a tie as 0);
+ *   averaging     : plane b holds bit b of the count p in {0..N}, for
+ *                   b < bits(N) = ceil(log2(N+1)) -- the "log(N) d" of Table 1.
+ * Bits past d are 0.
+ * ------------------------------------------------------------------------- */
+int oracle_delta_planes(int32_t N, int mode)
+{
+    if (mode == ORACLE_AVG) {
+        int bits = 0;
+        while (((int64_t)1 << bits) <= (int64_t)N)
+            ++bits;
+        return bits;
+    }
+    return (N % 2 == 0) ? 2 : 1;
+}
+
+void oracle_encode_delta(const uint16_t *counts, int64_t d, int32_t N, int mode, uint64_t *planes,
+                         int64_t plane_stride)
+{
+    const int P = oracle_delta_planes(N, mode);
+    const int64_t W = (d + 63) / 64;
+    for (int b = 0; b < P; ++b)
+        for (int64_t w = 0; w < W; ++w)
+            planes[(int64_t)b * plane_stride + w] = 0;
+    for (int64_t j = 0; j < d; ++j) {
+        const uint64_t bit = (uint64_t)1 << (j % 64);
+        if (mode == ORACLE_AVG) {
+            for (int b = 0; b < P; ++b)
+                if ((counts[j] >> b) & 1u)
+                    planes[(int64_t)b * plane_stride + j / 64] |= bit;
+        } else {
+            int32_t S = 2 * (int32_t)counts[j] - N;
+            if (S > 0)
+                planes[j / 64] |= bit;
+            if (S == 0)
+                planes[plane_stride + j / 64] |= bit; /* S == 0 needs N even, so plane 1 exists */
+        }
+    }
+}
+
+/* What a worker does with the message: rebuild Delta and take the step
+ * x <- x - lr*(Delta + lambda*x) (Section 3.2, third display). */
+void oracle_apply_encoded(float *x, const uint64_t *planes, int64_t plane_stride, int64_t d, int32_t N,
+                          int mode, float lr, float lambda, float *delta_out)
+{
+    const int P = oracle_delta_planes(N, mode);
+    for (int64_t j = 0; j < d; ++j) {
+        float Delta;
+        if (mode == ORACLE_AVG) {
+            int32_t p = 0;
+            for (int b = 0; b < P; ++b)
+                p |= (int32_t)((planes[(int64_t)b * plane_stride + j / 64] >> (j % 64)) & 1u) << b;
+            Delta = (float)(2 * p - N) / (float)N;
+        } else {
+            int plus = (int)((planes[j / 64] >> (j % 64)) & 1u);
+            int tie = (P > 1) ? (int)((planes[plane_stride + j / 64] >> (j % 64)) & 1u) : 0;
+            Delta = plus ? 1.0f : (tie ? 0.0f : -1.0f);
+        }
+        float t = lambda * x[j];
+        float u = Delta + t;
+        float v = lr * u;
+        x[j] = x[j] - v;
+        if (delta_out)
+            delta_out[j] = Delta;
+    }
+}
+
+/* ------------------------------------------------------------------------- *
+ * Worker step with each worker's own beta1, beta2 (footnote of Algorithm 1:
+ * every worker may set its individual coefficients).  Same arithmetic as
+ * oracle_worker_step with beta1[i], beta2[i] in place of the shared scalars.
+ * With beta1[i] == beta2[i] this is the sign-momentum (SIGNUM) worker of the
+ * D-SIGNUM comparison in Section 5.
+ * ------------------------------------------------------------------------- */
+void oracle_worker_step_pw(float *m, int64_t m_stride, const void *g, int64_t g_stride, int g_dtype,
+                           uint64_t *packed, int64_t packed_stride, int64_t d, int32_t N,
+                           const float *beta1, const float *beta2)
+{
+    const int64_t W = (d + 63) / 64;
+    for (int32_t i = 0; i < N; ++i) {
+        const float one_minus_beta1 = 1.0f - beta1[i];
+        const float one_minus_beta2 = 1.0f - beta2[i];
+        float *mi = m + (int64_t)i * m_stride;
+        uint64_t *pi = packed + (int64_t)i * packed_stride;
+        for (int64_t w = 0; w < W; ++w)
+            pi[w] = 0;
+        for (int64_t j = 0; j < d; ++j) {
+            float gij = grad_at(g, g_dtype, (int64_t)i * g_stride + j);
+            float a = beta1[i] * mi[j];
+            float b = one_minus_beta1 * gij;
+            float c = a + b;
+            if (!(c < 0.0f))
+                pi[j / 64] |= (uint64_t)1 << (j % 64);
+            float a2 = beta2[i] * mi[j];
+            float b2 = one_minus_beta2 * gij;
+            mi[j] = a2 + b2;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------- *
+ * Global Lion (Appendix, "Global Lion Convergence", the displayed scheme; the
+ * G-Lion baseline of Section 5): every worker forms its blend
+ *   c_i = beta1*m_i + (1-beta1)*g_i,  m_i <- beta2*m_i + (1-beta2)*g_i,
+ * the full-precision blends are averaged, and
+ *   x <- x - lr*(sign(mean_i c_i) + lambda*x).
+ * Readings: the mean is the fp32 sum over i = 0..N-1 in that order, divided by
+ * (float)N; the sign maps 0 to +1 like the worker sign, so that N = 1 is the
+ * same single-worker Lion that Distributed Lion reduces to.
+ * sign_bits (may be NULL) receives the W words of sign(mean c), packed like a
+ * worker's message.
+ * ------------------------------------------------------------------------- */
+void oracle_global_lion_step(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
+                             int g_dtype, int64_t d, int32_t N, float beta1, float beta2, float lr,
+                             float lambda, uint64_t *sign_bits)
+{
+    const float one_minus_beta1 = 1.0f - beta1;
+    const float one_minus_beta2 = 1.0f - beta2;
+    const int64_t W = (d + 63) / 64;
+    if (sign_bits)
+        for (int64_t w = 0; w < W; ++w)
+            sign_bits[w] = 0;
+    for (int64_t j = 0; j < d; ++j) {
+        float sum = 0.0f;
+        for (int32_t i = 0; i < N; ++i) {
+            float *mij = m + (int64_t)i * m_stride + j;
+            float gij = grad_at(g, g_dtype, (int64_t)i * g_stride + j);
+            float a = beta1 * (*mij);
+            float b = one_minus_beta1 * gij;
+            float c = a + b;
+            sum = sum + c;
+            float a2 = beta2 * (*mij);
+            float b2 = one_minus_beta2 * gij;
+            *mij = a2 + b2;
+        }
+        float mean = sum / (float)N;
+        float Delta = (mean < 0.0f) ? -1.0f : 1.0f;
+        if (sign_bits && !(mean < 0.0f))
+            sign_bits[j / 64] |= (uint64_t)1 << (j % 64);
+        float t = lambda * x[j];
+        float u = Delta + t;
+        float v = lr * u;
+        x[j] = x[j] - v;
+    }
+}

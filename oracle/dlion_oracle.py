@@ -92,6 +92,16 @@ class Oracle:
         lib.oracle_step.restype = None
         lib.oracle_step_threads.argtypes = lib.oracle_step.argtypes + [ci]
         lib.oracle_step_threads.restype = ci
+        lib.oracle_delta_planes.argtypes = [i32, ci]
+        lib.oracle_delta_planes.restype = ci
+        lib.oracle_encode_delta.argtypes = [vp, i64, i32, ci, vp, i64]
+        lib.oracle_encode_delta.restype = None
+        lib.oracle_apply_encoded.argtypes = [vp, vp, i64, i64, i32, ci, f32, f32, vp]
+        lib.oracle_apply_encoded.restype = None
+        lib.oracle_worker_step_pw.argtypes = [vp, i64, vp, i64, ci, vp, i64, i64, i32, vp, vp]
+        lib.oracle_worker_step_pw.restype = None
+        lib.oracle_global_lion_step.argtypes = [vp, vp, i64, vp, i64, ci, i64, i32, f32, f32, f32, f32, vp]
+        lib.oracle_global_lion_step.restype = None
         self.lib = lib
 
     def worker_step(self, m, g, beta1, beta2, want_delta=False):
@@ -154,6 +164,60 @@ class Oracle:
             raise MemoryError("oracle_step_threads")
         return packed, counts
 
+    def delta_planes(self, N, mode):
+        """Number of bit-planes of the server -> worker message."""
+        return self.lib.oracle_delta_planes(N, mode)
+
+    def encode_delta(self, counts, N, mode):
+        """Server -> worker message: ``[planes, W]`` uint64 bit-planes built from the counts."""
+        counts = np.ascontiguousarray(counts, dtype=np.uint16)
+        d = counts.shape[0]
+        W = words_for(d)
+        planes = np.empty((self.delta_planes(N, mode), W), dtype=np.uint64)
+        self.lib.oracle_encode_delta(_ptr(counts), d, N, mode, _ptr(planes), W)
+        return planes
+
+    def apply_encoded(self, x, planes, N, mode, lr, lam, want_delta=False):
+        """Worker side of the down-link: decode the planes and update ``x`` in place."""
+        if x.dtype != np.float32 or x.ndim != 1 or not x.flags.c_contiguous:
+            raise TypeError("x must be contiguous float32 [d]")
+        P, W, ps = _rows(planes, [np.uint64], "planes")
+        if P != self.delta_planes(N, mode) or W < words_for(x.shape[0]):
+            raise ValueError("planes has the wrong shape")
+        delta = np.empty_like(x) if want_delta else None
+        self.lib.oracle_apply_encoded(_ptr(x), _ptr(planes), ps, x.shape[0], N, mode, lr, lam,
+                                      _ptr(delta) if want_delta else None)
+        return delta
+
+    def worker_step_pw(self, m, g, beta1, beta2):
+        """Worker step with per-worker coefficients (``beta1``, ``beta2`` float32 ``[N]``); returns packed."""
+        N, d, ms = _rows(m, [np.float32], "m")
+        Ng, dg, gs = _rows(g, [np.float32, np.uint16], "g")
+        if (N, d) != (Ng, dg):
+            raise ValueError("m and g shapes differ")
+        b1 = np.ascontiguousarray(beta1, dtype=np.float32)
+        b2 = np.ascontiguousarray(beta2, dtype=np.float32)
+        if b1.shape != (N,) or b2.shape != (N,):
+            raise ValueError("need one beta1 and one beta2 per worker")
+        W = words_for(d)
+        packed = np.empty((N, W), dtype=np.uint64)
+        self.lib.oracle_worker_step_pw(_ptr(m), ms, _ptr(g), gs, _gdtype(g), _ptr(packed), W, d, N,
+                                       _ptr(b1), _ptr(b2))
+        return packed
+
+    def global_lion_step(self, x, m, g, beta1, beta2, lr, lam):
+        """One Global Lion iteration; ``x``, ``m`` in place; returns the packed sign of the mean blend."""
+        N, d, ms = _rows(m, [np.float32], "m")
+        Ng, dg, gs = _rows(g, [np.float32, np.uint16], "g")
+        if (N, d) != (Ng, dg):
+            raise ValueError("m and g shapes differ")
+        if x.dtype != np.float32 or x.shape != (d,) or not x.flags.c_contiguous:
+            raise TypeError("x must be contiguous float32 [d]")
+        bits = np.empty(words_for(d), dtype=np.uint64)
+        self.lib.oracle_global_lion_step(_ptr(x), _ptr(m), ms, _ptr(g), gs, _gdtype(g), d, N, beta1, beta2,
+                                         lr, lam, _ptr(bits))
+        return bits
+
     def step_mt(self, xs, ms, gs, mode, beta1, beta2, lr, lam):
         """Multi-tensor iteration: tensor ``k`` is ``xs[k]`` flat ``[n_k]``, ``ms[k]``/``gs[k]`` ``[N, n_k]``.
 
@@ -201,3 +265,23 @@ def step(*a, **k):
 
 def step_mt(*a, **k):
     return default().step_mt(*a, **k)
+
+
+def delta_planes(*a, **k):
+    return default().delta_planes(*a, **k)
+
+
+def encode_delta(*a, **k):
+    return default().encode_delta(*a, **k)
+
+
+def apply_encoded(*a, **k):
+    return default().apply_encoded(*a, **k)
+
+
+def worker_step_pw(*a, **k):
+    return default().worker_step_pw(*a, **k)
+
+
+def global_lion_step(*a, **k):
+    return default().global_lion_step(*a, **k)

@@ -10,6 +10,7 @@ import pytest
 
 import oracle
 from test_oracle_pins import ALL_CHECKS
+from test_oracle_next_pins import NEXT_CHECKS
 
 MUTANTS = {
     "beta1_beta2_swapped_in_sign": ("float a = beta1 * mi[j];", "float a = beta2 * mi[j];"),
@@ -31,6 +32,17 @@ MUTANTS = {
     "count_skips_last_worker": ("for (int32_t i = 0; i < N; ++i) {\n            uint64_t word",
                                 "for (int32_t i = 0; i + 1 < N || i == 0; ++i) {\n            uint64_t word"),
     "momentum_not_stored": ("mi[j] = a2 + b2;", "(void)(a2 + b2);"),
+    # the wider rows
+    "plus_plane_includes_ties": ("if (S > 0)\n                planes[j / 64] |= bit;", "if (S >= 0)\n                planes[j / 64] |= bit;"),
+    "tie_plane_dropped": ("if (S == 0)\n                planes[plane_stride + j / 64] |= bit;", "if (S == 0 && 0)\n                planes[plane_stride + j / 64] |= bit;"),
+    "count_planes_one_short": ("while (((int64_t)1 << bits) <= (int64_t)N)", "while (((int64_t)1 << bits) < (int64_t)N)"),
+    "decoded_tie_is_minus": ("Delta = plus ? 1.0f : (tie ? 0.0f : -1.0f);", "Delta = plus ? 1.0f : -1.0f;"),
+    "decoded_count_not_centred": ("Delta = (float)(2 * p - N) / (float)N;", "Delta = (float)p / (float)N;"),
+    "per_worker_beta_uses_worker_0": ("float a = beta1[i] * mi[j];", "float a = beta1[0] * mi[j];"),
+    "per_worker_beta2_swapped": ("float a2 = beta2[i] * mi[j];", "float a2 = beta1[i] * mi[j];"),
+    "global_sign_of_last_worker": ("sum = sum + c;", "sum = c;"),
+    "global_sign_zero_is_minus": ("float Delta = (mean < 0.0f) ? -1.0f : 1.0f;", "float Delta = (mean > 0.0f) ? 1.0f : -1.0f;"),
+    "global_momentum_from_blend": ("*mij = a2 + b2;", "*mij = c;"),
 }
 
 
@@ -39,15 +51,16 @@ def test_planted_mistake_is_caught(name, tmp_path):
     old, new = MUTANTS[name]
     with open(oracle.SOURCE) as f:
         src = f.read()
-    assert src.count(old) == 1, f"mutation site for {name} not found exactly once"
+    # the first occurrence is the one meant (later functions repeat some lines of earlier ones)
+    assert src.count(old) >= 1, f"mutation site for {name} not found"
     c_path = os.path.join(tmp_path, f"mutant_{name}.c")
     with open(c_path, "w") as f:
-        f.write(src.replace(old, new))
+        f.write(src.replace(old, new, 1))
     so_path = os.path.join(tmp_path, f"mutant_{name}.so")
     oracle.compile_source(c_path, so_path)
     mutant = oracle.Oracle(so_path)
     caught = []
-    for check in ALL_CHECKS:
+    for check in ALL_CHECKS + NEXT_CHECKS:
         try:
             check(mutant)
         except AssertionError:
