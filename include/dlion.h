@@ -169,6 +169,70 @@ dlion_status dlion_step_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev
                            float beta2, float lr, float lambda, uint64_t *packed_or_null,
                            int64_t packed_stride, uint16_t *counts_or_null, void *stream);
 
+/* ------------------------------------------------------------------------- *
+ * Wider rows around the hot path.
+ * ------------------------------------------------------------------------- */
+
+/*
+ * Server -> worker message for Delta ("Communication Cost" paragraph; Table 1's
+ * Server->Worker column) as bit-planes over the same 64-coordinate words as the
+ * workers' messages (bit j%64 of word j/64 = coordinate j, bits past d zero):
+ *   DLION_VOTE : plane 0 "plus" = (S > 0); plane 1 "tie" = (S == 0) exists only
+ *                for even N.  Delta = plus ? +1 : (tie ? 0 : -1).  d bits for odd
+ *                N as in Table 1, 2d bits for even N (the cost of tie -> 0).
+ *   DLION_AVG  : plane b = bit b of the count p, b < ceil(log2(N+1)); the
+ *                "log(N) d" bits of Table 1.  Delta = (2p - N)/N.
+ * dlion_delta_planes: number of planes (host helper; 0 for invalid arguments).
+ */
+int32_t dlion_delta_planes(int32_t N, dlion_mode mode);
+
+/*
+ * Server side in wire format: packed worker messages in, Delta planes out
+ * (delta: [planes rows of W] uint64, row stride delta_stride >= W).
+ */
+dlion_status dlion_aggregate_encode(const uint64_t *packed, int64_t packed_stride, int64_t d, int32_t N,
+                                    dlion_mode mode, uint64_t *delta, int64_t delta_stride, void *stream);
+
+/*
+ * Worker side of the down-link: decode the planes and take the step
+ * x <- x - lr*(Delta + lambda*x) (Section 3.2, third display).
+ */
+dlion_status dlion_apply_encoded(float *x, const uint64_t *delta, int64_t delta_stride, int64_t d,
+                                 int32_t N, dlion_mode mode, float lr, float lambda, void *stream);
+
+/*
+ * Worker step / fused step with each worker's own coefficients (footnote of
+ * Algorithm 1).  beta1, beta2: DEVICE arrays of N floats; (1 - beta) is formed
+ * in fp32 on the device.  beta1[i] == beta2[i] gives the sign-momentum worker
+ * of the D-SIGNUM comparison (Section 5).  Everything else as in
+ * dlion_worker_step / dlion_step.
+ */
+dlion_status dlion_worker_step_pw(float *m, int64_t m_stride, const void *g, int64_t g_stride,
+                                  dlion_dtype g_dtype, uint64_t *packed, int64_t packed_stride,
+                                  int64_t d, int32_t N, const float *beta1, const float *beta2,
+                                  void *stream);
+dlion_status dlion_step_pw(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
+                           dlion_dtype g_dtype, int64_t d, int32_t N, dlion_mode mode,
+                           const float *beta1, const float *beta2, float lr, float lambda,
+                           uint64_t *packed_or_null, int64_t packed_stride, uint16_t *counts_or_null,
+                           void *stream);
+
+/*
+ * Global Lion, the full-precision comparison scheme (Appendix, "Global Lion
+ * Convergence"; the G-Lion baseline of Section 5):
+ *   c_i = beta1*m_i + (1-beta1)*g_i;  m_i <- beta2*m_i + (1-beta2)*g_i;
+ *   x <- x - lr*(sign(mean_i c_i) + lambda*x).
+ * The mean is the fp32 sum over i = 0..N-1 in that order divided by (float)N;
+ * the sign maps 0 to +1 as the worker sign does (N = 1 is then the same
+ * single-worker Lion).  sign_bits_or_null, if given, receives the W words of
+ * sign(mean c) packed like a worker's message, so that agreement with the
+ * majority vote can be counted.
+ */
+dlion_status dlion_global_lion_step(float *x, float *m, int64_t m_stride, const void *g,
+                                    int64_t g_stride, dlion_dtype g_dtype, int64_t d, int32_t N,
+                                    float beta1, float beta2, float lr, float lambda,
+                                    uint64_t *sign_bits_or_null, void *stream);
+
 /* Text for a status code (static storage, never NULL). */
 const char *dlion_status_str(dlion_status s);
 

@@ -12,6 +12,12 @@ from .binding import (  # noqa: F401
     DlionError,
     SegTable,
     dlion_aggregate,
+    dlion_aggregate_encode,
+    dlion_apply_encoded,
+    dlion_delta_planes,
+    dlion_global_lion_step,
+    dlion_step_pw,
+    dlion_worker_step_pw,
     dlion_aggregate_apply,
     dlion_aggregate_apply_mt,
     dlion_aggregate_mt,

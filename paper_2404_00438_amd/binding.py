@@ -27,6 +27,8 @@ EXPORTS = (
     "dlion_worker_step", "dlion_aggregate", "dlion_apply", "dlion_aggregate_apply", "dlion_step",
     "dlion_mt_layout", "dlion_worker_step_mt", "dlion_aggregate_mt", "dlion_apply_mt",
     "dlion_aggregate_apply_mt", "dlion_step_mt", "dlion_status_str", "dlion_version",
+    "dlion_delta_planes", "dlion_aggregate_encode", "dlion_apply_encoded", "dlion_worker_step_pw",
+    "dlion_step_pw", "dlion_global_lion_step",
 )
 
 
@@ -70,6 +72,12 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "dlion_apply_mt": [segp, vp, i32, vp, i32, ci, f32, f32, vp],
         "dlion_aggregate_apply_mt": [segp, vp, i32, vp, i64, i32, ci, f32, f32, vp, vp],
         "dlion_step_mt": [segp, vp, i32, ci, i32, ci, f32, f32, f32, f32, vp, i64, vp, vp],
+        "dlion_delta_planes": [i32, ci],
+        "dlion_aggregate_encode": [vp, i64, i64, i32, ci, vp, i64, vp],
+        "dlion_apply_encoded": [vp, vp, i64, i64, i32, ci, f32, f32, vp],
+        "dlion_worker_step_pw": [vp, i64, vp, i64, ci, vp, i64, i64, i32, vp, vp, vp],
+        "dlion_step_pw": [vp, vp, i64, vp, i64, ci, i64, i32, ci, vp, vp, f32, f32, vp, i64, vp, vp],
+        "dlion_global_lion_step": [vp, vp, i64, vp, i64, ci, i64, i32, f32, f32, f32, f32, vp, vp],
     }
     for name, argtypes in protos.items():
         fn = getattr(lib, name)
@@ -291,3 +299,76 @@ def dlion_step_mt(table: SegTable, N, mode, beta1, beta2, lr, lam, packed=None, 
     cp = _as_u16(counts, "counts").data_ptr() if counts is not None else None
     _check(load_library().dlion_step_mt(table.host, table.dev_ptr, table.K, table.g_dtype, N, mode, beta1, beta2,
                                         lr, lam, pp, ps, cp, _stream(stream)), "dlion_step_mt")
+
+
+def dlion_delta_planes(N: int, mode: int) -> int:
+    return load_library().dlion_delta_planes(N, mode)
+
+
+def dlion_aggregate_encode(packed, d, mode, delta, stream=None):
+    pp, ps, N, _ = _rows(_as_u64(packed, "packed"), "packed")
+    dp, ds, P, _ = _rows(_as_u64(delta, "delta"), "delta")
+    if P != dlion_delta_planes(N, mode):
+        raise ValueError("delta must have dlion_delta_planes(N, mode) rows")
+    _check(load_library().dlion_aggregate_encode(pp, ps, d, N, mode, dp, ds, _stream(stream)),
+           "dlion_aggregate_encode")
+
+
+def dlion_apply_encoded(x, delta, N, mode, lr, lam, stream=None):
+    xp = _flat(x, "x", torch.float32)
+    dp, ds, P, _ = _rows(_as_u64(delta, "delta"), "delta")
+    if P != dlion_delta_planes(N, mode):
+        raise ValueError("delta must have dlion_delta_planes(N, mode) rows")
+    _check(load_library().dlion_apply_encoded(xp, dp, ds, x.numel(), N, mode, lr, lam, _stream(stream)),
+           "dlion_apply_encoded")
+
+
+def _betas(beta1, beta2, N):
+    for b in (beta1, beta2):
+        if b.dtype != torch.float32 or b.dim() != 1 or b.numel() != N or not b.is_cuda or \
+                (N > 1 and b.stride(0) != 1):
+            raise ValueError("beta1/beta2 must be contiguous float32 device tensors of N elements")
+    return beta1.data_ptr(), beta2.data_ptr()
+
+
+def dlion_worker_step_pw(m, g, packed, beta1, beta2, stream=None):
+    mp, ms, N, d = _rows(m, "m")
+    gp, gs, Ng, dg = _rows(g, "g")
+    pp, ps, Np, _ = _rows(_as_u64(packed, "packed"), "packed")
+    if m.dtype != torch.float32 or (N, d) != (Ng, dg) or Np != N:
+        raise ValueError("m must be fp32 and m, g, packed must agree on N and d")
+    b1, b2 = _betas(beta1, beta2, N)
+    _check(load_library().dlion_worker_step_pw(mp, ms, gp, gs, _gdtype(g), pp, ps, d, N, b1, b2,
+                                               _stream(stream)), "dlion_worker_step_pw")
+
+
+def dlion_step_pw(x, m, g, mode, beta1, beta2, lr, lam, packed=None, counts=None, stream=None):
+    xp = _flat(x, "x", torch.float32)
+    mp, ms, N, d = _rows(m, "m")
+    gp, gs, Ng, dg = _rows(g, "g")
+    if m.dtype != torch.float32 or (N, d) != (Ng, dg) or x.numel() != d:
+        raise ValueError("m must be fp32 and x, m, g must agree on N and d")
+    pp, ps = (None, 0)
+    if packed is not None:
+        pp, ps, Np, _ = _rows(_as_u64(packed, "packed"), "packed")
+        if Np != N:
+            raise ValueError("packed must have N rows")
+    cp = _as_u16(counts, "counts").data_ptr() if counts is not None else None
+    b1, b2 = _betas(beta1, beta2, N)
+    _check(load_library().dlion_step_pw(xp, mp, ms, gp, gs, _gdtype(g), d, N, mode, b1, b2, lr, lam,
+                                        pp, ps, cp, _stream(stream)), "dlion_step_pw")
+
+
+def dlion_global_lion_step(x, m, g, beta1, beta2, lr, lam, sign_bits=None, stream=None):
+    xp = _flat(x, "x", torch.float32)
+    mp, ms, N, d = _rows(m, "m")
+    gp, gs, Ng, dg = _rows(g, "g")
+    if m.dtype != torch.float32 or (N, d) != (Ng, dg) or x.numel() != d:
+        raise ValueError("m must be fp32 and x, m, g must agree on N and d")
+    sp = None
+    if sign_bits is not None:
+        if _as_u64(sign_bits, "sign_bits").numel() < words_for(d) or sign_bits.dim() != 1:
+            raise ValueError("sign_bits must be a 1-D tensor of at least W words")
+        sp = sign_bits.data_ptr()
+    _check(load_library().dlion_global_lion_step(xp, mp, ms, gp, gs, _gdtype(g), d, N, beta1, beta2, lr, lam,
+                                                 sp, _stream(stream)), "dlion_global_lion_step")

@@ -32,6 +32,8 @@ Hyper make_hyper(int32_t N, int mode, float beta1, float beta2, float lr, float 
     h.N = N;
     h.mode = mode;
     h.stream_counts = 0;
+    h.beta1_pw = nullptr;
+    h.beta2_pw = nullptr;
     return h;
 }
 
@@ -229,6 +231,64 @@ dlion_status launch_sliced(const FlatAddr &addr, const Hyper &h, bool apply, boo
 template <class Addr> dlion_status launch_apply(const Addr &addr, const Hyper &h, hipStream_t s)
 {
     hipLaunchKernelGGL((apply_kernel<Addr>), grid_for(addr.total_tiles), dim3(kBlock), 0, s, addr, h);
+    return launched();
+}
+
+// Down-link message: planes needed for Delta.
+inline int32_t delta_planes(int32_t N, int mode)
+{
+    if (mode == DLION_AVG) {
+        int32_t bits = 0;
+        while ((static_cast<int64_t>(1) << bits) <= static_cast<int64_t>(N))
+            ++bits;
+        return bits;
+    }
+    return (N % 2 == 0) ? 2 : 1;
+}
+
+template <int kPlanes, int kWaves>
+dlion_status launch_encode_shape(const FlatAddr &addr, const Hyper &h, const DeltaOut &out, hipStream_t s)
+{
+    const int64_t W = words_for(addr.p.numel);
+    const int64_t groups = (W + kSlicedWords - 1) / kSlicedWords;
+    const dim3 grid(static_cast<uint32_t>((groups + kWaves - 1) / kWaves)), block(kLanes * kWaves);
+    hipLaunchKernelGGL((aggregate_encode_kernel<kPlanes, kWaves>), grid, block, 0, s, addr, h, out);
+    return launched();
+}
+
+template <int kPlanes>
+dlion_status launch_encode_planes(const FlatAddr &addr, const Hyper &h, const DeltaOut &out, hipStream_t s)
+{
+    static const int env_waves = env_int("DLION_SLICED_WAVES");
+    const int waves = env_waves > 0 ? env_waves : (h.N >= kSlicedLockstepMinWorkers ? 8 : 1);
+    if (waves >= 8)
+        return launch_encode_shape<kPlanes, 8>(addr, h, out, s);
+    return launch_encode_shape<kPlanes, 1>(addr, h, out, s);
+}
+
+dlion_status launch_encode(const FlatAddr &addr, const Hyper &h, const DeltaOut &out, hipStream_t s)
+{
+    if (h.N < 32)
+        return launch_encode_planes<5>(addr, h, out, s);
+    if (h.N < 128)
+        return launch_encode_planes<7>(addr, h, out, s);
+    if (h.N < 512)
+        return launch_encode_planes<9>(addr, h, out, s);
+    if (h.N < 4096)
+        return launch_encode_planes<12>(addr, h, out, s);
+    return launch_encode_planes<16>(addr, h, out, s);
+}
+
+template <typename GT>
+dlion_status launch_global_lion_unroll(const FlatAddr &addr, const Hyper &h, uint64_t *sign_bits, hipStream_t s)
+{
+    const LaunchShape shape = step_shape(h.N, kLanes * (16 + Grad<GT>::kVecBytes));
+    const size_t lds = shape.waves > 1 ? 0 : lds_reservation(shape.blocks_per_cu);
+    const dim3 grid(static_cast<uint32_t>(addr.total_tiles)), block(kLanes);
+    if (shape.unroll >= 2 && h.N >= 2)
+        hipLaunchKernelGGL((global_lion_kernel<GT, 2>), grid, block, lds, s, addr, h, sign_bits);
+    else
+        hipLaunchKernelGGL((global_lion_kernel<GT, 1>), grid, block, lds, s, addr, h, sign_bits);
     return launched();
 }
 
@@ -527,6 +587,108 @@ dlion_status dlion_step_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev
     const SegAddr a = seg_addr(segs_dev, K, tiles, packed_or_null, packed_stride, counts_or_null);
     return launch_step<true>(a, h, g_dtype, packed_or_null != nullptr, counts_or_null != nullptr,
                              static_cast<hipStream_t>(stream));
+}
+
+// ----------------------------------------------------------------------- wider rows
+int32_t dlion_delta_planes(int32_t N, dlion_mode mode)
+{
+    if (N < 1 || N > DLION_MAX_WORKERS || !mode_ok(mode))
+        return 0;
+    return delta_planes(N, mode);
+}
+
+dlion_status dlion_aggregate_encode(const uint64_t *packed, int64_t packed_stride, int64_t d, int32_t N,
+                                    dlion_mode mode, uint64_t *delta, int64_t delta_stride, void *stream)
+{
+    DLION_TRY(check_common(d, N));
+    if (!mode_ok(mode))
+        return DLION_EINVAL;
+    DLION_TRY(check_rows(packed, packed_stride, words_for(d), N, 8));
+    const int32_t planes = delta_planes(N, mode);
+    DLION_TRY(check_rows(delta, delta_stride, words_for(d), planes, 8));
+    const Hyper h = make_hyper(N, mode, 0.0f, 0.0f, 0.0f, 0.0f);
+    const FlatAddr a = flat_addr(nullptr, nullptr, 0, nullptr, 0, d, const_cast<uint64_t *>(packed),
+                                 packed_stride, nullptr);
+    const DeltaOut out = {delta, delta_stride, planes};
+    return launch_encode(a, h, out, static_cast<hipStream_t>(stream));
+}
+
+dlion_status dlion_apply_encoded(float *x, const uint64_t *delta, int64_t delta_stride, int64_t d, int32_t N,
+                                 dlion_mode mode, float lr, float lambda, void *stream)
+{
+    DLION_TRY(check_common(d, N));
+    if (!mode_ok(mode) || !x)
+        return DLION_EINVAL;
+    if (!aligned_to(x, 4))
+        return DLION_EALIGN;
+    const int32_t planes = delta_planes(N, mode);
+    DLION_TRY(check_rows(delta, delta_stride, words_for(d), planes, 8));
+    const Hyper h = make_hyper(N, mode, 0.0f, 0.0f, lr, lambda);
+    const FlatAddr a = flat_addr(x, nullptr, 0, nullptr, 0, d, nullptr, 0, nullptr);
+    const DeltaOut in = {const_cast<uint64_t *>(delta), delta_stride, planes};
+    hipLaunchKernelGGL(apply_encoded_kernel, dim3(static_cast<uint32_t>(a.total_tiles)), dim3(kLanes), 0,
+                       static_cast<hipStream_t>(stream), a, h, in);
+    return launched();
+}
+
+dlion_status dlion_worker_step_pw(float *m, int64_t m_stride, const void *g, int64_t g_stride,
+                                  dlion_dtype g_dtype, uint64_t *packed, int64_t packed_stride, int64_t d,
+                                  int32_t N, const float *beta1, const float *beta2, void *stream)
+{
+    DLION_TRY(check_common(d, N));
+    if (!dtype_ok(g_dtype) || !beta1 || !beta2)
+        return DLION_EINVAL;
+    if (!aligned_to(beta1, 4) || !aligned_to(beta2, 4))
+        return DLION_EALIGN;
+    DLION_TRY(check_rows(m, m_stride, d, N, 4));
+    DLION_TRY(check_rows(g, g_stride, d, N, grad_size(g_dtype)));
+    DLION_TRY(check_rows(packed, packed_stride, words_for(d), N, 8));
+    Hyper h = make_hyper(N, DLION_VOTE, 0.0f, 0.0f, 0.0f, 0.0f);
+    h.beta1_pw = beta1;
+    h.beta2_pw = beta2;
+    const FlatAddr a = flat_addr(nullptr, m, m_stride, g, g_stride, d, packed, packed_stride, nullptr);
+    return launch_step<false>(a, h, g_dtype, true, false, static_cast<hipStream_t>(stream));
+}
+
+dlion_status dlion_step_pw(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
+                           dlion_dtype g_dtype, int64_t d, int32_t N, dlion_mode mode, const float *beta1,
+                           const float *beta2, float lr, float lambda, uint64_t *packed_or_null,
+                           int64_t packed_stride, uint16_t *counts_or_null, void *stream)
+{
+    DLION_TRY(check_common(d, N));
+    if (!dtype_ok(g_dtype) || !mode_ok(mode) || !x || !beta1 || !beta2)
+        return DLION_EINVAL;
+    if (!aligned_to(x, 4) || !aligned_to(counts_or_null, 2) || !aligned_to(beta1, 4) || !aligned_to(beta2, 4))
+        return DLION_EALIGN;
+    DLION_TRY(check_rows(m, m_stride, d, N, 4));
+    DLION_TRY(check_rows(g, g_stride, d, N, grad_size(g_dtype)));
+    if (packed_or_null)
+        DLION_TRY(check_rows(packed_or_null, packed_stride, words_for(d), N, 8));
+    Hyper h = make_hyper(N, mode, 0.0f, 0.0f, lr, lambda);
+    h.beta1_pw = beta1;
+    h.beta2_pw = beta2;
+    h.stream_counts = counts_or_null ? counts_exceed_cache(d) : 0;
+    const FlatAddr a = flat_addr(x, m, m_stride, g, g_stride, d, packed_or_null, packed_stride, counts_or_null);
+    return launch_step<true>(a, h, g_dtype, packed_or_null != nullptr, counts_or_null != nullptr,
+                             static_cast<hipStream_t>(stream));
+}
+
+dlion_status dlion_global_lion_step(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
+                                    dlion_dtype g_dtype, int64_t d, int32_t N, float beta1, float beta2,
+                                    float lr, float lambda, uint64_t *sign_bits_or_null, void *stream)
+{
+    DLION_TRY(check_common(d, N));
+    if (!dtype_ok(g_dtype) || !x)
+        return DLION_EINVAL;
+    if (!aligned_to(x, 4) || !aligned_to(sign_bits_or_null, 8))
+        return DLION_EALIGN;
+    DLION_TRY(check_rows(m, m_stride, d, N, 4));
+    DLION_TRY(check_rows(g, g_stride, d, N, grad_size(g_dtype)));
+    const Hyper h = make_hyper(N, DLION_VOTE, beta1, beta2, lr, lambda);
+    const FlatAddr a = flat_addr(x, m, m_stride, g, g_stride, d, nullptr, 0, nullptr);
+    if (g_dtype == DLION_BF16)
+        return launch_global_lion_unroll<uint16_t>(a, h, sign_bits_or_null, static_cast<hipStream_t>(stream));
+    return launch_global_lion_unroll<float>(a, h, sign_bits_or_null, static_cast<hipStream_t>(stream));
 }
 
 const char *dlion_status_str(dlion_status s)

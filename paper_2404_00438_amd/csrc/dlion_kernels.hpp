@@ -74,6 +74,13 @@ struct Hyper {
     int32_t N;
     int32_t mode;     // dlion_mode
     int32_t stream_counts;   // counts array too large to stay cached: write it with streaming stores
+    const float *beta1_pw;   // per-worker coefficients (device arrays of N floats), or null:
+    const float *beta2_pw;   // then beta1/beta2 above are shared by all workers
+};
+
+// Coefficients of one worker (footnote of Algorithm 1: each worker may set its own).
+struct Coef {
+    float beta1, omb1, beta2, omb2;
 };
 
 // One flat problem as a tile sees it.
@@ -232,11 +239,28 @@ template <> struct Grad<uint16_t> {   // bf16 bit patterns; widening to fp32 is 
 // ---------------------------------------------------------------- arithmetic
 // Worker update for one coordinate (Section 3.2, first display).  Returns the
 // vote (true = +1) and replaces m by the new momentum.
-__device__ __forceinline__ bool lion_worker(float &m, float g, const Hyper &h)
+__device__ __forceinline__ float lion_blend(float &m, float g, const Coef &k)
 {
-    const float c = __fadd_rn(__fmul_rn(h.beta1, m), __fmul_rn(h.omb1, g));
-    m = __fadd_rn(__fmul_rn(h.beta2, m), __fmul_rn(h.omb2, g));
-    return !(c < 0.0f);
+    const float c = __fadd_rn(__fmul_rn(k.beta1, m), __fmul_rn(k.omb1, g));
+    m = __fadd_rn(__fmul_rn(k.beta2, m), __fmul_rn(k.omb2, g));
+    return c;
+}
+__device__ __forceinline__ bool lion_worker(float &m, float g, const Coef &k)
+{
+    return !(lion_blend(m, g, k) < 0.0f);
+}
+
+// i is uniform across the wave: scalar loads
+__device__ __forceinline__ Coef worker_coef(const Hyper &h, int i)
+{
+    Coef k = {h.beta1, h.omb1, h.beta2, h.omb2};
+    if (h.beta1_pw) {
+        k.beta1 = h.beta1_pw[i];
+        k.omb1 = __fsub_rn(1.0f, k.beta1);
+        k.beta2 = h.beta2_pw[i];
+        k.omb2 = __fsub_rn(1.0f, k.beta2);
+    }
+    return k;
 }
 
 // Aggregation of p votes for +1 out of N (Section 3.2, second display).
@@ -301,11 +325,12 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
     const int N = h.N;
 
     auto one_worker = [&](int i, int r, f32x4 mv, f32x4 gv) {
+        const Coef k = worker_coef(h, i);
         float m0 = mv.x, m1 = mv.y, m2 = mv.z, m3 = mv.w;
-        const bool b0 = lion_worker(m0, gv.x, h);
-        const bool b1 = lion_worker(m1, gv.y, h);
-        const bool b2 = lion_worker(m2, gv.z, h);
-        const bool b3 = lion_worker(m3, gv.w, h);
+        const bool b0 = lion_worker(m0, gv.x, k);
+        const bool b1 = lion_worker(m1, gv.y, k);
+        const bool b2 = lion_worker(m2, gv.z, k);
+        const bool b3 = lion_worker(m3, gv.w, k);
         mv.x = m0;
         mv.y = m1;
         mv.z = m2;
@@ -396,7 +421,7 @@ __device__ __forceinline__ void step_subtile_guarded(const Problem &p, int64_t t
                 float *mp = p.m + (int64_t)i * p.m_stride + j;
                 float mv = *mp;
                 const float gv = Grad<GT>::load1(p.g, (int64_t)i * p.g_stride + j);
-                plus = lion_worker(mv, gv, h);
+                plus = lion_worker(mv, gv, worker_coef(h, i));
                 *mp = mv;
             }
             cnt += plus;
@@ -589,35 +614,23 @@ __device__ __forceinline__ void csa(uint32_t &carry, uint32_t &sum, uint32_t a, 
     sum = __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
 }
 
-//
-// kWaves waves per workgroup, each with its own word group and its own LDS region.  With more
-// than one, the waves walk over the streams in lockstep (a barrier per batch of 16 streams,
-// so that the compute unit works inside 16 pages at a time instead of up to N), and they start
-// writing their results together: the memory system handles a few large bursts of writes much
-// better than a trickle of small ones between reads.  A wave without words terminates at once;
-// barriers only wait for waves that are alive, and all of those run the same number of batches.
-constexpr int kSlicedLdsPerPlane = kLanes * kSlices;   // dwords per wave and plane
+// Planes of one lane: v[b][q] = bits b of the counts of the 32 coordinates of slice q.
+template <int kPlanes> struct Planes {
+    uint32_t v[kPlanes][kSlices];
+};
 
-template <int kPlanes, int kWaves, bool kApply, bool kCounts>
-__global__ __launch_bounds__(kLanes * kWaves) void aggregate_sliced_kernel(FlatAddr addr, Hyper h)
+// Counting loop shared by the kernels below: adds the N words of every stream into `out`.
+// w0 = first word of the wave; kWaves > 1: a barrier per batch of 16 streams (lockstep).
+template <int kPlanes, int kWaves>
+__device__ __forceinline__ void sliced_count(const Problem &p, int N, int64_t w0, int64_t W, int lane,
+                                             Planes<kPlanes> &out)
 {
     static_assert(kPlanes >= 5 && kPlanes <= 16, "planes");
     static_assert(kWpl == 1 || kWpl == 2, "words per lane");
-    extern __shared__ uint32_t sliced_lds[];                    // [kWaves][kPlanes][kSlicedLdsPerPlane]
-    const Problem &p = addr.p;
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    uint32_t(*lds)[kSlicedLdsPerPlane] =
-        reinterpret_cast<uint32_t(*)[kSlicedLdsPerPlane]>(sliced_lds + wave * kPlanes * kSlicedLdsPerPlane);
-    const int64_t W = (p.numel + 63) >> 6;
-    const int64_t w0 = ((int64_t)blockIdx.x * kWaves + wave) * kSlicedWords;   // first word of the wave
-    if (w0 >= W)
-        return;
     const int64_t wl0 = w0 + (int64_t)lane * kWpl;              // first word of the lane
     const bool vec = (p.packed_stride % kWpl) == 0 && is_aligned(p.packed, 8 * kWpl);
     // whole group inside the word range and rows that allow full-width loads: no per-lane guards
     const bool fast = vec && w0 + kSlicedWords <= W;
-    const int N = h.N;
 
     uint32_t ones[kSlices], twos[kSlices], fours[kSlices], eights[kSlices];
     uint32_t hi[kPlanes - 4][kSlices];                          // planes 4.. (sixteens and up)
@@ -690,18 +703,48 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_sliced_kernel(FlatA
         if (kWaves > 1)
             __builtin_amdgcn_s_barrier();
     }
+#pragma unroll
+    for (int q = 0; q < kSlices; ++q) {
+        out.v[0][q] = ones[q];
+        out.v[1][q] = twos[q];
+        out.v[2][q] = fours[q];
+        out.v[3][q] = eights[q];
+#pragma unroll
+        for (int b = 0; b < kPlanes - 4; ++b)
+            out.v[4 + b][q] = hi[b][q];
+    }
+}
+
+// kWaves waves per workgroup, each with its own word group and its own LDS region.  With more
+// than one, the waves walk over the streams in lockstep (a barrier per batch of 16 streams,
+// so that the compute unit works inside 16 pages at a time instead of up to N), and they start
+// writing their results together: the memory system handles a few large bursts of writes much
+// better than a trickle of small ones between reads.  A wave without words terminates at once;
+// barriers only wait for waves that are alive, and all of those run the same number of batches.
+constexpr int kSlicedLdsPerPlane = kLanes * kSlices;   // dwords per wave and plane
+
+template <int kPlanes, int kWaves, bool kApply, bool kCounts>
+__global__ __launch_bounds__(kLanes * kWaves) void aggregate_sliced_kernel(FlatAddr addr, Hyper h)
+{
+    extern __shared__ uint32_t sliced_lds[];                    // [kWaves][kPlanes][kSlicedLdsPerPlane]
+    const Problem &p = addr.p;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint32_t(*lds)[kSlicedLdsPerPlane] =
+        reinterpret_cast<uint32_t(*)[kSlicedLdsPerPlane]>(sliced_lds + wave * kPlanes * kSlicedLdsPerPlane);
+    const int64_t W = (p.numel + 63) >> 6;
+    const int64_t w0 = ((int64_t)blockIdx.x * kWaves + wave) * kSlicedWords;   // first word of the wave
+    if (w0 >= W)
+        return;
+    Planes<kPlanes> pl;
+    sliced_count<kPlanes, kWaves>(p, h.N, w0, W, lane, pl);
 
     // stage: lds[b][2*wl + half] = low / high dword of plane b of word wl of the group
 #pragma unroll
     for (int q = 0; q < kSlices; ++q) {
-        const int at = lane * kSlices + q;
-        lds[0][at] = ones[q];
-        lds[1][at] = twos[q];
-        lds[2][at] = fours[q];
-        lds[3][at] = eights[q];
 #pragma unroll
-        for (int b = 0; b < kPlanes - 4; ++b)
-            lds[4 + b][at] = hi[b][q];
+        for (int b = 0; b < kPlanes; ++b)
+            lds[b][lane * kSlices + q] = pl.v[b][q];
     }
     __syncthreads();
 
@@ -716,7 +759,7 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_sliced_kernel(FlatA
             continue;
         const int dword = 2 * wl + ((lane >> 3) & 1);
         const int shift = (lane & 7) * 4;
-        // byte k of lo / hi collects bits 0..7 / 8..15 of the count of coordinate j0 + k
+        // byte k of lo / up collects bits 0..7 / 8..15 of the count of coordinate j0 + k
         uint32_t lo = 0, up = 0;
 #pragma unroll
         for (int b = 0; b < kPlanes; ++b) {
@@ -760,6 +803,257 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_sliced_kernel(FlatA
                     if (j0 + k < p.numel)
                         p.counts[j0 + k] = static_cast<uint16_t>(cnt[k]);
             }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- server -> worker message
+// The aggregated update as bit-planes over the same 64-coordinate words as the workers'
+// messages ("Communication Cost" paragraph; Table 1):
+//   majority vote: plane 0 "plus" (S > 0) and, for even N only, plane 1 "tie" (S == 0);
+//   averaging    : plane b = bit b of the count p, b < bits(N) = ceil(log2(N+1)).
+// The counting loop leaves exactly such planes in registers, so the averaged message is
+// written straight from them, and the vote needs one bit-sliced comparison against N/2:
+// no transposition, no LDS, and 1/8 .. bits(N)/8 bytes written per coordinate instead of 2.
+struct DeltaOut {
+    uint64_t *planes;      // plane b at planes + b*stride
+    int64_t stride;
+    int32_t n_planes;      // planes to write: 1 or 2 (vote), bits(N) (average)
+};
+
+template <int kPlanes, int kWaves>
+__global__ __launch_bounds__(kLanes * kWaves) void aggregate_encode_kernel(FlatAddr addr, Hyper h, DeltaOut out)
+{
+    const Problem &p = addr.p;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t W = (p.numel + 63) >> 6;
+    const int64_t w0 = ((int64_t)blockIdx.x * kWaves + wave) * kSlicedWords;
+    if (w0 >= W)
+        return;
+    Planes<kPlanes> pl;
+    sliced_count<kPlanes, kWaves>(p, h.N, w0, W, lane, pl);
+    if (kWaves > 1)
+        __builtin_amdgcn_s_barrier();        // start the write burst together
+
+    uint32_t res[2][kSlices];                // vote: plus, tie
+    if (h.mode == DLION_VOTE) {
+        // bit-sliced compare of the count with K = floor(N/2), from the top plane down:
+        // gt = count > K, eq = count == K on every bit position at once
+        const uint32_t K = static_cast<uint32_t>(h.N) >> 1;
+#pragma unroll
+        for (int q = 0; q < kSlices; ++q) {
+            uint32_t gt = 0, eq = 0xFFFFFFFFu;
+#pragma unroll
+            for (int b = kPlanes - 1; b >= 0; --b) {
+                if ((K >> b) & 1u) {
+                    eq &= pl.v[b][q];
+                } else {
+                    gt |= eq & pl.v[b][q];
+                    eq &= ~pl.v[b][q];
+                }
+            }
+            res[0][q] = gt;                  // S > 0
+            res[1][q] = eq;                  // S == 0 (written only when N is even)
+        }
+    }
+    const int64_t wl0 = w0 + (int64_t)lane * kWpl;
+#pragma unroll 1
+    for (int b = 0; b < out.n_planes; ++b) {
+#pragma unroll
+        for (int q = 0; q < kWpl; ++q) {
+            const int64_t w = wl0 + q;
+            if (w >= W)
+                continue;
+            uint32_t lo, up;
+            if (h.mode == DLION_VOTE) {
+                lo = b == 0 ? res[0][2 * q] : res[1][2 * q];
+                up = b == 0 ? res[0][2 * q + 1] : res[1][2 * q + 1];
+            } else {
+                lo = up = 0;
+#pragma unroll
+                for (int bb = 0; bb < kPlanes; ++bb) {      // select plane b without indexing registers
+                    if (bb == b) {
+                        lo = pl.v[bb][2 * q];
+                        up = pl.v[bb][2 * q + 1];
+                    }
+                }
+            }
+            uint64_t word = (static_cast<uint64_t>(up) << 32) | lo;
+            const int64_t left = p.numel - w * 64;            // coordinates in this word
+            if (left < 64)
+                word &= (static_cast<uint64_t>(1) << left) - 1;   // bits past d are zero
+            out.planes[(int64_t)b * out.stride + w] = word;
+        }
+    }
+}
+
+// Worker side of the down-link: decode the planes and take the step.  Same tiling as the
+// per-nibble server kernel: lane l owns coordinates 4l..4l+3 of a 256-coordinate tile, i.e.
+// nibble (l & 15) of word (l >> 4); the guarded path gives lane l bit l of one word.
+__device__ __forceinline__ float decode_vote(uint32_t plus, uint32_t tie)
+{
+    return plus ? 1.0f : (tie ? 0.0f : -1.0f);
+}
+
+__global__ __launch_bounds__(kLanes) void apply_encoded_kernel(FlatAddr addr, Hyper h, DeltaOut in)
+{
+    const Problem &p = addr.p;
+    const int64_t t = blockIdx.x;                               // one wave per tile
+    const int lane = threadIdx.x;
+    const bool full = (t + 1) * kSubTile <= p.numel && is_aligned(p.x, 16);
+    if (full) {
+        const int64_t j0 = t * kSubTile + lane * kVec;
+        const int64_t dword = 2 * (t * kWordsPerSub + (lane >> 4)) + ((lane >> 3) & 1);
+        const int shift = (lane & 7) * 4;
+        auto nibble = [&](int b) {
+            const uint32_t *plane = reinterpret_cast<const uint32_t *>(in.planes + (int64_t)b * in.stride);
+            return (plane[dword] >> shift) & 0xFu;
+        };
+        float Delta[4];
+        if (h.mode == DLION_VOTE) {
+            const uint32_t plus = nibble(0);
+            const uint32_t tie = in.n_planes > 1 ? nibble(1) : 0u;
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                Delta[k] = decode_vote((plus >> k) & 1u, (tie >> k) & 1u);
+        } else {
+            uint32_t lo = 0, up = 0;
+            for (int b = 0; b < in.n_planes; ++b) {
+                const uint32_t bytes = nibble_to_bytes(nibble(b));
+                if (b < 8)
+                    lo += bytes << b;
+                else
+                    up += bytes << (b - 8);
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                Delta[k] = aggregate_votes(((lo >> (8 * k)) & 0xFFu) | (((up >> (8 * k)) & 0xFFu) << 8), h);
+        }
+        f32x4 xv = X_LOAD(reinterpret_cast<const f32x4 *>(p.x + j0));
+        xv.x = lion_apply(xv.x, Delta[0], h);
+        xv.y = lion_apply(xv.y, Delta[1], h);
+        xv.z = lion_apply(xv.z, Delta[2], h);
+        xv.w = lion_apply(xv.w, Delta[3], h);
+        X_STORE(xv, reinterpret_cast<f32x4 *>(p.x + j0));
+        return;
+    }
+    const int64_t W = (p.numel + 63) >> 6;
+#pragma unroll 1
+    for (int k = 0; k < kWordsPerSub; ++k) {
+        const int64_t w = t * kWordsPerSub + k;
+        if (w >= W)
+            break;
+        const int64_t j = w * 64 + lane;
+        float Delta;
+        if (h.mode == DLION_VOTE) {
+            const uint32_t plus = static_cast<uint32_t>((in.planes[w] >> lane) & 1u);
+            const uint32_t tie = in.n_planes > 1 ? static_cast<uint32_t>((in.planes[in.stride + w] >> lane) & 1u) : 0u;
+            Delta = decode_vote(plus, tie);
+        } else {
+            uint32_t cnt = 0;
+            for (int b = 0; b < in.n_planes; ++b)
+                cnt |= static_cast<uint32_t>((in.planes[(int64_t)b * in.stride + w] >> lane) & 1u) << b;
+            Delta = aggregate_votes(cnt, h);
+        }
+        if (j < p.numel)
+            p.x[j] = lion_apply(p.x[j], Delta, h);
+    }
+}
+
+// ---------------------------------------------------------------- Global Lion (comparison scheme)
+// Appendix, "Global Lion Convergence": the workers' full-precision blends c_i are averaged and
+// x <- x - lr*(sign(mean_i c_i) + lambda*x); each worker's momentum moves as in Distributed
+// Lion.  The mean is the fp32 sum over i = 0..N-1 in that order divided by (float)N, and the
+// sign maps 0 to +1 (so that N = 1 is the same single-worker Lion).  Same tiling as the fused
+// step; sign_bits (optional) receives sign(mean c) packed like a worker's message.
+__device__ __forceinline__ bool global_sign(float sum, const Hyper &h)
+{
+    const float mean = (h.inv_n != 0.0f) ? __fmul_rn(sum, h.inv_n) : sum / static_cast<float>(h.N);
+    return !(mean < 0.0f);
+}
+
+template <typename GT, int kUnroll>
+__global__ __launch_bounds__(kLanes) void global_lion_kernel(FlatAddr addr, Hyper h, uint64_t *sign_bits)
+{
+    const Problem &p = addr.p;
+    const int64_t t = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int N = h.N;
+    const Coef k = {h.beta1, h.omb1, h.beta2, h.omb2};
+    const bool vec = (t + 1) * kSubTile <= p.numel && is_aligned(p.m, 16) && (p.m_stride & 3) == 0 &&
+                     is_aligned(p.g, Grad<GT>::kVecBytes) && (p.g_stride & 3) == 0 && is_aligned(p.x, 16);
+    if (vec) {
+        const int64_t j0 = t * kSubTile + lane * kVec;
+        f32x4 xv = X_LOAD(reinterpret_cast<const f32x4 *>(p.x + j0));
+        float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+        auto one_worker = [&](int i, f32x4 mv, f32x4 gv) {
+            float m0 = mv.x, m1 = mv.y, m2 = mv.z, m3 = mv.w;
+            s0 = __fadd_rn(s0, lion_blend(m0, gv.x, k));
+            s1 = __fadd_rn(s1, lion_blend(m1, gv.y, k));
+            s2 = __fadd_rn(s2, lion_blend(m2, gv.z, k));
+            s3 = __fadd_rn(s3, lion_blend(m3, gv.w, k));
+            mv.x = m0;
+            mv.y = m1;
+            mv.z = m2;
+            mv.w = m3;
+            stream_store(mv, reinterpret_cast<f32x4 *>(p.m + (int64_t)i * p.m_stride + j0));
+        };
+        int i = 0;
+        for (; i + kUnroll <= N; i += kUnroll) {
+            f32x4 mv[kUnroll], gv[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                mv[u] = stream_load(reinterpret_cast<const f32x4 *>(p.m + (int64_t)(i + u) * p.m_stride + j0));
+                gv[u] = Grad<GT>::load4(p.g, (int64_t)(i + u) * p.g_stride + j0);
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+                one_worker(i + u, mv[u], gv[u]);
+        }
+        for (; i < N; ++i) {
+            const f32x4 mv = stream_load(reinterpret_cast<const f32x4 *>(p.m + (int64_t)i * p.m_stride + j0));
+            const f32x4 gv = Grad<GT>::load4(p.g, (int64_t)i * p.g_stride + j0);
+            one_worker(i, mv, gv);
+        }
+        const bool b0 = global_sign(s0, h), b1 = global_sign(s1, h), b2 = global_sign(s2, h), b3 = global_sign(s3, h);
+        xv.x = lion_apply(xv.x, b0 ? 1.0f : -1.0f, h);
+        xv.y = lion_apply(xv.y, b1 ? 1.0f : -1.0f, h);
+        xv.z = lion_apply(xv.z, b2 ? 1.0f : -1.0f, h);
+        xv.w = lion_apply(xv.w, b3 ? 1.0f : -1.0f, h);
+        X_STORE(xv, reinterpret_cast<f32x4 *>(p.x + j0));
+        if (sign_bits) {
+            const uint32_t nib = (b0 ? 1u : 0u) | (b1 ? 2u : 0u) | (b2 ? 4u : 0u) | (b3 ? 8u : 0u);
+            const uint64_t word = row_gather_nibbles(nib, lane);
+            if ((lane & 15) == 0)
+                sign_bits[t * kWordsPerSub + (lane >> 4)] = word;
+        }
+        return;
+    }
+    const int64_t W = (p.numel + 63) >> 6;
+#pragma unroll 1
+    for (int kk = 0; kk < kWordsPerSub; ++kk) {
+        const int64_t w = t * kWordsPerSub + kk;
+        if (w >= W)
+            break;
+        const int64_t j = w * 64 + lane;
+        const bool valid = j < p.numel;
+        float sum = 0.0f;
+        if (valid) {
+            for (int i = 0; i < N; ++i) {
+                float *mp = p.m + (int64_t)i * p.m_stride + j;
+                float mv = *mp;
+                sum = __fadd_rn(sum, lion_blend(mv, Grad<GT>::load1(p.g, (int64_t)i * p.g_stride + j), k));
+                *mp = mv;
+            }
+        }
+        const bool plus = valid && global_sign(sum, h);
+        if (valid)
+            p.x[j] = lion_apply(p.x[j], plus ? 1.0f : -1.0f, h);
+        if (sign_bits) {
+            const uint64_t word = __ballot(plus);
+            if (lane == 0)
+                sign_bits[w] = word;
         }
     }
 }

@@ -122,3 +122,33 @@ def test_tensor_list_layout_and_validation(lib):
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(FileNotFoundError):
         binding.load_library(os.path.join(tmp_path, "libdlion.so"))
+
+
+def test_wider_rows_validation(lib):
+    EINVAL, EALIGN = 1, 2
+    assert lib.dlion_delta_planes(3, 0) == 1 and lib.dlion_delta_planes(4, 0) == 2
+    assert [lib.dlion_delta_planes(n, 1) for n in (1, 2, 3, 4, 7, 8, 255, 256, 65535)] == [1, 2, 2, 3, 3, 4, 8, 9, 16]
+    assert lib.dlion_delta_planes(0, 0) == 0 and lib.dlion_delta_planes(4, 7) == 0
+    enc = lib.dlion_aggregate_encode
+    assert enc(None, 2, 128, 4, 0, A, 2, None) == EINVAL
+    assert enc(A, 2, 128, 4, 0, None, 2, None) == EINVAL
+    assert enc(A, 2, 128, 4, 0, A, 1, None) == EINVAL          # two planes need stride >= W
+    assert enc(A, 2, 128, 4, 9, A, 2, None) == EINVAL
+    assert enc(A, 2, 128, 4, 0, A + 4, 2, None) == EALIGN
+    dec = lib.dlion_apply_encoded
+    assert dec(None, A, 2, 128, 4, 0, 1e-4, 0.1, None) == EINVAL
+    assert dec(A, None, 2, 128, 4, 0, 1e-4, 0.1, None) == EINVAL
+    assert dec(A + 2, A, 2, 128, 4, 0, 1e-4, 0.1, None) == EALIGN
+    assert dec(A, A, 1, 128, 4, 1, 1e-4, 0.1, None) == EINVAL  # three planes, stride < W
+    pw = lib.dlion_worker_step_pw
+    assert pw(A, 128, A, 128, 0, A, 2, 128, 4, None, A, None) == EINVAL
+    assert pw(A, 128, A, 128, 0, A, 2, 128, 4, A, None, None) == EINVAL
+    assert pw(A, 128, A, 128, 0, A, 2, 128, 4, A + 2, A, None) == EALIGN
+    spw = lib.dlion_step_pw
+    assert spw(A, A, 128, A, 128, 0, 128, 4, 0, None, A, 1e-4, 0.1, None, 0, None, None) == EINVAL
+    assert spw(None, A, 128, A, 128, 0, 128, 4, 0, A, A, 1e-4, 0.1, None, 0, None, None) == EINVAL
+    gl = lib.dlion_global_lion_step
+    assert gl(None, A, 128, A, 128, 0, 128, 4, 0.9, 0.99, 1e-4, 0.1, None, None) == EINVAL
+    assert gl(A, A, 100, A, 128, 0, 128, 4, 0.9, 0.99, 1e-4, 0.1, None, None) == EINVAL
+    assert gl(A, A, 128, A, 128, 3, 128, 4, 0.9, 0.99, 1e-4, 0.1, None, None) == EINVAL
+    assert gl(A, A, 128, A, 128, 0, 128, 4, 0.9, 0.99, 1e-4, 0.1, A + 4, None) == EALIGN
