@@ -896,6 +896,7 @@ __device__ __forceinline__ float decode_vote(uint32_t plus, uint32_t tie)
     return plus ? 1.0f : (tie ? 0.0f : -1.0f);
 }
 
+template <int kMaxPlanes>
 __global__ __launch_bounds__(kLanes) void apply_encoded_kernel(FlatAddr addr, Hyper h, DeltaOut in)
 {
     const Problem &p = addr.p;
@@ -906,21 +907,25 @@ __global__ __launch_bounds__(kLanes) void apply_encoded_kernel(FlatAddr addr, Hy
         const int64_t j0 = t * kSubTile + lane * kVec;
         const int64_t dword = 2 * (t * kWordsPerSub + (lane >> 4)) + ((lane >> 3) & 1);
         const int shift = (lane & 7) * 4;
-        auto nibble = [&](int b) {
+        // all planes' loads first (n_planes <= kMaxPlanes; the test is uniform)
+        uint32_t raw[kMaxPlanes];
+#pragma unroll
+        for (int b = 0; b < kMaxPlanes; ++b) {
             const uint32_t *plane = reinterpret_cast<const uint32_t *>(in.planes + (int64_t)b * in.stride);
-            return (plane[dword] >> shift) & 0xFu;
-        };
+            raw[b] = b < in.n_planes ? plane[dword] : 0u;
+        }
         float Delta[4];
         if (h.mode == DLION_VOTE) {
-            const uint32_t plus = nibble(0);
-            const uint32_t tie = in.n_planes > 1 ? nibble(1) : 0u;
+            const uint32_t plus = (raw[0] >> shift) & 0xFu;
+            const uint32_t tie = (raw[1] >> shift) & 0xFu;
 #pragma unroll
             for (int k = 0; k < 4; ++k)
                 Delta[k] = decode_vote((plus >> k) & 1u, (tie >> k) & 1u);
         } else {
             uint32_t lo = 0, up = 0;
-            for (int b = 0; b < in.n_planes; ++b) {
-                const uint32_t bytes = nibble_to_bytes(nibble(b));
+#pragma unroll
+            for (int b = 0; b < kMaxPlanes; ++b) {
+                const uint32_t bytes = nibble_to_bytes((raw[b] >> shift) & 0xFu);
                 if (b < 8)
                     lo += bytes << b;
                 else
