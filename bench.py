@@ -80,8 +80,8 @@ def recorded_traffic(workload: str):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="gpt2s_avg8")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -106,17 +106,41 @@ def main() -> int:
     torch.cuda.set_device(0)
     dl.load_library()
     w = wl.CONFIGS[args.workload]
-    if w.shapes is not None or w.g_dist == "packed_bernoulli":
-        print("bench.py times flat fused-step workloads", file=sys.stderr)
-        return 2
+    g_bytes = 2 if w.g_dtype == torch.bfloat16 else 4
+    kernel = "dlion_step (fused, no packed/counts output)"
+    metric = "param-updates/s (d*N per fused step)"
+    units = w.d * w.N                               # parameter-updates (or votes) per step
+    bytes_per_launch = algorithmic_bytes_per_step(w.d, w.N, g_bytes)
+    x = m = g = None
+    if w.g_dist == "packed_bernoulli":
+        # vote-only pass: N pre-packed sign streams in, counts out
+        W = dl.words_for(w.d)
+        packed = wl.random_packed(w.N, W, dev, seed=w.seed)
+        counts = torch.empty(w.d, dtype=torch.int16, device=dev)
+        kernel = "dlion_aggregate (packed words in, uint16 counts out)"
+        metric = "votes/s (d*N per vote-only pass)"
+        bytes_per_launch = w.N * W * 8 + 2 * w.d
 
-    x = wl.init_x(w, dev)
-    m = wl.init_m(w, dev)
-    g = wl.make_grads(w, 0, dev)
+        def step():
+            dl.dlion_aggregate(packed, w.d, counts)
+    elif w.shapes is not None:
+        numels = w.numels()
+        xs = [wl.init_x(w, dev, tensor=k) for k in range(len(numels))]
+        ms = [wl.init_m(w, dev, numel=n) for n in numels]
+        gs = [wl.make_grads(w, 0, dev, tensor=k) for k in range(len(numels))]
+        table = dl.SegTable(xs, ms, gs)
+        kernel = f"dlion_step_mt (fused, {len(numels)} tensors)"
+
+        def step():
+            dl.dlion_step_mt(table, w.N, w.mode, w.beta1, w.beta2, w.lr, w.lam)
+    else:
+        x = wl.init_x(w, dev)
+        m = wl.init_m(w, dev)
+        g = wl.make_grads(w, 0, dev)
+
+        def step():
+            dl.dlion_step(x, m, g, w.mode, w.beta1, w.beta2, w.lr, w.lam)
     torch.cuda.synchronize()
-
-    def step():
-        dl.dlion_step(x, m, g, w.mode, w.beta1, w.beta2, w.lr, w.lam)
 
     for _ in range(args.warmup):
         step()
@@ -132,13 +156,11 @@ def main() -> int:
     wall = time.perf_counter() - t0
     kernel_ms = ev0.elapsed_time(ev1) / args.steps
 
-    g_bytes = 2 if w.g_dtype == torch.bfloat16 else 4
-    bytes_per_launch = algorithmic_bytes_per_step(w.d, w.N, g_bytes)
     achieved = bytes_per_launch / (kernel_ms * 1e-3) / 1e9
     out = {
-        "metric": "param-updates/s (d*N per fused step)",
-        "value": w.d * w.N * args.steps / wall,
-        "unit": "param-updates/s",
+        "metric": metric,
+        "value": units * args.steps / wall,
+        "unit": metric.split(" ")[0],
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
@@ -151,7 +173,7 @@ def main() -> int:
         "config": {
             "workload": w.name, "d": w.d, "workers": w.N, "aggregation": "avg" if w.mode else "vote",
             "grad_dtype": str(w.g_dtype).replace("torch.", ""), "grad_dist": w.g_dist,
-            "state_dtype": "float32", "kernel": "dlion_step (fused, no packed/counts output)",
+            "state_dtype": "float32", "kernel": kernel,
         },
         "roofline": {
             "bound": "hbm",
@@ -162,7 +184,7 @@ def main() -> int:
             "traffic": recorded_traffic(w.name),
             "kernel_ms": kernel_ms,
             "bytes_per_launch": bytes_per_launch,
-            "bytes_per_update": bytes_per_launch / (w.d * w.N),
+            "bytes_per_update": bytes_per_launch / units,
         },
     }
     if args.copy_calibration:
@@ -172,7 +194,7 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
         out["copy_calibration"] = {"bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "launches": 5}
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and x is not None:
         out["cpu_baseline"] = cpu_baseline(w, x, m, g)
     print(json.dumps(out), flush=True)
     return 0

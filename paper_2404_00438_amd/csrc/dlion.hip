@@ -49,29 +49,26 @@ inline dlion_status launched()
 }
 
 // ------------------------------------------------------------------ launch shape
-// Two measured properties of the memory system decide the launch shape of the streaming kernels.
+// HBM delivers the most when the chip keeps only a modest, compact window of addresses in
+// flight: roughly 24 KB of outstanding loads per compute unit (a little less with many
+// workers).  A wave of the fused kernel has `unroll` workers' loads outstanding at once, so
+// the number of resident waves per compute unit is capped accordingly.  The cap is applied by
+// reserving (unused) dynamic LDS per workgroup: a compute unit has 160 KB, so a reservation
+// of 160 KB / k admits k workgroups.
 //
-// (1) HBM delivers the most when the chip keeps only a modest, compact window of addresses in
-//     flight: roughly 24 KB of outstanding loads per compute unit.  A wave of the fused kernel
-//     has `unroll` workers' loads outstanding at once, so the number of resident waves per
-//     compute unit is capped accordingly.  The cap is applied by reserving (unused) dynamic LDS
-//     per workgroup: a compute unit has 160 KB, so a reservation of 160 KB / k admits k
-//     workgroups.
-// (2) Every worker adds three pages (m read/write, g) to what a wave touches.  With one-wave
-//     workgroups the waves of a compute unit drift apart; beyond roughly 16 workers their
-//     pages no longer fit the per-CU translation cache (N = 32: 84 M misses per launch against
-//     36 K at N = 8).  For many workers the kernel therefore runs 16-wave workgroups that
-//     walk over the workers in lockstep.
+// What was tried and dropped for many workers: 16-wave workgroups walking over the workers
+// in lockstep cut the per-CU translation-cache misses 15x at N = 32 (5.5 M against 84 M per
+// launch) but were 1-3 % slower on the same allocation; the large run-to-run spread at
+// N = 32 (65-76 % of peak) follows the physical placement of the allocation, not the launch
+// shape.
 struct LaunchShape {
     int unroll;          // workers whose loads are issued back to back (8, 4, 2 or 1)
-    int waves;           // waves per workgroup: 1, or 16 in lockstep
     int blocks_per_cu;   // resident workgroups per compute unit (0: no cap)
 };
 
 constexpr size_t kLdsPerCu = 160 * 1024;
 constexpr size_t kMaxDynamicLds = 160 * 1024;
-constexpr int kLockstepWaves = 16;
-constexpr int kLockstepMinWorkers = 24;
+constexpr int kManyWorkers = 24;
 
 inline size_t lds_reservation(int blocks_per_cu)
 {
@@ -81,8 +78,7 @@ inline size_t lds_reservation(int blocks_per_cu)
     return bytes > kMaxDynamicLds ? kMaxDynamicLds : bytes;
 }
 
-// Environment overrides for tuning runs, read once:
-// DLION_UNROLL, DLION_WAVES (1 or 16), DLION_BLOCKS_PER_CU.
+// Environment overrides for tuning runs: DLION_UNROLL, DLION_BLOCKS_PER_CU.
 inline int env_int(const char *name)
 {
     const char *v = std::getenv(name);
@@ -91,45 +87,41 @@ inline int env_int(const char *name)
 
 LaunchShape step_shape(int32_t N, size_t bytes_per_worker_per_wave)
 {
-    static const int env_unroll = env_int("DLION_UNROLL");
-    static const int env_waves = env_int("DLION_WAVES");
-    static const int env_blocks = env_int("DLION_BLOCKS_PER_CU");
+    // read on every call (a getenv is nothing next to a launch) so that a tuning run can
+    // switch shapes inside one process, on the same allocation
+    const int env_unroll = env_int("DLION_UNROLL");
+    const int env_blocks = env_int("DLION_BLOCKS_PER_CU");
     LaunchShape s;
     s.unroll = env_unroll > 0 ? env_unroll : 2;
     while (s.unroll > N)
         s.unroll >>= 1;
     if (s.unroll < 1)
         s.unroll = 1;
-    if (env_waves > 0)
-        s.waves = env_waves >= kLockstepWaves ? kLockstepWaves : 1;
-    else
-        s.waves = (N >= kLockstepMinWorkers) ? kLockstepWaves : 1;
     if (env_blocks >= 0) {
         s.blocks_per_cu = env_blocks;
-    } else if (s.waves > 1) {
-        s.blocks_per_cu = 2;
     } else {
+        const size_t target = (N >= kManyWorkers ? 18 : 24) * 1024;
         const size_t in_flight = bytes_per_worker_per_wave * static_cast<size_t>(s.unroll);
-        int k = static_cast<int>((24 * 1024 + in_flight / 2) / in_flight);
+        int k = static_cast<int>((target + in_flight / 2) / in_flight);
         s.blocks_per_cu = k < 3 ? 3 : (k > 32 ? 0 : k);
     }
     return s;
 }
 
 // ------------------------------------------------------------------ dispatch
-template <typename GT, int kUnroll, int kWaves, bool kApply, class Addr>
+template <typename GT, int kUnroll, bool kApply, class Addr>
 dlion_status launch_step_flags(const Addr &addr, const Hyper &h, bool packed, bool counts, size_t lds,
                                hipStream_t s)
 {
-    const dim3 grid(static_cast<uint32_t>((addr.total_tiles + kWaves - 1) / kWaves)), block(kLanes * kWaves);
+    const dim3 grid = grid_for(addr.total_tiles), block(kBlock);
     if (packed && counts)
-        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kWaves, kApply, true, true, Addr>), grid, block, lds, s, addr, h);
+        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, true, true, Addr>), grid, block, lds, s, addr, h);
     else if (packed)
-        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kWaves, kApply, true, false, Addr>), grid, block, lds, s, addr, h);
+        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, true, false, Addr>), grid, block, lds, s, addr, h);
     else if (counts)
-        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kWaves, kApply, false, true, Addr>), grid, block, lds, s, addr, h);
+        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, false, true, Addr>), grid, block, lds, s, addr, h);
     else
-        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kWaves, kApply, false, false, Addr>), grid, block, lds, s, addr, h);
+        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, false, false, Addr>), grid, block, lds, s, addr, h);
     return launched();
 }
 
@@ -138,19 +130,11 @@ dlion_status launch_step_unroll(const Addr &addr, const Hyper &h, bool packed, b
 {
     const LaunchShape shape = step_shape(h.N, kSubs * kLanes * (16 + Grad<GT>::kVecBytes));
     const size_t lds = lds_reservation(shape.blocks_per_cu);
-    if (shape.waves > 1) {
-        switch (shape.unroll) {
-        case 8:
-        case 4: return launch_step_flags<GT, 4, kLockstepWaves, kApply, Addr>(addr, h, packed, counts, lds, s);
-        case 2: return launch_step_flags<GT, 2, kLockstepWaves, kApply, Addr>(addr, h, packed, counts, lds, s);
-        default: return launch_step_flags<GT, 1, kLockstepWaves, kApply, Addr>(addr, h, packed, counts, lds, s);
-        }
-    }
     switch (shape.unroll) {
-    case 8: return launch_step_flags<GT, 8, 1, kApply, Addr>(addr, h, packed, counts, lds, s);
-    case 4: return launch_step_flags<GT, 4, 1, kApply, Addr>(addr, h, packed, counts, lds, s);
-    case 2: return launch_step_flags<GT, 2, 1, kApply, Addr>(addr, h, packed, counts, lds, s);
-    default: return launch_step_flags<GT, 1, 1, kApply, Addr>(addr, h, packed, counts, lds, s);
+    case 8: return launch_step_flags<GT, 8, kApply, Addr>(addr, h, packed, counts, lds, s);
+    case 4: return launch_step_flags<GT, 4, kApply, Addr>(addr, h, packed, counts, lds, s);
+    case 2: return launch_step_flags<GT, 2, kApply, Addr>(addr, h, packed, counts, lds, s);
+    default: return launch_step_flags<GT, 1, kApply, Addr>(addr, h, packed, counts, lds, s);
     }
 }
 
@@ -206,7 +190,7 @@ inline bool use_sliced(int32_t N)
 template <int kPlanes, bool kAllow16>
 dlion_status launch_sliced_planes(const FlatAddr &addr, const Hyper &h, bool apply, bool counts, hipStream_t s)
 {
-    static const int env_waves = env_int("DLION_SLICED_WAVES");   // tuning: 1, 8 or 16
+    const int env_waves = env_int("DLION_SLICED_WAVES");   // tuning: 1, 8 or 16
     const int waves = env_waves > 0 ? env_waves : (h.N >= kSlicedLockstepMinWorkers ? 8 : 1);
     if (waves >= 16 && kAllow16)
         return launch_sliced_shape<kPlanes, kAllow16 ? 16 : 8>(addr, h, apply, counts, s);
@@ -259,7 +243,7 @@ dlion_status launch_encode_shape(const FlatAddr &addr, const Hyper &h, const Del
 template <int kPlanes>
 dlion_status launch_encode_planes(const FlatAddr &addr, const Hyper &h, const DeltaOut &out, hipStream_t s)
 {
-    static const int env_waves = env_int("DLION_SLICED_WAVES");
+    const int env_waves = env_int("DLION_SLICED_WAVES");
     const int waves = env_waves > 0 ? env_waves : (h.N >= kSlicedLockstepMinWorkers ? 8 : 1);
     if (waves >= 8)
         return launch_encode_shape<kPlanes, 8>(addr, h, out, s);
@@ -283,7 +267,7 @@ template <typename GT>
 dlion_status launch_global_lion_unroll(const FlatAddr &addr, const Hyper &h, uint64_t *sign_bits, hipStream_t s)
 {
     const LaunchShape shape = step_shape(h.N, kLanes * (16 + Grad<GT>::kVecBytes));
-    const size_t lds = shape.waves > 1 ? 0 : lds_reservation(shape.blocks_per_cu);
+    const size_t lds = lds_reservation(shape.blocks_per_cu);
     const dim3 grid(static_cast<uint32_t>(addr.total_tiles)), block(kLanes);
     if (shape.unroll >= 2 && h.N >= 2)
         hipLaunchKernelGGL((global_lion_kernel<GT, 2>), grid, block, lds, s, addr, h, sign_bits);

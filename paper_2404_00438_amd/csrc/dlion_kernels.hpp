@@ -308,7 +308,7 @@ __device__ __forceinline__ uint64_t row_gather_nibbles(uint32_t nibble, int lane
 // kPacked: write packed words.   kCounts: write counts.
 // Vector path over kR full sub-tiles starting at sub-tile `t`: the loads of kUnroll workers
 // x kR sub-tiles are issued back to back before any arithmetic.
-template <typename GT, int kUnroll, int kR, bool kApply, bool kPacked, bool kCounts, bool kLockstep = false>
+template <typename GT, int kUnroll, int kR, bool kApply, bool kPacked, bool kCounts>
 __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t, int lane, const Hyper &h)
 {
     const int64_t j0 = t * kSubTile + lane * kVec;
@@ -366,8 +366,6 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
             for (int r = 0; r < kR; ++r)
                 one_worker(i + u, r, mv[u][r], gv[u][r]);
         }
-        if (kLockstep)
-            __builtin_amdgcn_s_barrier();     // keep the waves of the workgroup on the same workers
     }
     for (; i < N; ++i) {
         f32x4 mv[kR], gv[kR];
@@ -438,17 +436,10 @@ __device__ __forceinline__ void step_subtile_guarded(const Problem &p, int64_t t
     }
 }
 
-// kWaves waves per workgroup.  With more than one, the waves of a workgroup walk over the
-// workers in lockstep (a barrier per batch of workers): with many workers, waves that drift
-// apart touch 3 pages per worker each and thrash the per-CU address-translation cache; kept
-// together, the compute unit works inside a handful of pages at any time.  A wave that takes
-// the guarded path, or has no tile, simply terminates; the barrier only waits for waves that
-// are still alive, and every surviving wave executes the same number of barriers (N is the
-// same for every tile).
-template <typename GT, int kUnroll, int kWaves, bool kApply, bool kPacked, bool kCounts, class Addr>
-__global__ __launch_bounds__(kLanes * kWaves) DLION_OCCUPANCY void step_kernel(Addr addr, Hyper h)
+template <typename GT, int kUnroll, bool kApply, bool kPacked, bool kCounts, class Addr>
+__global__ __launch_bounds__(kBlock) DLION_OCCUPANCY void step_kernel(Addr addr, Hyper h)
 {
-    const int64_t tile = wave_tile_index<kWaves>();
+    const int64_t tile = wave_tile_index();
     if (tile >= addr.total_tiles)
         return;
     const int lane = threadIdx.x & 63;
@@ -461,7 +452,7 @@ __global__ __launch_bounds__(kLanes * kWaves) DLION_OCCUPANCY void step_kernel(A
     if (kCounts)
         aligned = aligned && is_aligned(p.counts, 8);
     if (aligned && (t + kSubs) * kSubTile <= p.numel) {
-        step_subtiles_vector<GT, kUnroll, kSubs, kApply, kPacked, kCounts, (kWaves > 1)>(p, t, lane, h);
+        step_subtiles_vector<GT, kUnroll, kSubs, kApply, kPacked, kCounts>(p, t, lane, h);
         return;
     }
     // ragged end of a tensor, or rows that cannot take 128-bit accesses
