@@ -40,12 +40,6 @@ namespace dlion {
 #ifndef DLION_NT_STORE
 #define DLION_NT_STORE 1        // streaming stores of m
 #endif
-#ifndef DLION_MAX_WAVES_PER_EU
-#define DLION_MAX_WAVES_PER_EU 0   // cap on resident waves per SIMD for the streaming kernels (0: no cap)
-#endif
-#ifndef DLION_XCD_REMAP
-#define DLION_XCD_REMAP 0       // give each of the 8 XCDs one contiguous range of tiles
-#endif
 
 constexpr int kLanes = 64;
 constexpr int kVec = 4;                       // coordinates per lane per sub-tile on the vector path
@@ -55,13 +49,7 @@ constexpr int kSubs = DLION_SUBTILES;
 constexpr int kTile = kSubTile * kSubs;       // coordinates one wave owns
 constexpr int kWavesPerBlock = DLION_WAVES_PER_BLOCK;
 constexpr int kBlock = kLanes * kWavesPerBlock;
-constexpr int kXcds = 8;
 
-#if DLION_MAX_WAVES_PER_EU > 0
-#define DLION_OCCUPANCY __attribute__((amdgpu_waves_per_eu(1, DLION_MAX_WAVES_PER_EU)))
-#else
-#define DLION_OCCUPANCY
-#endif
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -149,13 +137,12 @@ template <int kWaves = kWavesPerBlock> __device__ __forceinline__ int64_t wave_t
     // blockIdx and the wave number are uniform across the wavefront; say so, so
     // that everything derived from the tile index stays in scalar registers.
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    uint32_t block = blockIdx.x;
-#if DLION_XCD_REMAP
-    // Workgroups are handed to the 8 XCDs round-robin (block b runs on XCD b % 8).
-    // Renumber them so that XCD x walks one contiguous range of tiles.
-    const uint32_t G = gridDim.x, q = G / kXcds, r = G % kXcds, xcd = block % kXcds;
-    block = xcd * q + (xcd < r ? xcd : r) + block / kXcds;
-#endif
+    // Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b % 8), so
+    // with the plain numbering all XCDs work inside the same narrow window of addresses.
+    // That is what DRAM page locality wants: renumbering so that every XCD walks its own
+    // contiguous eighth of the tiles costs 15 % of the bandwidth, and grouping 4 consecutive
+    // tiles per XCD (to merge the 32-byte packed writes in one L2) changes nothing.
+    const uint32_t block = blockIdx.x;
     return (int64_t)block * kWaves + wave;
 }
 
@@ -437,7 +424,7 @@ __device__ __forceinline__ void step_subtile_guarded(const Problem &p, int64_t t
 }
 
 template <typename GT, int kUnroll, bool kApply, bool kPacked, bool kCounts, class Addr>
-__global__ __launch_bounds__(kBlock) DLION_OCCUPANCY void step_kernel(Addr addr, Hyper h)
+__global__ __launch_bounds__(kBlock) void step_kernel(Addr addr, Hyper h)
 {
     const int64_t tile = wave_tile_index();
     if (tile >= addr.total_tiles)
