@@ -28,7 +28,7 @@ def algorithmic_bytes_per_step(d: int, N: int, g_bytes: int) -> int:
     return d * N * (4 + 4 + g_bytes) + 8 * d
 
 
-def cpu_baseline(w, x, m, g, seconds_target: float = 15.0):
+def cpu_baseline(w, x, m, g, seconds_target: float = 12.0):
     """Time the CPU oracle (as it stands) on the first coordinates of the same workload."""
     import numpy as np
     import torch
@@ -36,7 +36,7 @@ def cpu_baseline(w, x, m, g, seconds_target: float = 15.0):
     import oracle
 
     cores = min(len(os.sched_getaffinity(0)), 16)
-    d_s = min(w.d, 4_000_000)
+    d_s = min(w.d, 16_000_000)
     xs = x[:d_s].cpu().numpy().copy()
     ms = m[:, :d_s].cpu().numpy().copy()
     gc = g[:, :d_s].cpu().contiguous()
@@ -45,7 +45,7 @@ def cpu_baseline(w, x, m, g, seconds_target: float = 15.0):
     t0 = time.perf_counter()
     oracle.step(xs.copy(), ms.copy(), gs, w.mode, w.beta1, w.beta2, w.lr, w.lam, threads=cores)
     one = max(time.perf_counter() - t0, 1e-6)
-    reps = max(1, min(200, int(seconds_target / one)))
+    reps = max(1, min(400, int(seconds_target / one)))
     t0 = time.perf_counter()
     for _ in range(reps):
         oracle.step(xs, ms, gs, w.mode, w.beta1, w.beta2, w.lr, w.lam, threads=cores)

@@ -332,3 +332,60 @@ def test_many_worker_aggregate_matches_oracle():
                 assert_f32_equal(to_np(x), xn, f"N={N} d={d} mode={mode}: x")
                 if mode == dl.AVG:
                     assert np.array_equal(to_np(counts2), want)
+
+
+def test_randomized_shapes_strides_and_flags():
+    """Seeded random sweep over d, N, row strides (aligned or not), gradient dtype, aggregation and
+    optional outputs, two steps each, fused and unfused, against the oracle."""
+    rng = np.random.default_rng(20240400)
+    for case in range(120):
+        N = int(rng.choice([1, 2, 3, 4, 6, 8, 11, 16, 24, 40]))
+        d = int(rng.choice([rng.integers(1, 300), rng.integers(300, 5000), rng.integers(5000, 40_000)]))
+        g_dtype = torch.bfloat16 if rng.random() < 0.5 else torch.float32
+        mode = dl.AVG if rng.random() < 0.5 else dl.VOTE
+        m_stride = d + int(rng.choice([0, 1, 2, 3, 4, 64 - d % 64, 257]))
+        g_stride = d + int(rng.choice([0, 1, 2, 4, 8, 64 - d % 64, 100]))
+        want_p, want_c = bool(rng.random() < 0.6), bool(rng.random() < 0.6)
+        hyp = dict(beta1=float(rng.choice([0.0, 0.5, 0.9, 0.95])), beta2=float(rng.choice([0.9, 0.99, 0.999])),
+                   lr=float(rng.choice([1e-5, 3e-4, 1e-2])), lam=float(rng.choice([0.0, 0.1, 10.0])))
+        announce("random", case, "N", N, "d", d, g_dtype, "mode", mode, "strides", m_stride, g_stride,
+                 "p", want_p, "c", want_c, hyp)
+        x, m, g = draw_state(rng, N, d, g_dtype, m_stride, g_stride, scale=float(rng.choice([1e-3, 1.0])))
+        W = dl.words_for(d)
+        for step in range(2):
+            xn, mn, pn, cn = oracle_step(x, m, g, mode, hyp)
+            # unfused on copies
+            x_u, m_u = x.clone(), m.clone()
+            packed_u = torch.full((N, W), -1, dtype=torch.int64, device=DEV)
+            dl.dlion_worker_step(m_u, g, packed_u, hyp["beta1"], hyp["beta2"])
+            dl.dlion_aggregate_apply(x_u, packed_u, mode, hyp["lr"], hyp["lam"])
+            # fused in place
+            packed = torch.full((N, W), -1, dtype=torch.int64, device=DEV) if want_p else None
+            counts = torch.full((d,), -1, dtype=torch.int16, device=DEV) if want_c else None
+            dl.dlion_step(x, m, g, mode, hyp["beta1"], hyp["beta2"], hyp["lr"], hyp["lam"],
+                          packed=packed, counts=counts)
+            torch.cuda.synchronize()
+            compare_all(f"random {case} fused", x, m, packed, counts, xn, mn, pn, cn)
+            compare_all(f"random {case} unfused", x_u, m_u, packed_u, None, xn, mn, pn, cn)
+            g.copy_(torch.from_numpy(rng.standard_t(3, (N, d)).astype(np.float32) * 1e-3).to(g_dtype))
+
+
+def test_calls_follow_the_given_stream():
+    """Work is enqueued on the stream that is passed (torch's current stream in the binding):
+    a step issued on a side stream after an event sees the data written before that event."""
+    rng = np.random.default_rng(8)
+    N, d = 4, 300_003
+    x, m, g = draw_state(rng, N, d, torch.float32, d + 1, d + 3)
+    xn, mn, pn, cn = oracle_step(x, m, g, dl.VOTE, HYP)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    packed = torch.zeros((N, dl.words_for(d)), dtype=torch.int64, device=DEV)
+    counts = torch.zeros(d, dtype=torch.int16, device=DEV)
+    with torch.cuda.stream(side):
+        packed.zero_()
+        dl.dlion_step(x, m, g, dl.VOTE, HYP["beta1"], HYP["beta2"], HYP["lr"], HYP["lam"],
+                      packed=packed, counts=counts)
+        done = torch.cuda.Event()
+        done.record()
+    done.synchronize()
+    compare_all("side stream", x, m, packed, counts, xn, mn, pn, cn)
