@@ -181,10 +181,11 @@ dlion_status launch_sliced_shape(const FlatAddr &addr, const Hyper &h, bool appl
 constexpr int kSlicedMinWorkers = 8;    // below this the per-nibble kernel is cheaper
 constexpr int kSlicedLockstepMinWorkers = 64;   // measured: 1 wave wins at N = 32, 8 waves at N = 256
 
-inline bool use_sliced(int32_t N)
+// measured crossover: counts only -> N >= 8; with the weight update fused -> N >= 16
+inline bool use_sliced(int32_t N, bool apply)
 {
-    static const int env_min = env_int("DLION_SLICED_MIN_WORKERS");
-    return N >= (env_min >= 0 ? env_min : kSlicedMinWorkers);
+    const int env_min = env_int("DLION_SLICED_MIN_WORKERS");
+    return N >= (env_min >= 0 ? env_min : (apply ? 2 * kSlicedMinWorkers : kSlicedMinWorkers));
 }
 
 template <int kPlanes, bool kAllow16>
@@ -408,7 +409,7 @@ dlion_status dlion_aggregate(const uint64_t *packed, int64_t packed_stride, int6
     h.stream_counts = counts_exceed_cache(d);
     const FlatAddr a = flat_addr(nullptr, nullptr, 0, nullptr, 0, d, const_cast<uint64_t *>(packed),
                                  packed_stride, counts);
-    if (use_sliced(N))
+    if (use_sliced(N, false))
         return launch_sliced(a, h, false, true, static_cast<hipStream_t>(stream));
     return launch_aggregate(a, h, false, true, static_cast<hipStream_t>(stream));
 }
@@ -440,7 +441,7 @@ dlion_status dlion_aggregate_apply(float *x, const uint64_t *packed, int64_t pac
     h.stream_counts = counts_or_null ? counts_exceed_cache(d) : 0;
     const FlatAddr a = flat_addr(x, nullptr, 0, nullptr, 0, d, const_cast<uint64_t *>(packed), packed_stride,
                                  counts_or_null);
-    if (use_sliced(N))
+    if (use_sliced(N, true))
         return launch_sliced(a, h, true, counts_or_null != nullptr, static_cast<hipStream_t>(stream));
     return launch_aggregate(a, h, true, counts_or_null != nullptr, static_cast<hipStream_t>(stream));
 }

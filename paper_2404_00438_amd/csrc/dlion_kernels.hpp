@@ -622,21 +622,26 @@ __device__ __forceinline__ void sliced_count(const Problem &p, int N, int64_t w0
 
     for (int i = 0; i < N; i += 16) {
         uint32_t v[16][kSlices];
-        if (fast && i + 16 <= N) {
+        if (fast) {
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
-                // uniform row base + small per-lane offset
-                const uint64_t *row = p.packed + (int64_t)(i + k) * p.packed_stride + w0;
-                if (kWpl == 2) {
-                    const u32x4 r = stream_load(reinterpret_cast<const u32x4 *>(row) + lane);
-                    v[k][0] = r.x;
-                    v[k][1] = r.y;
-                    v[k][kSlices - 2] = r.z;
-                    v[k][kSlices - 1] = r.w;
-                } else {
-                    const u32x2 r = stream_load(reinterpret_cast<const u32x2 *>(row) + lane);
-                    v[k][0] = r.x;
-                    v[k][1] = r.y;
+#pragma unroll
+                for (int q = 0; q < kSlices; ++q)
+                    v[k][q] = 0;
+                if (i + k < N) {                             // uniform: rows past N contribute zeros
+                    // uniform row base + small per-lane offset
+                    const uint64_t *row = p.packed + (int64_t)(i + k) * p.packed_stride + w0;
+                    if (kWpl == 2) {
+                        const u32x4 r = stream_load(reinterpret_cast<const u32x4 *>(row) + lane);
+                        v[k][0] = r.x;
+                        v[k][1] = r.y;
+                        v[k][kSlices - 2] = r.z;
+                        v[k][kSlices - 1] = r.w;
+                    } else {
+                        const u32x2 r = stream_load(reinterpret_cast<const u32x2 *>(row) + lane);
+                        v[k][0] = r.x;
+                        v[k][1] = r.y;
+                    }
                 }
             }
         } else {
