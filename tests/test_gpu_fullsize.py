@@ -206,3 +206,79 @@ def test_vote_only_256_streams_full_size():
         del x
     print(f"{w.name}: counts bit-exact on {sum(b - a for a, b in ranges)} sampled coordinates; "
           f"sum(counts) equals the popcount of all {N * W} words", flush=True)
+
+
+def test_unfused_and_wider_rows_full_size():
+    """d = 1.3 B, N = 8: the unfused pipeline, the down-link planes, per-worker coefficients and
+    Global Lion at a size where one stream is more than 2^32 bytes long, on sampled chunks."""
+    w = wl.CONFIGS["stress1p3b_vote8"]
+    d, N = w.d, w.N
+    W = dl.words_for(d)
+    announce("unfused + wider rows", "d", d, "N", N)
+    ranges = sample_chunks(d, 16, seed=5)
+    x = wl.init_x(w, DEV)
+    m = wl.init_m(w, DEV)
+    m.normal_(0, 1e-3)
+    g = wl.make_grads(w, 0, DEV)
+    x0h, m0h, gh = to_np(gather(x, ranges)), to_np(gather(m, ranges)), to_np(gather(g, ranges))
+    hyp = (w.beta1, w.beta2, w.lr, w.lam)
+
+    # 1. worker_step -> aggregate -> apply, and aggregate_encode -> apply_encoded, both modes
+    m1 = m.clone()
+    packed = torch.empty((N, W), dtype=torch.int64, device=DEV)
+    counts = torch.empty(d, dtype=torch.int16, device=DEV)
+    dl.dlion_worker_step(m1, g, packed, w.beta1, w.beta2)
+    dl.dlion_aggregate(packed, d, counts)
+    torch.cuda.synchronize()
+    mh = m0h.copy()
+    ph = oracle.worker_step(mh, gh, w.beta1, w.beta2)
+    ch = oracle.aggregate_packed(ph, ph.shape[1] * 64)[: x0h.shape[0]]
+    assert np.array_equal(to_np(gather_words(packed, ranges)), ph)
+    assert np.array_equal(to_np(gather(counts, ranges)), ch)
+    assert_f32_equal(to_np(gather(m1, ranges)), mh, "worker_step: m")
+    del m1
+    for mode in (dl.VOTE, dl.AVG):
+        xa = x.clone()
+        dl.dlion_apply(xa, counts, N, mode, w.lr, w.lam)
+        xh = x0h.copy()
+        oracle.apply(xh, ch, N, mode, w.lr, w.lam)
+        torch.cuda.synchronize()
+        assert_f32_equal(to_np(gather(xa, ranges)), xh, f"apply mode {mode}: x")
+        P = dl.dlion_delta_planes(N, mode)
+        delta = torch.empty((P, W), dtype=torch.int64, device=DEV)
+        dl.dlion_aggregate_encode(packed, d, mode, delta)
+        xa.copy_(x)
+        dl.dlion_apply_encoded(xa, delta, N, mode, w.lr, w.lam)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(gather_words(delta, ranges)), oracle.encode_delta(ch, N, mode))
+        assert_f32_equal(to_np(gather(xa, ranges)), xh, f"apply_encoded mode {mode}: x")
+        del xa, delta
+    del packed, counts
+    torch.cuda.empty_cache()
+    print("  unfused pipeline and down-link ok", flush=True)
+
+    # 2. per-worker coefficients, fused
+    b1 = np.array([0.9, 0.5, 0.95, 0.8, 0.9, 0.0, 1.0, 0.99], np.float32)
+    b2 = np.array([0.99, 0.75, 0.98, 0.8, 0.999, 0.5, 0.25, 0.99], np.float32)
+    m2, x2 = m.clone(), x.clone()
+    dl.dlion_step_pw(x2, m2, g, dl.VOTE, torch.from_numpy(b1).to(DEV), torch.from_numpy(b2).to(DEV), w.lr, w.lam)
+    torch.cuda.synchronize()
+    mh, xh = m0h.copy(), x0h.copy()
+    ph = oracle.worker_step_pw(mh, gh, b1, b2)
+    oracle.apply(xh, oracle.aggregate_packed(ph, ph.shape[1] * 64)[: xh.shape[0]], N, oracle.VOTE, w.lr, w.lam)
+    assert_f32_equal(to_np(gather(m2, ranges)), mh, "step_pw: m")
+    assert_f32_equal(to_np(gather(x2, ranges)), xh, "step_pw: x")
+    del m2, x2
+    torch.cuda.empty_cache()
+    print("  per-worker coefficients ok", flush=True)
+
+    # 3. Global Lion, in place on the originals
+    bits = torch.empty(W, dtype=torch.int64, device=DEV)
+    dl.dlion_global_lion_step(x, m, g, *hyp, sign_bits=bits)
+    torch.cuda.synchronize()
+    mh, xh = m0h.copy(), x0h.copy()
+    bh = oracle.global_lion_step(xh, mh, gh, *hyp)
+    assert np.array_equal(to_np(gather_words(bits, ranges)), bh)
+    assert_f32_equal(to_np(gather(m, ranges)), mh, "global lion: m")
+    assert_f32_equal(to_np(gather(x, ranges)), xh, "global lion: x")
+    print("  Global Lion ok", flush=True)
