@@ -64,17 +64,21 @@ def recorded_traffic(workload: str):
 
     The counters cannot be read from inside this process; the figure is the one
     measured with ``rocprofv3 --pmc FETCH_SIZE`` / ``WRITE_SIZE`` over this very
-    script and written into ``profiles/dlion_step_<workload>.md``.
+    script and written into ``profiles/<kernel>_<workload>.md``.
     """
     import re
 
-    path = os.path.join(ROOT, "profiles", f"dlion_step_{workload}.md")
-    try:
-        with open(path) as f:
-            m = re.search(r"traffic_bytes_per_launch:\s*(\d+)", f.read())
-        return int(m.group(1)) if m else None
-    except OSError:
-        return None
+    import glob
+
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", f"*_{workload}.md"))):
+        try:
+            with open(path) as f:
+                m = re.search(r"traffic_bytes_per_launch:\s*(\d+)", f.read())
+        except OSError:
+            continue
+        if m:
+            return int(m.group(1))
+    return None
 
 
 def main() -> int:
