@@ -611,7 +611,7 @@ dlion_status dlion_apply_encoded(float *x, const uint64_t *delta, int64_t delta_
     const Hyper h = make_hyper(N, mode, 0.0f, 0.0f, lr, lambda);
     const FlatAddr a = flat_addr(x, nullptr, 0, nullptr, 0, d, nullptr, 0, nullptr);
     const DeltaOut in = {const_cast<uint64_t *>(delta), delta_stride, planes};
-    const dim3 grid(static_cast<uint32_t>(a.total_tiles)), block(kLanes);
+    const dim3 grid(static_cast<uint32_t>((d + kLineCoords - 1) / kLineCoords)), block(kLanes);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (planes <= 2)
         hipLaunchKernelGGL(apply_encoded_kernel<2>, grid, block, 0, s, a, h, in);

@@ -34,6 +34,9 @@ namespace dlion {
 #ifndef DLION_WAVES_PER_BLOCK
 #define DLION_WAVES_PER_BLOCK 1
 #endif
+#ifndef DLION_XCD_QUADS
+#define DLION_XCD_QUADS 1       // readers of packed rows: 4 consecutive tiles on one XCD
+#endif
 #ifndef DLION_NT_LOAD
 #define DLION_NT_LOAD 1         // streaming (non-temporal) loads of m and g
 #endif
@@ -131,6 +134,23 @@ struct SegAddr {
         return tile - s.tile_begin;
     }
 };
+
+// Tile numbering for kernels that READ bit-packed rows.  A tile needs only 32 bytes of each
+// packed row, a quarter of a 128-byte line, and every XCD has its own L2: with the plain
+// numbering the four quarters of a line are fetched by four different L2s, i.e. up to four
+// times from memory.  Within every group of 32 workgroups, XCD x (workgroups b with b % 8 == x)
+// takes tiles 4x..4x+3 instead, so the line is fetched once.  Groups stay in order, so the
+// window of addresses in flight remains compact.
+__device__ __forceinline__ int64_t quad_tile_index()
+{
+    uint32_t block = blockIdx.x;
+#if DLION_XCD_QUADS
+    const uint32_t group = block & ~31u;
+    if (group + 32 <= gridDim.x)                           // whole group of 32 exists
+        block = group + ((block & 7u) << 2) + ((block >> 3) & 3u);
+#endif
+    return block;
+}
 
 template <int kWaves = kWavesPerBlock> __device__ __forceinline__ int64_t wave_tile_index()
 {
@@ -542,7 +562,7 @@ __device__ __forceinline__ void agg_subtile_guarded(const Problem &p, int64_t t,
 template <bool kApply, bool kCounts, class Addr>
 __global__ __launch_bounds__(kBlock) void aggregate_kernel(Addr addr, Hyper h)
 {
-    const int64_t tile = wave_tile_index();
+    const int64_t tile = kWavesPerBlock == 1 ? quad_tile_index() : wave_tile_index();
     if (tile >= addr.total_tiles)
         return;
     const int lane = threadIdx.x & 63;
@@ -879,57 +899,72 @@ __device__ __forceinline__ float decode_vote(uint32_t plus, uint32_t tie)
     return plus ? 1.0f : (tie ? 0.0f : -1.0f);
 }
 
+// One wave owns kLineSubs = 4 consecutive sub-tiles = 16 words = one 128-byte line of every
+// plane, so that each line is read by exactly one wave (and one L2): lane l loads dword
+// (l & 31) of the line, and for sub-tile s takes the dword that holds its nibble from lane
+// 8s + (l >> 3) with a lane permute.
+constexpr int kLineSubs = 4;
+constexpr int kLineCoords = kLineSubs * kSubTile;   // 1024
+
 template <int kMaxPlanes>
 __global__ __launch_bounds__(kLanes) void apply_encoded_kernel(FlatAddr addr, Hyper h, DeltaOut in)
 {
     const Problem &p = addr.p;
-    const int64_t t = blockIdx.x;                               // one wave per tile
+    const int64_t t = blockIdx.x;                               // line index
     const int lane = threadIdx.x;
-    const bool full = (t + 1) * kSubTile <= p.numel && is_aligned(p.x, 16);
+    const bool full = (t + 1) * kLineCoords <= p.numel && is_aligned(p.x, 16);
     if (full) {
-        const int64_t j0 = t * kSubTile + lane * kVec;
-        const int64_t dword = 2 * (t * kWordsPerSub + (lane >> 4)) + ((lane >> 3) & 1);
-        const int shift = (lane & 7) * 4;
         // all planes' loads first (n_planes <= kMaxPlanes; the test is uniform)
         uint32_t raw[kMaxPlanes];
 #pragma unroll
         for (int b = 0; b < kMaxPlanes; ++b) {
-            const uint32_t *plane = reinterpret_cast<const uint32_t *>(in.planes + (int64_t)b * in.stride);
-            raw[b] = b < in.n_planes ? plane[dword] : 0u;
+            const uint32_t *line = reinterpret_cast<const uint32_t *>(in.planes + (int64_t)b * in.stride +
+                                                                      t * (kLineSubs * kWordsPerSub));
+            raw[b] = b < in.n_planes ? line[lane & 31] : 0u;
         }
-        float Delta[4];
-        if (h.mode == DLION_VOTE) {
-            const uint32_t plus = (raw[0] >> shift) & 0xFu;
-            const uint32_t tie = (raw[1] >> shift) & 0xFu;
+        f32x4 xv[kLineSubs];
 #pragma unroll
-            for (int k = 0; k < 4; ++k)
-                Delta[k] = decode_vote((plus >> k) & 1u, (tie >> k) & 1u);
-        } else {
-            uint32_t lo = 0, up = 0;
+        for (int s = 0; s < kLineSubs; ++s)
+            xv[s] = X_LOAD(reinterpret_cast<const f32x4 *>(p.x + t * kLineCoords + s * kSubTile + lane * kVec));
+        const int shift = (lane & 7) * 4;
 #pragma unroll
-            for (int b = 0; b < kMaxPlanes; ++b) {
-                const uint32_t bytes = nibble_to_bytes((raw[b] >> shift) & 0xFu);
-                if (b < 8)
-                    lo += bytes << b;
-                else
-                    up += bytes << (b - 8);
+        for (int s = 0; s < kLineSubs; ++s) {
+            const int from = (8 * s + (lane >> 3)) << 2;       // byte address of the source lane
+            float Delta[4];
+            if (h.mode == DLION_VOTE) {
+                const uint32_t plus = (static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(from, raw[0])) >> shift) & 0xFu;
+                const uint32_t tie = (static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(from, raw[kMaxPlanes > 1 ? 1 : 0])) >> shift) & 0xFu;
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    Delta[k] = decode_vote((plus >> k) & 1u, in.n_planes > 1 ? (tie >> k) & 1u : 0u);
+            } else {
+                uint32_t lo = 0, up = 0;
+#pragma unroll
+                for (int b = 0; b < kMaxPlanes; ++b) {
+                    const uint32_t dw = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(from, raw[b]));
+                    const uint32_t bytes = nibble_to_bytes((dw >> shift) & 0xFu);
+                    if (b < 8)
+                        lo += bytes << b;
+                    else
+                        up += bytes << (b - 8);
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    Delta[k] = aggregate_votes(((lo >> (8 * k)) & 0xFFu) | (((up >> (8 * k)) & 0xFFu) << 8), h);
             }
-#pragma unroll
-            for (int k = 0; k < 4; ++k)
-                Delta[k] = aggregate_votes(((lo >> (8 * k)) & 0xFFu) | (((up >> (8 * k)) & 0xFFu) << 8), h);
+            xv[s].x = lion_apply(xv[s].x, Delta[0], h);
+            xv[s].y = lion_apply(xv[s].y, Delta[1], h);
+            xv[s].z = lion_apply(xv[s].z, Delta[2], h);
+            xv[s].w = lion_apply(xv[s].w, Delta[3], h);
+            X_STORE(xv[s], reinterpret_cast<f32x4 *>(p.x + t * kLineCoords + s * kSubTile + lane * kVec));
         }
-        f32x4 xv = X_LOAD(reinterpret_cast<const f32x4 *>(p.x + j0));
-        xv.x = lion_apply(xv.x, Delta[0], h);
-        xv.y = lion_apply(xv.y, Delta[1], h);
-        xv.z = lion_apply(xv.z, Delta[2], h);
-        xv.w = lion_apply(xv.w, Delta[3], h);
-        X_STORE(xv, reinterpret_cast<f32x4 *>(p.x + j0));
         return;
     }
+    // ragged end or unaligned x: lane l owns bit l of one word at a time
     const int64_t W = (p.numel + 63) >> 6;
 #pragma unroll 1
-    for (int k = 0; k < kWordsPerSub; ++k) {
-        const int64_t w = t * kWordsPerSub + k;
+    for (int k = 0; k < kLineSubs * kWordsPerSub; ++k) {
+        const int64_t w = t * (kLineSubs * kWordsPerSub) + k;
         if (w >= W)
             break;
         const int64_t j = w * 64 + lane;
