@@ -25,8 +25,8 @@
  * Workers.  Worker i's momentum is m + i*m_stride, its gradient g + i*g_stride,
  *           its packed update packed + i*packed_stride; strides count ELEMENTS
  *           of the respective type (fp32 / g_dtype / uint64) and must be
- *           >= d (>= W for packed).  Any stride is accepted; rows whose base is
- *           16-byte aligned with a stride that keeps it so take the 128-bit path.
+ *           >= d (>= W for packed).  Any stride is accepted: bases and strides
+ *           need only the alignment of the element type.
  * Sign.     The worker's sign maps 0 (and -0, and NaN) to +1, so that delta is
  *           one bit:  bit = !(c < 0).
  * Packing.  W = ceil(d/64) uint64 words per worker; bit (j % 64) of word (j / 64),

@@ -69,6 +69,7 @@ struct LaunchShape {
 constexpr size_t kLdsPerCu = 160 * 1024;
 constexpr size_t kMaxDynamicLds = 160 * 1024;
 constexpr int kManyWorkers = 24;
+constexpr int64_t kResidentWaves = 256 * 32;   // one-wave workgroups the 256 compute units hold at once
 
 inline size_t lds_reservation(int blocks_per_cu)
 {
@@ -125,21 +126,14 @@ dlion_status launch_step_flags(const Addr &addr, const Hyper &h, bool packed, bo
     return launched();
 }
 
-// Rows that cannot take 128-bit accesses run the guarded dword path on every tile; that path
-// is latency-bound and wants all the waves it can get, so the occupancy cap is dropped for it
-// (tiny workload, d = 1,000,003 with contiguous rows: 31 -> 15.5 us).
-inline bool rows_take_vector_path(const FlatAddr &a, size_t g_vec_bytes)
-{
-    return aligned_to(a.p.m, 16) && (a.p.m_stride & 3) == 0 && aligned_to(a.p.g, g_vec_bytes) &&
-           (a.p.g_stride & 3) == 0;
-}
-inline bool rows_take_vector_path(const SegAddr &, size_t) { return true; }   // decided per tensor on the device
-
 template <typename GT, bool kApply, class Addr>
 dlion_status launch_step_unroll(const Addr &addr, const Hyper &h, bool packed, bool counts, hipStream_t s)
 {
     LaunchShape shape = step_shape(h.N, kSubs * kLanes * (16 + Grad<GT>::kVecBytes));
-    if (env_int("DLION_BLOCKS_PER_CU") < 0 && !rows_take_vector_path(addr, Grad<GT>::kVecBytes))
+    // A problem whose waves all fit on the chip at once never reaches the steady state the cap
+    // is tuned for; it is latency-bound and wants every wave resident (d = 1,000,003, N = 4:
+    // 12.7 -> 10.4 us).
+    if (env_int("DLION_BLOCKS_PER_CU") < 0 && addr.total_tiles <= kResidentWaves)
         shape.blocks_per_cu = 0;
     const size_t lds = lds_reservation(shape.blocks_per_cu);
     switch (shape.unroll) {

@@ -7,13 +7,13 @@
 // or barriers are needed anywhere on the worker/fused path.
 //
 // Two code paths per tile:
-//   * vector path (full tile, 16-byte aligned rows): lane l owns coordinates
-//     4l..4l+3 and moves them with one 128-bit access per stream.  Its four
-//     sign bits form a nibble; the nibbles of the 16 lanes of a DPP row are
-//     OR-combined into one canonical packed word per row.
-//   * guarded path (ragged last tile, or rows that are not 16-byte aligned):
-//     lane l owns coordinates 64k+l, k=0..3, moved with dword accesses; a
-//     64-lane ballot of the sign predicate is already a canonical packed word.
+//   * vector path (full tile): lane l owns coordinates 4l..4l+3 and moves them
+//     with one 128-bit access per stream, whatever the alignment of the rows.
+//     Its four sign bits form a nibble; the nibbles of the 16 lanes of a DPP
+//     row are OR-combined into one canonical packed word per row.
+//   * guarded path (ragged last tile of a tensor): lane l owns coordinates
+//     64k+l, k=0..3, moved with dword accesses; a 64-lane ballot of the sign
+//     predicate is already a canonical packed word.
 //
 // All fp32 arithmetic goes through __fmul_rn/__fadd_rn/__fsub_rn so that no
 // multiply-add is ever fused (Section 3.2's expressions, each operation rounded
@@ -173,22 +173,6 @@ template <int kWaves = kWavesPerBlock> __device__ __forceinline__ int64_t wave_t
 #ifndef DLION_NT_X
 #define DLION_NT_X 1
 #endif
-#define C_STORE(v, p)                              \
-    do {                                           \
-        if (h.stream_counts)                       \
-            __builtin_nontemporal_store(v, p);     \
-        else                                       \
-            *(p) = (v);                            \
-    } while (0)
-#define C_LOAD(p) (*(p))
-#if DLION_NT_X
-#define X_STORE(v, p) __builtin_nontemporal_store(v, p)
-#define X_LOAD(p) __builtin_nontemporal_load(p)
-#else
-#define X_STORE(v, p) (*(p) = (v))
-#define X_LOAD(p) (*(p))
-#endif
-
 template <typename T> __device__ __forceinline__ T stream_load(const T *p)
 {
 #if DLION_NT_LOAD
@@ -206,10 +190,69 @@ template <typename T> __device__ __forceinline__ void stream_store(T v, T *p)
 #endif
 }
 
-__device__ __forceinline__ bool is_aligned(const void *p, uint64_t a)
+// Four consecutive elements of a row, of x or of the counts, in one access.  The callers'
+// arrays are only promised the alignment of their element type (rows of a contiguous [N, d]
+// array with d not a multiple of 4 start anywhere), so the vector types used for the access
+// carry the element's alignment: the compiler still selects one 128-bit (or 64-bit)
+// instruction, which global memory on this target accepts at any alignment, and assumes
+// nothing about the low address bits.  These are plain functions, not templates, because a
+// deduced template argument would drop the alignment of the typedef.
+typedef f32x4 f32x4_e __attribute__((aligned(4)));
+typedef u32x2 bf16x4_e __attribute__((aligned(2)));
+typedef u16x4 u16x4_e __attribute__((aligned(2)));
+
+__device__ __forceinline__ f32x4 row_load4(const float *p)
 {
-    return (reinterpret_cast<uint64_t>(p) & (a - 1)) == 0;
+#if DLION_NT_LOAD
+    return __builtin_nontemporal_load(reinterpret_cast<const f32x4_e *>(p));
+#else
+    return *reinterpret_cast<const f32x4_e *>(p);
+#endif
 }
+__device__ __forceinline__ u32x2 row_load4(const uint16_t *p)
+{
+#if DLION_NT_LOAD
+    return __builtin_nontemporal_load(reinterpret_cast<const bf16x4_e *>(p));
+#else
+    return *reinterpret_cast<const bf16x4_e *>(p);
+#endif
+}
+__device__ __forceinline__ void row_store4(f32x4 v, float *p)
+{
+#if DLION_NT_STORE
+    __builtin_nontemporal_store(v, reinterpret_cast<f32x4_e *>(p));
+#else
+    *reinterpret_cast<f32x4_e *>(p) = v;
+#endif
+}
+__device__ __forceinline__ f32x4 x_load4(const float *p)
+{
+#if DLION_NT_X
+    return __builtin_nontemporal_load(reinterpret_cast<const f32x4_e *>(p));
+#else
+    return *reinterpret_cast<const f32x4_e *>(p);
+#endif
+}
+__device__ __forceinline__ void x_store4(f32x4 v, float *p)
+{
+#if DLION_NT_X
+    __builtin_nontemporal_store(v, reinterpret_cast<f32x4_e *>(p));
+#else
+    *reinterpret_cast<f32x4_e *>(p) = v;
+#endif
+}
+__device__ __forceinline__ u16x4 counts_load4(const uint16_t *p)
+{
+    return *reinterpret_cast<const u16x4_e *>(p);
+}
+__device__ __forceinline__ void counts_store4(u16x4 v, uint16_t *p, bool stream)
+{
+    if (stream)
+        __builtin_nontemporal_store(v, reinterpret_cast<u16x4_e *>(p));
+    else
+        *reinterpret_cast<u16x4_e *>(p) = v;
+}
+#define COUNTS_STORE4(v, p) counts_store4(v, p, h.stream_counts)
 
 // ---------------------------------------------------------------- gradients
 template <typename GT> struct Grad;
@@ -217,7 +260,7 @@ template <> struct Grad<float> {
     static constexpr int kVecBytes = 16;
     static __device__ __forceinline__ f32x4 load4(const void *g, int64_t idx)
     {
-        return stream_load(reinterpret_cast<const f32x4 *>(static_cast<const float *>(g) + idx));
+        return row_load4(static_cast<const float *>(g) + idx);
     }
     static __device__ __forceinline__ float load1(const void *g, int64_t idx)
     {
@@ -228,7 +271,7 @@ template <> struct Grad<uint16_t> {   // bf16 bit patterns; widening to fp32 is 
     static constexpr int kVecBytes = 8;
     static __device__ __forceinline__ f32x4 load4(const void *g, int64_t idx)
     {
-        const u32x2 raw = stream_load(reinterpret_cast<const u32x2 *>(static_cast<const uint16_t *>(g) + idx));
+        const u32x2 raw = row_load4(static_cast<const uint16_t *>(g) + idx);
         f32x4 r;
         r.x = __uint_as_float(raw.x << 16);
         r.y = __uint_as_float(raw.x & 0xFFFF0000u);
@@ -323,7 +366,7 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
     if (kApply) {
 #pragma unroll
         for (int r = 0; r < kR; ++r)
-            xv[r] = X_LOAD(reinterpret_cast<const f32x4 *>(p.x + j0 + r * kSubTile));
+            xv[r] = x_load4(p.x + j0 + r * kSubTile);
     }
     uint32_t cnt[kR][4];
 #pragma unroll
@@ -342,7 +385,7 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
         mv.y = m1;
         mv.z = m2;
         mv.w = m3;
-        stream_store(mv, reinterpret_cast<f32x4 *>(p.m + (int64_t)i * p.m_stride + j0 + r * kSubTile));
+        row_store4(mv, p.m + (int64_t)i * p.m_stride + j0 + r * kSubTile);
         cnt[r][0] += b0;
         cnt[r][1] += b1;
         cnt[r][2] += b2;
@@ -362,8 +405,7 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
         for (int u = 0; u < kUnroll; ++u) {
 #pragma unroll
             for (int r = 0; r < kR; ++r) {
-                mv[u][r] = stream_load(
-                    reinterpret_cast<const f32x4 *>(p.m + (int64_t)(i + u) * p.m_stride + j0 + r * kSubTile));
+                mv[u][r] = row_load4(p.m + (int64_t)(i + u) * p.m_stride + j0 + r * kSubTile);
                 gv[u][r] = Grad<GT>::load4(p.g, (int64_t)(i + u) * p.g_stride + j0 + r * kSubTile);
             }
         }
@@ -378,7 +420,7 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
         f32x4 mv[kR], gv[kR];
 #pragma unroll
         for (int r = 0; r < kR; ++r) {
-            mv[r] = stream_load(reinterpret_cast<const f32x4 *>(p.m + (int64_t)i * p.m_stride + j0 + r * kSubTile));
+            mv[r] = row_load4(p.m + (int64_t)i * p.m_stride + j0 + r * kSubTile);
             gv[r] = Grad<GT>::load4(p.g, (int64_t)i * p.g_stride + j0 + r * kSubTile);
         }
 #pragma unroll
@@ -393,7 +435,7 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
             xv[r].y = lion_apply(xv[r].y, aggregate_votes(cnt[r][1], h), h);
             xv[r].z = lion_apply(xv[r].z, aggregate_votes(cnt[r][2], h), h);
             xv[r].w = lion_apply(xv[r].w, aggregate_votes(cnt[r][3], h), h);
-            X_STORE(xv[r], reinterpret_cast<f32x4 *>(p.x + j0 + r * kSubTile));
+            x_store4(xv[r], p.x + j0 + r * kSubTile);
         }
         if (kCounts) {
             u16x4 c;
@@ -401,7 +443,7 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
             c.y = static_cast<uint16_t>(cnt[r][1]);
             c.z = static_cast<uint16_t>(cnt[r][2]);
             c.w = static_cast<uint16_t>(cnt[r][3]);
-            C_STORE(c, reinterpret_cast<u16x4 *>(p.counts + j0 + r * kSubTile));
+            COUNTS_STORE4(c, p.counts + j0 + r * kSubTile);
         }
     }
 }
@@ -452,23 +494,17 @@ __global__ __launch_bounds__(kBlock) void step_kernel(Addr addr, Hyper h)
     const int lane = threadIdx.x & 63;
     Problem p;
     const int64_t t = addr.resolve(tile, p) * kSubs;      // first sub-tile of this wave
-    bool aligned = is_aligned(p.m, 16) && (p.m_stride & 3) == 0 && is_aligned(p.g, Grad<GT>::kVecBytes) &&
-                   (p.g_stride & 3) == 0;
-    if (kApply)
-        aligned = aligned && is_aligned(p.x, 16);
-    if (kCounts)
-        aligned = aligned && is_aligned(p.counts, 8);
-    if (aligned && (t + kSubs) * kSubTile <= p.numel) {
+    if ((t + kSubs) * kSubTile <= p.numel) {
         step_subtiles_vector<GT, kUnroll, kSubs, kApply, kPacked, kCounts>(p, t, lane, h);
         return;
     }
-    // ragged end of a tensor, or rows that cannot take 128-bit accesses
+    // ragged end of a tensor
 #pragma unroll 1
     for (int r = 0; r < kSubs; ++r) {
         const int64_t sub = t + r;
         if (sub * kSubTile >= p.numel)
             break;
-        if (kSubs > 1 && aligned && (sub + 1) * kSubTile <= p.numel)
+        if (kSubs > 1 && (sub + 1) * kSubTile <= p.numel)
             step_subtiles_vector<GT, kUnroll, 1, kApply, kPacked, kCounts>(p, sub, lane, h);
         else
             step_subtile_guarded<GT, kApply, kPacked, kCounts>(p, sub, lane, h);
@@ -516,12 +552,12 @@ __device__ __forceinline__ void agg_subtile_vector(const Problem &p, int64_t t, 
     }
     const int64_t j0 = t * kSubTile + lane * kVec;
     if (kApply) {
-        f32x4 xv = X_LOAD(reinterpret_cast<const f32x4 *>(p.x + j0));
+        f32x4 xv = x_load4(p.x + j0);
         xv.x = lion_apply(xv.x, aggregate_votes(cnt0, h), h);
         xv.y = lion_apply(xv.y, aggregate_votes(cnt1, h), h);
         xv.z = lion_apply(xv.z, aggregate_votes(cnt2, h), h);
         xv.w = lion_apply(xv.w, aggregate_votes(cnt3, h), h);
-        X_STORE(xv, reinterpret_cast<f32x4 *>(p.x + j0));
+        x_store4(xv, p.x + j0);
     }
     if (kCounts) {
         u16x4 c;
@@ -529,7 +565,7 @@ __device__ __forceinline__ void agg_subtile_vector(const Problem &p, int64_t t, 
         c.y = static_cast<uint16_t>(cnt1);
         c.z = static_cast<uint16_t>(cnt2);
         c.w = static_cast<uint16_t>(cnt3);
-        C_STORE(c, reinterpret_cast<u16x4 *>(p.counts + j0));
+        COUNTS_STORE4(c, p.counts + j0);
     }
 }
 
@@ -568,17 +604,12 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(Addr addr, Hyper h)
     const int lane = threadIdx.x & 63;
     Problem p;
     const int64_t t = addr.resolve(tile, p) * kSubs;
-    bool aligned = true;
-    if (kApply)
-        aligned = aligned && is_aligned(p.x, 16);
-    if (kCounts)
-        aligned = aligned && is_aligned(p.counts, 8);
 #pragma unroll 1
     for (int r = 0; r < kSubs; ++r) {
         const int64_t sub = t + r;
         if (sub * kSubTile >= p.numel)
             break;
-        if (aligned && (sub + 1) * kSubTile <= p.numel)
+        if ((sub + 1) * kSubTile <= p.numel)
             agg_subtile_vector<kApply, kCounts>(p, sub, lane, h);
         else
             agg_subtile_guarded<kApply, kCounts>(p, sub, lane, h);
@@ -602,6 +633,17 @@ constexpr int kSlicedWords = kLanes * kWpl;            // words per wave
 constexpr int kSlicedCoords = kSlicedWords * 64;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef u32x4 words2_e __attribute__((aligned(8)));
+
+// two consecutive packed words (only promised the alignment of one) in one 128-bit access
+__device__ __forceinline__ u32x4 packed_load2(const uint64_t *p)
+{
+#if DLION_NT_LOAD
+    return __builtin_nontemporal_load(reinterpret_cast<const words2_e *>(p));
+#else
+    return *reinterpret_cast<const words2_e *>(p);
+#endif
+}
 
 // carry-save adder on 32 independent bit positions: a + b + c = 2*carry + sum.  gfx950 has a
 // three-input boolean instruction, so each output is one operation (truth tables: majority
@@ -626,9 +668,8 @@ __device__ __forceinline__ void sliced_count(const Problem &p, int N, int64_t w0
     static_assert(kPlanes >= 5 && kPlanes <= 16, "planes");
     static_assert(kWpl == 1 || kWpl == 2, "words per lane");
     const int64_t wl0 = w0 + (int64_t)lane * kWpl;              // first word of the lane
-    const bool vec = (p.packed_stride % kWpl) == 0 && is_aligned(p.packed, 8 * kWpl);
-    // whole group inside the word range and rows that allow full-width loads: no per-lane guards
-    const bool fast = vec && w0 + kSlicedWords <= W;
+    // whole group inside the word range: full-width loads, no per-lane guards
+    const bool fast = w0 + kSlicedWords <= W;
 
     uint32_t ones[kSlices], twos[kSlices], fours[kSlices], eights[kSlices];
     uint32_t hi[kPlanes - 4][kSlices];                          // planes 4.. (sixteens and up)
@@ -652,7 +693,7 @@ __device__ __forceinline__ void sliced_count(const Problem &p, int N, int64_t w0
                     // uniform row base + small per-lane offset
                     const uint64_t *row = p.packed + (int64_t)(i + k) * p.packed_stride + w0;
                     if (kWpl == 2) {
-                        const u32x4 r = stream_load(reinterpret_cast<const u32x4 *>(row) + lane);
+                        const u32x4 r = packed_load2(row + 2 * lane);
                         v[k][0] = r.x;
                         v[k][1] = r.y;
                         v[k][kSlices - 2] = r.z;
@@ -751,8 +792,6 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_sliced_kernel(FlatA
     }
     __syncthreads();
 
-    const bool vec_x = !kApply || is_aligned(p.x, 16);
-    const bool vec_c = !kCounts || is_aligned(p.counts, 8);
     // now lane l owns coordinates 4*(l&15).. of word 4*s + (l>>4), s = 0..kSlicedWords/4-1
 #pragma unroll 2
     for (int s = 0; s < kSlicedWords / kWordsPerSub; ++s) {
@@ -778,13 +817,13 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_sliced_kernel(FlatA
             cnt[k] = ((lo >> (8 * k)) & 0xFFu) | (kPlanes > 8 ? ((up >> (8 * k)) & 0xFFu) << 8 : 0u);
         const bool full = j0 + kVec <= p.numel;
         if (kApply) {
-            if (full && vec_x) {
-                f32x4 xv = X_LOAD(reinterpret_cast<const f32x4 *>(p.x + j0));
+            if (full) {
+                f32x4 xv = x_load4(p.x + j0);
                 xv.x = lion_apply(xv.x, aggregate_votes(cnt[0], h), h);
                 xv.y = lion_apply(xv.y, aggregate_votes(cnt[1], h), h);
                 xv.z = lion_apply(xv.z, aggregate_votes(cnt[2], h), h);
                 xv.w = lion_apply(xv.w, aggregate_votes(cnt[3], h), h);
-                X_STORE(xv, reinterpret_cast<f32x4 *>(p.x + j0));
+                x_store4(xv, p.x + j0);
             } else {
 #pragma unroll
                 for (int k = 0; k < kVec; ++k)
@@ -793,13 +832,13 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_sliced_kernel(FlatA
             }
         }
         if (kCounts) {
-            if (full && vec_c) {
+            if (full) {
                 u16x4 c;
                 c.x = static_cast<uint16_t>(cnt[0]);
                 c.y = static_cast<uint16_t>(cnt[1]);
                 c.z = static_cast<uint16_t>(cnt[2]);
                 c.w = static_cast<uint16_t>(cnt[3]);
-                C_STORE(c, reinterpret_cast<u16x4 *>(p.counts + j0));
+                COUNTS_STORE4(c, p.counts + j0);
             } else {
 #pragma unroll
                 for (int k = 0; k < kVec; ++k)
@@ -912,7 +951,7 @@ __global__ __launch_bounds__(kLanes) void apply_encoded_kernel(FlatAddr addr, Hy
     const Problem &p = addr.p;
     const int64_t t = blockIdx.x;                               // line index
     const int lane = threadIdx.x;
-    const bool full = (t + 1) * kLineCoords <= p.numel && is_aligned(p.x, 16);
+    const bool full = (t + 1) * kLineCoords <= p.numel;
     if (full) {
         // all planes' loads first (n_planes <= kMaxPlanes; the test is uniform)
         uint32_t raw[kMaxPlanes];
@@ -925,7 +964,7 @@ __global__ __launch_bounds__(kLanes) void apply_encoded_kernel(FlatAddr addr, Hy
         f32x4 xv[kLineSubs];
 #pragma unroll
         for (int s = 0; s < kLineSubs; ++s)
-            xv[s] = X_LOAD(reinterpret_cast<const f32x4 *>(p.x + t * kLineCoords + s * kSubTile + lane * kVec));
+            xv[s] = x_load4(p.x + t * kLineCoords + s * kSubTile + lane * kVec);
         const int shift = (lane & 7) * 4;
 #pragma unroll
         for (int s = 0; s < kLineSubs; ++s) {
@@ -956,11 +995,11 @@ __global__ __launch_bounds__(kLanes) void apply_encoded_kernel(FlatAddr addr, Hy
             xv[s].y = lion_apply(xv[s].y, Delta[1], h);
             xv[s].z = lion_apply(xv[s].z, Delta[2], h);
             xv[s].w = lion_apply(xv[s].w, Delta[3], h);
-            X_STORE(xv[s], reinterpret_cast<f32x4 *>(p.x + t * kLineCoords + s * kSubTile + lane * kVec));
+            x_store4(xv[s], p.x + t * kLineCoords + s * kSubTile + lane * kVec);
         }
         return;
     }
-    // ragged end or unaligned x: lane l owns bit l of one word at a time
+    // ragged end: lane l owns bit l of one word at a time
     const int64_t W = (p.numel + 63) >> 6;
 #pragma unroll 1
     for (int k = 0; k < kLineSubs * kWordsPerSub; ++k) {
@@ -1004,11 +1043,10 @@ __global__ __launch_bounds__(kLanes) void global_lion_kernel(FlatAddr addr, Hype
     const int lane = threadIdx.x;
     const int N = h.N;
     const Coef k = {h.beta1, h.omb1, h.beta2, h.omb2};
-    const bool vec = (t + 1) * kSubTile <= p.numel && is_aligned(p.m, 16) && (p.m_stride & 3) == 0 &&
-                     is_aligned(p.g, Grad<GT>::kVecBytes) && (p.g_stride & 3) == 0 && is_aligned(p.x, 16);
+    const bool vec = (t + 1) * kSubTile <= p.numel;
     if (vec) {
         const int64_t j0 = t * kSubTile + lane * kVec;
-        f32x4 xv = X_LOAD(reinterpret_cast<const f32x4 *>(p.x + j0));
+        f32x4 xv = x_load4(p.x + j0);
         float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
         auto one_worker = [&](int i, f32x4 mv, f32x4 gv) {
             float m0 = mv.x, m1 = mv.y, m2 = mv.z, m3 = mv.w;
@@ -1020,14 +1058,14 @@ __global__ __launch_bounds__(kLanes) void global_lion_kernel(FlatAddr addr, Hype
             mv.y = m1;
             mv.z = m2;
             mv.w = m3;
-            stream_store(mv, reinterpret_cast<f32x4 *>(p.m + (int64_t)i * p.m_stride + j0));
+            row_store4(mv, p.m + (int64_t)i * p.m_stride + j0);
         };
         int i = 0;
         for (; i + kUnroll <= N; i += kUnroll) {
             f32x4 mv[kUnroll], gv[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
-                mv[u] = stream_load(reinterpret_cast<const f32x4 *>(p.m + (int64_t)(i + u) * p.m_stride + j0));
+                mv[u] = row_load4(p.m + (int64_t)(i + u) * p.m_stride + j0);
                 gv[u] = Grad<GT>::load4(p.g, (int64_t)(i + u) * p.g_stride + j0);
             }
 #pragma unroll
@@ -1035,7 +1073,7 @@ __global__ __launch_bounds__(kLanes) void global_lion_kernel(FlatAddr addr, Hype
                 one_worker(i + u, mv[u], gv[u]);
         }
         for (; i < N; ++i) {
-            const f32x4 mv = stream_load(reinterpret_cast<const f32x4 *>(p.m + (int64_t)i * p.m_stride + j0));
+            const f32x4 mv = row_load4(p.m + (int64_t)i * p.m_stride + j0);
             const f32x4 gv = Grad<GT>::load4(p.g, (int64_t)i * p.g_stride + j0);
             one_worker(i, mv, gv);
         }
@@ -1044,7 +1082,7 @@ __global__ __launch_bounds__(kLanes) void global_lion_kernel(FlatAddr addr, Hype
         xv.y = lion_apply(xv.y, b1 ? 1.0f : -1.0f, h);
         xv.z = lion_apply(xv.z, b2 ? 1.0f : -1.0f, h);
         xv.w = lion_apply(xv.w, b3 ? 1.0f : -1.0f, h);
-        X_STORE(xv, reinterpret_cast<f32x4 *>(p.x + j0));
+        x_store4(xv, p.x + j0);
         if (sign_bits) {
             const uint32_t nib = (b0 ? 1u : 0u) | (b1 ? 2u : 0u) | (b2 ? 4u : 0u) | (b3 ? 8u : 0u);
             const uint64_t word = row_gather_nibbles(nib, lane);
@@ -1091,21 +1129,20 @@ __global__ __launch_bounds__(kBlock) void apply_kernel(Addr addr, Hyper h)
     const int lane = threadIdx.x & 63;
     Problem p;
     const int64_t t = addr.resolve(tile, p) * kSubs;
-    const bool aligned = is_aligned(p.x, 16) && is_aligned(p.counts, 8);
 #pragma unroll 1
     for (int r = 0; r < kSubs; ++r) {
         const int64_t sub = t + r;
         if (sub * kSubTile >= p.numel)
             break;
-        if (aligned && (sub + 1) * kSubTile <= p.numel) {
+        if ((sub + 1) * kSubTile <= p.numel) {
             const int64_t j0 = sub * kSubTile + lane * kVec;
-            const u16x4 c = C_LOAD(reinterpret_cast<const u16x4 *>(p.counts + j0));
-            f32x4 xv = X_LOAD(reinterpret_cast<const f32x4 *>(p.x + j0));
+            const u16x4 c = counts_load4(p.counts + j0);
+            f32x4 xv = x_load4(p.x + j0);
             xv.x = lion_apply(xv.x, aggregate_votes(c.x, h), h);
             xv.y = lion_apply(xv.y, aggregate_votes(c.y, h), h);
             xv.z = lion_apply(xv.z, aggregate_votes(c.z, h), h);
             xv.w = lion_apply(xv.w, aggregate_votes(c.w, h), h);
-            X_STORE(xv, reinterpret_cast<f32x4 *>(p.x + j0));
+            x_store4(xv, p.x + j0);
         } else {
 #pragma unroll 1
             for (int k = 0; k < kWordsPerSub; ++k) {

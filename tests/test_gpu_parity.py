@@ -334,6 +334,72 @@ def test_many_worker_aggregate_matches_oracle():
                     assert np.array_equal(to_np(counts2), want)
 
 
+def offset_view(shape, dtype, skip):
+    """Tensor of the given shape that starts `skip` elements into its allocation (allocations are
+    256-byte aligned, so skip = 1 leaves only the element's own alignment)."""
+    n = int(np.prod(shape))
+    buf = torch.empty(n + skip + 1, dtype=dtype, device=DEV)
+    if dtype in (torch.float32, torch.bfloat16):
+        buf.fill_(float("nan"))
+    else:
+        buf.fill_(-1)
+    return buf, buf[skip:skip + n].view(*shape)
+
+
+@pytest.mark.parametrize("g_dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_arrays_with_only_their_element_alignment(g_dtype):
+    """Every array starts one element past an aligned address and rows follow each other without
+    padding: full tiles still take the 128-bit accesses, so those must work at any alignment."""
+    rng = np.random.default_rng(808)
+    for (d, N), mode in itertools.product(((256, 1), (1027, 3), (4099, 8), (70_001, 5), (8193, 20)),
+                                          (dl.VOTE, dl.AVG)):
+        announce("element-aligned", g_dtype, "d", d, "N", N, "mode", mode)
+        W = dl.words_for(d)
+        xb, x = offset_view((d,), torch.float32, 1)
+        mb, m = offset_view((N, d), torch.float32, 1)
+        gb, g = offset_view((N, d), g_dtype, 1)
+        pb, packed = offset_view((N, W), torch.int64, 1)
+        cb, counts = offset_view((d,), torch.int16, 1)
+        x.copy_(torch.from_numpy(rng.normal(0, 0.02, d).astype(np.float32)))
+        m.copy_(torch.from_numpy(rng.normal(0, 1e-3, (N, d)).astype(np.float32)))
+        g.copy_(torch.from_numpy(rng.standard_t(3, (N, d)).astype(np.float32) * 1e-3).to(g_dtype))
+        assert x.data_ptr() % 16 == 4 and m.data_ptr() % 16 == 4 and counts.data_ptr() % 8 == 2
+        for step in range(2):
+            xn, mn, pn, cn = oracle_step(x, m, g, mode, HYP)
+            dl.dlion_step(x, m, g, mode, HYP["beta1"], HYP["beta2"], HYP["lr"], HYP["lam"],
+                          packed=packed, counts=counts)
+            torch.cuda.synchronize()
+            compare_all(f"fused d={d} N={N} step={step}", x, m, packed, counts, xn, mn, pn, cn)
+        # the same through the separate calls
+        x2 = x.clone()
+        xn, mn, pn, cn = oracle_step(x, m, g, mode, HYP)
+        packed.fill_(-1)
+        counts.fill_(-1)
+        dl.dlion_worker_step(m, g, packed, HYP["beta1"], HYP["beta2"])
+        dl.dlion_aggregate(packed, d, counts)
+        dl.dlion_apply(x, counts, N, mode, HYP["lr"], HYP["lam"])
+        torch.cuda.synchronize()
+        compare_all(f"unfused d={d} N={N}", x, m, packed, counts, xn, mn, pn, cn)
+        x2b, x2o = offset_view((d,), torch.float32, 3)
+        x2o.copy_(x2)
+        dl.dlion_aggregate_apply(x2o, packed, mode, HYP["lr"], HYP["lam"])
+        torch.cuda.synchronize()
+        assert_f32_equal(to_np(x2o), xn, "aggregate_apply: x")
+        # nothing outside the views was written
+        for buf, view in ((xb, x), (mb, m), (x2b, x2o)):
+            assert torch.isnan(buf[0]) and torch.isnan(buf[-1])
+        assert pb[0] == -1 and pb[-1] == -1 and cb[0] == -1 and cb[-1] == -1
+        # averaging over all workers' blends (same layout)
+        xn, mn = to_np(x), to_np(m)
+        bn = oracle.global_lion_step(xn, mn, to_np(g), 0.9, 0.99, 3e-4, 0.1)
+        bits = torch.full((W,), -1, dtype=torch.int64, device=DEV)
+        dl.dlion_global_lion_step(x, m, g, 0.9, 0.99, 3e-4, 0.1, sign_bits=bits)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(bits), bn)
+        assert_f32_equal(to_np(m), mn, "global lion: m")
+        assert_f32_equal(to_np(x), xn, "global lion: x")
+
+
 def test_randomized_shapes_strides_and_flags():
     """Seeded random sweep over d, N, row strides (aligned or not), gradient dtype, aggregation and
     optional outputs, two steps each, fused and unfused, against the oracle."""
