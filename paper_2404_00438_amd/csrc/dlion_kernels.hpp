@@ -374,8 +374,28 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
         cnt[r][0] = cnt[r][1] = cnt[r][2] = cnt[r][3] = 0;
     const int N = h.N;
 
+    // Per-worker coefficients: lane l keeps those of worker (i & ~63) + l, fetched once per 64
+    // workers; each worker's pair is then broadcast from its lane, so that no memory access
+    // sits between a worker's loads and its arithmetic.  Workers are visited in order from 0.
+    uint32_t pw_beta1 = 0, pw_beta2 = 0;
+    auto coef_of = [&](int i) {
+        Coef k = {h.beta1, h.omb1, h.beta2, h.omb2};
+        if (h.beta1_pw) {                               // uniform
+            if ((i & 63) == 0) {
+                const int w = i + lane;
+                pw_beta1 = w < N ? __float_as_uint(h.beta1_pw[w]) : 0u;
+                pw_beta2 = w < N ? __float_as_uint(h.beta2_pw[w]) : 0u;
+            }
+            k.beta1 = __uint_as_float(__builtin_amdgcn_readlane(pw_beta1, i & 63));
+            k.omb1 = __fsub_rn(1.0f, k.beta1);
+            k.beta2 = __uint_as_float(__builtin_amdgcn_readlane(pw_beta2, i & 63));
+            k.omb2 = __fsub_rn(1.0f, k.beta2);
+        }
+        return k;
+    };
+
     auto one_worker = [&](int i, int r, f32x4 mv, f32x4 gv) {
-        const Coef k = worker_coef(h, i);
+        const Coef k = coef_of(i);
         float m0 = mv.x, m1 = mv.y, m2 = mv.z, m3 = mv.w;
         const bool b0 = lion_worker(m0, gv.x, k);
         const bool b1 = lion_worker(m1, gv.y, k);

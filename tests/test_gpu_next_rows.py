@@ -69,7 +69,8 @@ def test_down_link_planes_match_oracle():
 @pytest.mark.parametrize("g_dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
 def test_per_worker_coefficients_match_oracle(g_dtype):
     rng = np.random.default_rng(78)
-    for N, d in ((1, 100), (2, 257), (5, 4096 + 3), (8, 70_001), (33, 1000)):
+    # N past 64 and 128: the vector path fetches the coefficients 64 workers at a time
+    for N, d in ((1, 100), (2, 257), (5, 4096 + 3), (8, 70_001), (33, 1000), (64, 300), (65, 513), (130, 700)):
         for kind in ("mixed", "signum"):
             b1 = rng.choice(np.array([0.0, 0.5, 0.8, 0.9, 0.95, 1.0], np.float32), N)
             b2 = rng.choice(np.array([0.25, 0.9, 0.98, 0.99, 0.999], np.float32), N) if kind == "mixed" else b1.copy()
