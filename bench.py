@@ -111,11 +111,15 @@ def main() -> int:
     dl.load_library()
     w = wl.CONFIGS[args.workload]
     g_bytes = 2 if w.g_dtype == torch.bfloat16 else 4
-    kernel = "dlion_step (fused, no packed/counts output)"
+    kernel = "dlion_step (fused"
     metric = "param-updates/s (d*N per fused step)"
     units = w.d * w.N                               # parameter-updates (or votes) per step
     bytes_per_launch = algorithmic_bytes_per_step(w.d, w.N, g_bytes)
     x = m = g = None
+    # From 16 workers on the library runs the step as consecutive launches over 8 workers each when
+    # it is given a counts array to carry the votes in; the counts then are an output of the step.
+    with_counts = w.N >= 16
+    launches = -(-w.N // 8) if with_counts else 1
     if w.g_dist == "packed_bernoulli":
         # vote-only pass: N pre-packed sign streams in, counts out
         W = dl.words_for(w.d)
@@ -133,17 +137,24 @@ def main() -> int:
         ms = [wl.init_m(w, dev, numel=n) for n in numels]
         gs = [wl.make_grads(w, 0, dev, tensor=k) for k in range(len(numels))]
         table = dl.SegTable(xs, ms, gs)
-        kernel = f"dlion_step_mt (fused, {len(numels)} tensors)"
+        counts = torch.empty(64 * table.total_words, dtype=torch.int16, device=dev) if with_counts else None
+        kernel = f"dlion_step_mt (fused, {len(numels)} tensors"
 
         def step():
-            dl.dlion_step_mt(table, w.N, w.mode, w.beta1, w.beta2, w.lr, w.lam)
+            dl.dlion_step_mt(table, w.N, w.mode, w.beta1, w.beta2, w.lr, w.lam, counts=counts)
     else:
         x = wl.init_x(w, dev)
         m = wl.init_m(w, dev)
         g = wl.make_grads(w, 0, dev)
+        counts = torch.empty(w.d, dtype=torch.int16, device=dev) if with_counts else None
 
         def step():
-            dl.dlion_step(x, m, g, w.mode, w.beta1, w.beta2, w.lr, w.lam)
+            dl.dlion_step(x, m, g, w.mode, w.beta1, w.beta2, w.lr, w.lam, counts=counts)
+    if with_counts and w.g_dist != "packed_bernoulli":
+        kernel += f", counts output; {launches} launches over {w.N // launches} workers each)"
+        bytes_per_launch += 2 * w.d                  # the counts the step hands back
+    else:
+        kernel += ", no packed/counts output)" if w.g_dist != "packed_bernoulli" else ""
     torch.cuda.synchronize()
 
     for _ in range(args.warmup):
@@ -186,8 +197,9 @@ def main() -> int:
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": recorded_traffic(w.name),
-            "kernel_ms": kernel_ms,
-            "bytes_per_launch": bytes_per_launch,
+            "kernel_ms": kernel_ms,                  # all launches of one step
+            "launches_per_step": launches if w.g_dist != "packed_bernoulli" else 1,
+            "bytes_per_launch": bytes_per_launch,    # algorithmic bytes of one step
             "bytes_per_update": bytes_per_launch / units,
         },
     }

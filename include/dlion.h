@@ -111,6 +111,11 @@ dlion_status dlion_aggregate_apply(float *x, const uint64_t *packed, int64_t pac
  * Per coordinate it moves m in, m out and g in for each worker and x in and out
  * once.  packed_or_null / counts_or_null, if not NULL, also receive the packed
  * updates and the counts exactly as the unfused calls would write them.
+ * With 16 or more workers and d beyond ~16 M a counts array also makes the call
+ * faster: the step is then enqueued as consecutive launches over 8 workers each
+ * that carry the votes in counts (same results; counts holds partial sums until
+ * the last launch has run).  Without it the step stays one launch: the library
+ * owns no memory.  The same holds for the _mt and _pw variants.
  */
 dlion_status dlion_step(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
                         dlion_dtype g_dtype, int64_t d, int32_t N, dlion_mode mode, float beta1,

@@ -32,6 +32,9 @@ Hyper make_hyper(int32_t N, int mode, float beta1, float beta2, float lr, float 
     h.N = N;
     h.mode = mode;
     h.stream_counts = 0;
+    h.worker_begin = 0;
+    h.worker_end = N;
+    h.counts_in = 0;
     h.beta1_pw = nullptr;
     h.beta2_pw = nullptr;
     return h;
@@ -129,7 +132,7 @@ dlion_status launch_step_flags(const Addr &addr, const Hyper &h, bool packed, bo
 template <typename GT, bool kApply, class Addr>
 dlion_status launch_step_unroll(const Addr &addr, const Hyper &h, bool packed, bool counts, hipStream_t s)
 {
-    LaunchShape shape = step_shape(h.N, kSubs * kLanes * (16 + Grad<GT>::kVecBytes));
+    LaunchShape shape = step_shape(h.worker_end - h.worker_begin, kSubs * kLanes * (16 + Grad<GT>::kVecBytes));
     // A problem whose waves all fit on the chip at once never reaches the steady state the cap
     // is tuned for; it is latency-bound and wants every wave resident (d = 1,000,003, N = 4:
     // 12.7 -> 10.4 us).
@@ -145,12 +148,56 @@ dlion_status launch_step_unroll(const Addr &addr, const Hyper &h, bool packed, b
 }
 
 template <bool kApply, class Addr>
-dlion_status launch_step(const Addr &addr, const Hyper &h, dlion_dtype g_dtype, bool packed, bool counts,
-                         hipStream_t s)
+dlion_status launch_step_once(const Addr &addr, const Hyper &h, dlion_dtype g_dtype, bool packed, bool counts,
+                              hipStream_t s)
 {
     if (g_dtype == DLION_BF16)
         return launch_step_unroll<uint16_t, kApply, Addr>(addr, h, packed, counts, s);
     return launch_step_unroll<float, kApply, Addr>(addr, h, packed, counts, s);
+}
+
+// Many workers, large d: the step runs as consecutive launches over kPassWorkers workers each.
+// One launch over all N rows keeps 2N + 1 streams (and as many pages) open across the chip at
+// once, and from N = 16 on that costs more bandwidth than the counts cost that carry the votes
+// from one launch to the next (2 B written and 2 B read per coordinate and launch, against
+// 10-12 B per coordinate and worker).  Measured, fused step with counts, bf16 gradients, one
+// launch -> launches over 8 workers: d = 350 M, N = 32: 21.3 -> 19.7 ms; d = 85.6 M, N = 16:
+// 2.38 -> 2.28 ms; d = 100 M, N = 64: 12.2 -> 10.5 ms; worker step, d = 350 M, N = 32:
+// 24.0 -> 19.7 ms.  N = 12 gains nothing, and below ~16 M coordinates the extra launches cost
+// what they save.  The worker step needs no carry at all; the fused step needs the caller's
+// counts array as the accumulator and stays one launch without it (the library owns no memory).
+constexpr int kPassWorkers = 8;
+constexpr int kPassMinN = 16;
+constexpr int64_t kPassMinTiles = 8 * kResidentWaves;
+
+template <bool kApply, class Addr>
+dlion_status launch_step(const Addr &addr, const Hyper &h0, dlion_dtype g_dtype, bool packed, bool counts,
+                         hipStream_t s)
+{
+    const int N = h0.N;
+    int per = env_int("DLION_PASS_WORKERS");             // tuning: 0 = always one launch
+    if (per < 0)
+        per = (N >= kPassMinN && addr.total_tiles >= kPassMinTiles) ? kPassWorkers : 0;
+    if (kApply && !counts)
+        per = 0;
+    if (per <= 0 || per >= N)
+        return launch_step_once<kApply, Addr>(addr, h0, g_dtype, packed, counts, s);
+    const int passes = (N + per - 1) / per;
+    Hyper h = h0;
+    for (int pass = 0; pass < passes; ++pass) {
+        // spread evenly: N = 30 runs as 8, 8, 7, 7
+        h.worker_begin = static_cast<int32_t>((int64_t)N * pass / passes);
+        h.worker_end = static_cast<int32_t>((int64_t)N * (pass + 1) / passes);
+        h.counts_in = (counts && pass > 0) ? 1 : 0;
+        dlion_status st;
+        if (kApply && pass == passes - 1)
+            st = launch_step_once<true, Addr>(addr, h, g_dtype, packed, counts, s);
+        else
+            st = launch_step_once<false, Addr>(addr, h, g_dtype, packed, counts, s);
+        if (st != DLION_OK)
+            return st;
+    }
+    return DLION_OK;
 }
 
 template <class Addr>

@@ -65,6 +65,11 @@ struct Hyper {
     int32_t N;
     int32_t mode;     // dlion_mode
     int32_t stream_counts;   // counts array too large to stay cached: write it with streaming stores
+    // The worker/fused kernels walk workers [worker_begin, worker_end) of the N: a step over many
+    // workers may be run as several launches over a few workers each.  counts_in: start from the
+    // counts the earlier launches left in the counts array instead of from zero.
+    int32_t worker_begin, worker_end;
+    int32_t counts_in;
     const float *beta1_pw;   // per-worker coefficients (device arrays of N floats), or null:
     const float *beta2_pw;   // then beta1/beta2 above are shared by all workers
 };
@@ -370,19 +375,27 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
     }
     uint32_t cnt[kR][4];
 #pragma unroll
-    for (int r = 0; r < kR; ++r)
+    for (int r = 0; r < kR; ++r) {
         cnt[r][0] = cnt[r][1] = cnt[r][2] = cnt[r][3] = 0;
-    const int N = h.N;
+        if (h.counts_in) {                              // uniform
+            const u16x4 c = counts_load4(p.counts + j0 + r * kSubTile);
+            cnt[r][0] = c.x;
+            cnt[r][1] = c.y;
+            cnt[r][2] = c.z;
+            cnt[r][3] = c.w;
+        }
+    }
+    const int N = h.N, i_begin = h.worker_begin, i_end = h.worker_end;
 
     // Per-worker coefficients: lane l keeps those of worker (i & ~63) + l, fetched once per 64
     // workers; each worker's pair is then broadcast from its lane, so that no memory access
-    // sits between a worker's loads and its arithmetic.  Workers are visited in order from 0.
+    // sits between a worker's loads and its arithmetic.  Workers are visited in order.
     uint32_t pw_beta1 = 0, pw_beta2 = 0;
     auto coef_of = [&](int i) {
         Coef k = {h.beta1, h.omb1, h.beta2, h.omb2};
         if (h.beta1_pw) {                               // uniform
-            if ((i & 63) == 0) {
-                const int w = i + lane;
+            if ((i & 63) == 0 || i == i_begin) {
+                const int w = (i & ~63) + lane;
                 pw_beta1 = w < N ? __float_as_uint(h.beta1_pw[w]) : 0u;
                 pw_beta2 = w < N ? __float_as_uint(h.beta2_pw[w]) : 0u;
             }
@@ -418,8 +431,8 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
         }
     };
 
-    int i = 0;
-    for (; i + kUnroll <= N; i += kUnroll) {
+    int i = i_begin;
+    for (; i + kUnroll <= i_end; i += kUnroll) {
         f32x4 mv[kUnroll][kR], gv[kUnroll][kR];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -436,7 +449,7 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
                 one_worker(i + u, r, mv[u][r], gv[u][r]);
         }
     }
-    for (; i < N; ++i) {
+    for (; i < i_end; ++i) {
         f32x4 mv[kR], gv[kR];
 #pragma unroll
         for (int r = 0; r < kR; ++r) {
@@ -481,8 +494,8 @@ __device__ __forceinline__ void step_subtile_guarded(const Problem &p, int64_t t
             break;                                   // uniform: whole wave leaves together
         const int64_t j = w * 64 + lane;
         const bool valid = j < p.numel;
-        uint32_t cnt = 0;
-        for (int i = 0; i < h.N; ++i) {
+        uint32_t cnt = (h.counts_in && valid) ? p.counts[j] : 0u;
+        for (int i = h.worker_begin; i < h.worker_end; ++i) {
             bool plus = false;
             if (valid) {
                 float *mp = p.m + (int64_t)i * p.m_stride + j;

@@ -400,6 +400,62 @@ def test_arrays_with_only_their_element_alignment(g_dtype):
         assert_f32_equal(to_np(x), xn, "global lion: x")
 
 
+@pytest.mark.parametrize("per", [1, 3, 8])
+def test_step_split_into_launches_over_few_workers(per, monkeypatch):
+    """Many workers at large d run as several launches over a few workers each, the votes carried in
+    the counts array; forced here at small sizes.  Same bits and state as one launch."""
+    monkeypatch.setenv("DLION_PASS_WORKERS", str(per))
+    rng = np.random.default_rng(4242 + per)
+    for (d, N), mode, g_dtype in itertools.product(((1000, 4), (4099, 9), (257, 17), (70_001, 33), (700, 70)),
+                                                   (dl.VOTE, dl.AVG), (torch.float32, torch.bfloat16)):
+        announce("launches of", per, "workers:", g_dtype, "d", d, "N", N, "mode", mode)
+        stride = d + 3
+        x, m, g = draw_state(rng, N, d, g_dtype, stride, stride)
+        W = dl.words_for(d)
+        packed = strided_rows(N, W, W + 1, torch.int64, DEV)
+        counts = torch.full((d,), -1, dtype=torch.int16, device=DEV)
+        for step in range(2):
+            xn, mn, pn, cn = oracle_step(x, m, g, mode, HYP)
+            m_w = m.clone()
+            packed_w = torch.full((N, W), -1, dtype=torch.int64, device=DEV)
+            dl.dlion_worker_step(m_w, g, packed_w, HYP["beta1"], HYP["beta2"])
+            dl.dlion_step(x, m, g, mode, HYP["beta1"], HYP["beta2"], HYP["lr"], HYP["lam"],
+                          packed=packed if step else None, counts=counts)
+            torch.cuda.synchronize()
+            compare_all(f"fused d={d} N={N} step={step}", x, m, packed if step else None, counts, xn, mn, pn, cn)
+            assert np.array_equal(to_np(packed_w), pn), "worker step: packed"
+            assert_f32_equal(to_np(m_w), mn, "worker step: m")
+        # per-worker coefficients: launches that begin inside a block of 64 workers
+        b1 = rng.choice(np.array([0.0, 0.5, 0.9, 0.95], np.float32), N)
+        b2 = rng.choice(np.array([0.25, 0.9, 0.99], np.float32), N)
+        xn, mn, gn = to_np(x), to_np(m), to_np(g)
+        pn = oracle.worker_step_pw(mn, gn, b1, b2)
+        cn = oracle.aggregate_packed(pn, d)
+        oracle.apply(xn, cn, N, mode, 3e-4, 0.1)
+        dl.dlion_step_pw(x, m, g, mode, torch.from_numpy(b1).to(DEV), torch.from_numpy(b2).to(DEV), 3e-4, 0.1,
+                         packed=packed, counts=counts)
+        torch.cuda.synchronize()
+        compare_all(f"step_pw d={d} N={N}", x, m, packed, counts, xn, mn, pn, cn)
+    # tensor list
+    numels = [1000, 5, 64, 256, 257, 1, 2304 * 8, 63]
+    for N, mode in ((5, dl.VOTE), (18, dl.AVG)):
+        announce("launches of", per, "workers: tensor list N", N)
+        xs, ms, gs = make_list(rng, numels, N, torch.bfloat16)
+        table = dl.SegTable(xs, ms, gs)
+        Wt = table.total_words
+        packed = torch.full((N, Wt), -1, dtype=torch.int64, device=DEV)
+        counts = torch.full((64 * Wt,), -1, dtype=torch.int16, device=DEV)
+        xn = [to_np(t) for t in xs]
+        mn = [to_np(t) for t in ms]
+        pn, cn = oracle.step_mt(xn, mn, [to_np(t) for t in gs], mode, 0.9, 0.99, 1e-4, 10.0)
+        dl.dlion_step_mt(table, N, mode, 0.9, 0.99, 1e-4, 10.0, packed=packed, counts=counts)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(packed), pn) and np.array_equal(unpad_counts(counts, table), cn)
+        for k in range(len(numels)):
+            assert_f32_equal(to_np(xs[k]), xn[k], f"x[{k}]")
+            assert_f32_equal(to_np(ms[k]), mn[k], f"m[{k}]")
+
+
 def test_randomized_shapes_strides_and_flags():
     """Seeded random sweep over d, N, row strides (aligned or not), gradient dtype, aggregation and
     optional outputs, two steps each, fused and unfused, against the oracle."""
