@@ -119,7 +119,6 @@ def main() -> int:
     # From 16 workers on the library runs the step as consecutive launches over 8 workers each when
     # it is given a counts array to carry the votes in; the counts then are an output of the step.
     with_counts = w.N >= 16
-    launches = -(-w.N // 8) if with_counts else 1
     if w.g_dist == "packed_bernoulli":
         # vote-only pass: N pre-packed sign streams in, counts out
         W = dl.words_for(w.d)
@@ -151,7 +150,7 @@ def main() -> int:
         def step():
             dl.dlion_step(x, m, g, w.mode, w.beta1, w.beta2, w.lr, w.lam, counts=counts)
     if with_counts and w.g_dist != "packed_bernoulli":
-        kernel += f", counts output; {launches} launches over {w.N // launches} workers each)"
+        kernel += ", counts output; launches over 8 workers each, 33.5 M coordinates at a time)"
         bytes_per_launch += 2 * w.d                  # the counts the step hands back
     else:
         kernel += ", no packed/counts output)" if w.g_dist != "packed_bernoulli" else ""
@@ -198,7 +197,6 @@ def main() -> int:
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": recorded_traffic(w.name),
             "kernel_ms": kernel_ms,                  # all launches of one step
-            "launches_per_step": launches if w.g_dist != "packed_bernoulli" else 1,
             "bytes_per_launch": bytes_per_launch,    # algorithmic bytes of one step
             "bytes_per_update": bytes_per_launch / units,
         },

@@ -98,6 +98,7 @@ struct Problem {
 struct FlatAddr {
     Problem p;
     int64_t total_tiles;
+    int64_t first_tile;    // worker/fused kernels: the launch covers tiles [first_tile, total_tiles)
     __device__ int64_t resolve(int64_t tile, Problem &out) const
     {
         out = p;
@@ -112,6 +113,7 @@ struct SegAddr {
     const dlion_seg *segs;
     int32_t K;
     int64_t total_tiles;
+    int64_t first_tile;
     uint64_t *packed;
     int64_t packed_stride;
     uint16_t *counts;
@@ -521,7 +523,7 @@ __device__ __forceinline__ void step_subtile_guarded(const Problem &p, int64_t t
 template <typename GT, int kUnroll, bool kApply, bool kPacked, bool kCounts, class Addr>
 __global__ __launch_bounds__(kBlock) void step_kernel(Addr addr, Hyper h)
 {
-    const int64_t tile = wave_tile_index();
+    const int64_t tile = addr.first_tile + wave_tile_index();
     if (tile >= addr.total_tiles)
         return;
     const int lane = threadIdx.x & 63;

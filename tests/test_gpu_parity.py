@@ -400,11 +400,13 @@ def test_arrays_with_only_their_element_alignment(g_dtype):
         assert_f32_equal(to_np(x), xn, "global lion: x")
 
 
-@pytest.mark.parametrize("per", [1, 3, 8])
-def test_step_split_into_launches_over_few_workers(per, monkeypatch):
+@pytest.mark.parametrize("per,tiles", [(1, 0), (3, 3), (8, 5)])
+def test_step_split_into_launches_over_few_workers(per, tiles, monkeypatch):
     """Many workers at large d run as several launches over a few workers each, the votes carried in
-    the counts array; forced here at small sizes.  Same bits and state as one launch."""
+    the counts array, block of tiles by block of tiles; forced here at small sizes (`per` workers per
+    launch, `tiles` tiles per block, 0 = one block).  Same bits and state as one launch."""
     monkeypatch.setenv("DLION_PASS_WORKERS", str(per))
+    monkeypatch.setenv("DLION_PASS_TILES", str(tiles))
     rng = np.random.default_rng(4242 + per)
     for (d, N), mode, g_dtype in itertools.product(((1000, 4), (4099, 9), (257, 17), (70_001, 33), (700, 70)),
                                                    (dl.VOTE, dl.AVG), (torch.float32, torch.bfloat16)):
