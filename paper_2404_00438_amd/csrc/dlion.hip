@@ -663,7 +663,9 @@ dlion_status dlion_aggregate_encode(const uint64_t *packed, int64_t packed_strid
     DLION_TRY(check_rows(packed, packed_stride, words_for(d), N, 8));
     const int32_t planes = delta_planes(N, mode);
     DLION_TRY(check_rows(delta, delta_stride, words_for(d), planes, 8));
-    const Hyper h = make_hyper(N, mode, 0.0f, 0.0f, 0.0f, 0.0f);
+    Hyper h = make_hyper(N, mode, 0.0f, 0.0f, 0.0f, 0.0f);
+    // planes too large to stay cached until they are applied: streaming stores (same field as for counts)
+    h.stream_counts = (int64_t)delta_planes(N, mode) * words_for(d) * 8 > ((int64_t)192 << 20);
     const FlatAddr a = flat_addr(nullptr, nullptr, 0, nullptr, 0, d, const_cast<uint64_t *>(packed),
                                  packed_stride, nullptr);
     const DeltaOut out = {delta, delta_stride, planes};

@@ -23,6 +23,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "../../include/dlion.h"
 
 namespace dlion {
@@ -252,14 +254,34 @@ __device__ __forceinline__ u16x4 counts_load4(const uint16_t *p)
 {
     return *reinterpret_cast<const u16x4_e *>(p);
 }
+// Streaming or ordinary store, chosen at run time.  The empty asm statements keep the two
+// branches from being merged into one store (hoisted above the branch or sunk below it), which
+// silently loses the streaming hint.
 __device__ __forceinline__ void counts_store4(u16x4 v, uint16_t *p, bool stream)
 {
-    if (stream)
+    if (stream) {
+        asm volatile("");
         __builtin_nontemporal_store(v, reinterpret_cast<u16x4_e *>(p));
-    else
+        asm volatile("");
+    } else {
         *reinterpret_cast<u16x4_e *>(p) = v;
+    }
 }
 #define COUNTS_STORE4(v, p) counts_store4(v, p, h.stream_counts)
+
+// eight counts in one 128-bit store
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef u32x4 u16x8_e __attribute__((aligned(2)));
+__device__ __forceinline__ void counts_store8(u32x4 v, uint16_t *p, bool stream)
+{
+    if (stream) {
+        asm volatile("");
+        __builtin_nontemporal_store(v, reinterpret_cast<u16x8_e *>(p));
+        asm volatile("");
+    } else {
+        *reinterpret_cast<u16x8_e *>(p) = v;
+    }
+}
 
 // ---------------------------------------------------------------- gradients
 template <typename GT> struct Grad;
@@ -389,18 +411,13 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
     }
     const int N = h.N, i_begin = h.worker_begin, i_end = h.worker_end;
 
-    // Per-worker coefficients: lane l keeps those of worker (i & ~63) + l, fetched once per 64
-    // workers; each worker's pair is then broadcast from its lane, so that no memory access
-    // sits between a worker's loads and its arithmetic.  Workers are visited in order.
+    // Per-worker coefficients: lane l keeps those of worker (i & ~63) + l, fetched once per block
+    // of 64 workers (outer loop below); each worker's pair is then broadcast from its lane, so
+    // that no memory access sits between a worker's loads and its arithmetic.
     uint32_t pw_beta1 = 0, pw_beta2 = 0;
     auto coef_of = [&](int i) {
         Coef k = {h.beta1, h.omb1, h.beta2, h.omb2};
         if (h.beta1_pw) {                               // uniform
-            if ((i & 63) == 0 || i == i_begin) {
-                const int w = (i & ~63) + lane;
-                pw_beta1 = w < N ? __float_as_uint(h.beta1_pw[w]) : 0u;
-                pw_beta2 = w < N ? __float_as_uint(h.beta2_pw[w]) : 0u;
-            }
             k.beta1 = __uint_as_float(__builtin_amdgcn_readlane(pw_beta1, i & 63));
             k.omb1 = __fsub_rn(1.0f, k.beta1);
             k.beta2 = __uint_as_float(__builtin_amdgcn_readlane(pw_beta2, i & 63));
@@ -433,8 +450,16 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
         }
     };
 
-    int i = i_begin;
-    for (; i + kUnroll <= i_end; i += kUnroll) {
+    for (int c0 = i_begin; c0 < i_end;) {
+    // workers [c0, c1): the rest of c0's block of 64
+    const int c1 = min(i_end, (c0 | 63) + 1);
+    if (h.beta1_pw) {                                   // uniform
+        const int w = (c0 & ~63) + lane;
+        pw_beta1 = w < N ? __float_as_uint(h.beta1_pw[w]) : 0u;
+        pw_beta2 = w < N ? __float_as_uint(h.beta2_pw[w]) : 0u;
+    }
+    int i = c0;
+    for (; i + kUnroll <= c1; i += kUnroll) {
         f32x4 mv[kUnroll][kR], gv[kUnroll][kR];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -451,7 +476,7 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
                 one_worker(i + u, r, mv[u][r], gv[u][r]);
         }
     }
-    for (; i < i_end; ++i) {
+    for (; i < c1; ++i) {
         f32x4 mv[kR], gv[kR];
 #pragma unroll
         for (int r = 0; r < kR; ++r) {
@@ -461,6 +486,8 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
 #pragma unroll
         for (int r = 0; r < kR; ++r)
             one_worker(i, r, mv[r], gv[r]);
+    }
+    c0 = c1;
     }
 
 #pragma unroll
@@ -667,7 +694,6 @@ constexpr int kSlices = 2 * kWpl;                      // 32-bit slices a lane c
 constexpr int kSlicedWords = kLanes * kWpl;            // words per wave
 constexpr int kSlicedCoords = kSlicedWords * 64;
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef u32x4 words2_e __attribute__((aligned(8)));
 
 // two consecutive packed words (only promised the alignment of one) in one 128-bit access
@@ -716,43 +742,8 @@ __device__ __forceinline__ void sliced_count(const Problem &p, int N, int64_t w0
             hi[b][q] = 0;
     }
 
-    for (int i = 0; i < N; i += 16) {
-        uint32_t v[16][kSlices];
-        if (fast) {
-#pragma unroll
-            for (int k = 0; k < 16; ++k) {
-#pragma unroll
-                for (int q = 0; q < kSlices; ++q)
-                    v[k][q] = 0;
-                if (i + k < N) {                             // uniform: rows past N contribute zeros
-                    // uniform row base + small per-lane offset
-                    const uint64_t *row = p.packed + (int64_t)(i + k) * p.packed_stride + w0;
-                    if (kWpl == 2) {
-                        const u32x4 r = packed_load2(row + 2 * lane);
-                        v[k][0] = r.x;
-                        v[k][1] = r.y;
-                        v[k][kSlices - 2] = r.z;
-                        v[k][kSlices - 1] = r.w;
-                    } else {
-                        const u32x2 r = stream_load(reinterpret_cast<const u32x2 *>(row) + lane);
-                        v[k][0] = r.x;
-                        v[k][1] = r.y;
-                    }
-                }
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < 16; ++k) {
-#pragma unroll
-                for (int q = 0; q < kWpl; ++q) {
-                    uint64_t word = 0;
-                    if (i + k < N && wl0 + q < W)
-                        word = stream_load(p.packed + (int64_t)(i + k) * p.packed_stride + wl0 + q);
-                    v[k][2 * q] = static_cast<uint32_t>(word);
-                    v[k][2 * q + 1] = static_cast<uint32_t>(word >> 32);
-                }
-            }
-        }
+    // adds one batch of 16 words per slice (carry-save tree, then a ripple into the upper planes)
+    auto add_batch = [&](const uint32_t (&v)[16][kSlices]) {
 #pragma unroll
         for (int q = 0; q < kSlices; ++q) {
             uint32_t t0, t1, t2, t3, t4, t5, t6, t7, f0, f1, f2, f3, e0, e1, s16;
@@ -779,8 +770,67 @@ __device__ __forceinline__ void sliced_count(const Problem &p, int N, int64_t w0
                 s16 = c;
             }
         }
-        if (kWaves > 1)
-            __builtin_amdgcn_s_barrier();
+    };
+    // one batch of 16 rows starting at row i, full-width loads; guard_rows: rows past N count as zeros
+    auto load_rows = [&](int i, uint32_t (&v)[16][kSlices], auto guard_rows) {
+        // the row base is uniform; each lane adds a small unsigned byte offset
+        const uint32_t lane_bytes = static_cast<uint32_t>(lane) * (8u * kWpl);
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+#pragma unroll
+            for (int q = 0; q < kSlices; ++q)
+                v[k][q] = 0;
+            if (!decltype(guard_rows)::value || i + k < N) {        // uniform
+                const char *row = reinterpret_cast<const char *>(p.packed + (int64_t)(i + k) * p.packed_stride + w0);
+                if (kWpl == 2) {
+                    const u32x4 r = packed_load2(reinterpret_cast<const uint64_t *>(row + lane_bytes));
+                    v[k][0] = r.x;
+                    v[k][1] = r.y;
+                    v[k][kSlices - 2] = r.z;
+                    v[k][kSlices - 1] = r.w;
+                } else {
+                    const u32x2 r = stream_load(reinterpret_cast<const u32x2 *>(row + lane_bytes));
+                    v[k][0] = r.x;
+                    v[k][1] = r.y;
+                }
+            }
+        }
+    };
+    if (fast) {
+        int i = 0;
+        for (; i + 16 <= N; i += 16) {
+            uint32_t v[16][kSlices];
+            load_rows(i, v, std::false_type());
+            add_batch(v);
+            if (kWaves > 1)
+                __builtin_amdgcn_s_barrier();
+        }
+        if (i < N) {
+            uint32_t v[16][kSlices];
+            load_rows(i, v, std::true_type());
+            add_batch(v);
+            if (kWaves > 1)
+                __builtin_amdgcn_s_barrier();
+        }
+    } else {
+        // ragged end of the word range: per-lane guards (same number of batches, hence of barriers)
+        for (int i = 0; i < N; i += 16) {
+            uint32_t v[16][kSlices];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+#pragma unroll
+                for (int q = 0; q < kWpl; ++q) {
+                    uint64_t word = 0;
+                    if (i + k < N && wl0 + q < W)
+                        word = stream_load(p.packed + (int64_t)(i + k) * p.packed_stride + wl0 + q);
+                    v[k][2 * q] = static_cast<uint32_t>(word);
+                    v[k][2 * q + 1] = static_cast<uint32_t>(word >> 32);
+                }
+            }
+            add_batch(v);
+            if (kWaves > 1)
+                __builtin_amdgcn_s_barrier();
+        }
     }
 #pragma unroll
     for (int q = 0; q < kSlices; ++q) {
@@ -817,7 +867,6 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_sliced_kernel(FlatA
         return;
     Planes<kPlanes> pl;
     sliced_count<kPlanes, kWaves>(p, h.N, w0, W, lane, pl);
-
     // stage: lds[b][2*wl + half] = low / high dword of plane b of word wl of the group
 #pragma unroll
     for (int q = 0; q < kSlices; ++q) {
@@ -827,16 +876,9 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_sliced_kernel(FlatA
     }
     __syncthreads();
 
-    // now lane l owns coordinates 4*(l&15).. of word 4*s + (l>>4), s = 0..kSlicedWords/4-1
-#pragma unroll 2
-    for (int s = 0; s < kSlicedWords / kWordsPerSub; ++s) {
-        const int wl = s * kWordsPerSub + (lane >> 4);          // word within the group
-        const int64_t j0 = (w0 + wl) * 64 + (lane & 15) * kVec;
-        if (j0 >= p.numel)
-            continue;
-        const int dword = 2 * wl + ((lane >> 3) & 1);
-        const int shift = (lane & 7) * 4;
-        // byte k of lo / up collects bits 0..7 / 8..15 of the count of coordinate j0 + k
+    // counts of the 4 coordinates whose bits sit at [shift, shift+4) of dword `dword` of every plane
+    auto unpack4 = [&](int dword, int shift, uint32_t (&cnt)[4]) {
+        // byte k of lo / up collects bits 0..7 / 8..15 of the count of coordinate k
         uint32_t lo = 0, up = 0;
 #pragma unroll
         for (int b = 0; b < kPlanes; ++b) {
@@ -846,13 +888,85 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_sliced_kernel(FlatA
             else
                 up += bytes << (b - 8);
         }
-        uint32_t cnt[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k)
             cnt[k] = ((lo >> (8 * k)) & 0xFFu) | (kPlanes > 8 ? ((up >> (8 * k)) & 0xFFu) << 8 : 0u);
-        const bool full = j0 + kVec <= p.numel;
-        if (kApply) {
-            if (full) {
+    };
+
+    if (kCounts) {
+        // lane l owns the 8 coordinates of byte l&7 of word 8*s + (l>>3): 16 bytes of counts per
+        // lane, 1 KB per store instruction.  Stores of 8 bytes per lane (4 coordinates) reach
+        // memory as 32-byte pieces and cost 13 % of the whole pass at N = 256 (6.45 -> 5.71 ms).
+        constexpr int kSteps = kSlicedWords / 8;
+        auto counts8 = [&](int s, u32x4 &c, uint32_t (&c0)[4], uint32_t (&c1)[4]) {
+            const int wl = s * 8 + (lane >> 3);                     // word within the group
+            const int dword = 2 * wl + ((lane >> 2) & 1);
+            const int shift = (lane & 3) * 8;
+            unpack4(dword, shift, c0);
+            unpack4(dword, shift + 4, c1);
+            c.x = c0[0] | (c0[1] << 16);
+            c.y = c0[2] | (c0[3] << 16);
+            c.z = c1[0] | (c1[1] << 16);
+            c.w = c1[2] | (c1[3] << 16);
+        };
+        if ((w0 + kSlicedWords) * 64 <= p.numel) {                  // uniform: the whole group is inside
+            // all results first, then the stores back to back (and, with several waves, together)
+            u32x4 c[kSteps];
+#pragma unroll
+            for (int s = 0; s < kSteps; ++s) {
+                uint32_t c0[4], c1[4];
+                counts8(s, c[s], c0, c1);
+            }
+            if (kWaves > 1)
+                __builtin_amdgcn_s_barrier();
+            uint16_t *dst = p.counts + w0 * 64 + lane * 8;         // + 512 coordinates per step
+            if (h.stream_counts) {
+                asm volatile("");                                   // see counts_store4
+#pragma unroll
+                for (int s = 0; s < kSteps; ++s)
+                    __builtin_nontemporal_store(c[s], reinterpret_cast<u16x8_e *>(dst + s * 512));
+                asm volatile("");
+            } else {
+#pragma unroll
+                for (int s = 0; s < kSteps; ++s)
+                    *reinterpret_cast<u16x8_e *>(dst + s * 512) = c[s];
+            }
+        } else {
+            if (kWaves > 1)
+                __builtin_amdgcn_s_barrier();                        // same number of barriers on every path
+#pragma unroll 1
+            for (int s = 0; s < kSteps; ++s) {
+                const int64_t j0 = (w0 + s * 8 + (lane >> 3)) * 64 + (lane & 7) * 8;
+                if (j0 >= p.numel)
+                    continue;
+                u32x4 c;
+                uint32_t c0[4], c1[4];
+                counts8(s, c, c0, c1);
+                if (j0 + 8 <= p.numel) {
+                    counts_store8(c, p.counts + j0, h.stream_counts);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        if (j0 + k < p.numel)
+                            p.counts[j0 + k] = static_cast<uint16_t>(c0[k]);
+                        if (j0 + 4 + k < p.numel)
+                            p.counts[j0 + 4 + k] = static_cast<uint16_t>(c1[k]);
+                    }
+                }
+            }
+        }
+    }
+    if (kApply) {
+        // lane l owns coordinates 4*(l&15).. of word 4*s + (l>>4): 16 bytes of x per lane
+#pragma unroll 2
+        for (int s = 0; s < kSlicedWords / kWordsPerSub; ++s) {
+            const int wl = s * kWordsPerSub + (lane >> 4);
+            const int64_t j0 = (w0 + wl) * 64 + (lane & 15) * kVec;
+            if (j0 >= p.numel)
+                continue;
+            uint32_t cnt[4];
+            unpack4(2 * wl + ((lane >> 3) & 1), (lane & 7) * 4, cnt);
+            if (j0 + kVec <= p.numel) {
                 f32x4 xv = x_load4(p.x + j0);
                 xv.x = lion_apply(xv.x, aggregate_votes(cnt[0], h), h);
                 xv.y = lion_apply(xv.y, aggregate_votes(cnt[1], h), h);
@@ -864,21 +978,6 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_sliced_kernel(FlatA
                 for (int k = 0; k < kVec; ++k)
                     if (j0 + k < p.numel)
                         p.x[j0 + k] = lion_apply(p.x[j0 + k], aggregate_votes(cnt[k], h), h);
-            }
-        }
-        if (kCounts) {
-            if (full) {
-                u16x4 c;
-                c.x = static_cast<uint16_t>(cnt[0]);
-                c.y = static_cast<uint16_t>(cnt[1]);
-                c.z = static_cast<uint16_t>(cnt[2]);
-                c.w = static_cast<uint16_t>(cnt[3]);
-                COUNTS_STORE4(c, p.counts + j0);
-            } else {
-#pragma unroll
-                for (int k = 0; k < kVec; ++k)
-                    if (j0 + k < p.numel)
-                        p.counts[j0 + k] = static_cast<uint16_t>(cnt[k]);
             }
         }
     }
@@ -935,13 +1034,12 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_encode_kernel(FlatA
         }
     }
     const int64_t wl0 = w0 + (int64_t)lane * kWpl;
+    const bool whole = w0 + kSlicedWords <= W;              // uniform: every lane's words exist
 #pragma unroll 1
     for (int b = 0; b < out.n_planes; ++b) {
+        uint64_t word[kWpl];
 #pragma unroll
         for (int q = 0; q < kWpl; ++q) {
-            const int64_t w = wl0 + q;
-            if (w >= W)
-                continue;
             uint32_t lo, up;
             if (h.mode == DLION_VOTE) {
                 lo = b == 0 ? res[0][2 * q] : res[1][2 * q];
@@ -956,11 +1054,31 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_encode_kernel(FlatA
                     }
                 }
             }
-            uint64_t word = (static_cast<uint64_t>(up) << 32) | lo;
-            const int64_t left = p.numel - w * 64;            // coordinates in this word
+            word[q] = (static_cast<uint64_t>(up) << 32) | lo;
+            const int64_t left = p.numel - (wl0 + q) * 64;    // coordinates in this word
             if (left < 64)
-                word &= (static_cast<uint64_t>(1) << left) - 1;   // bits past d are zero
-            out.planes[(int64_t)b * out.stride + w] = word;
+                word[q] &= left > 0 ? (static_cast<uint64_t>(1) << left) - 1 : 0;   // bits past d are zero
+        }
+        uint64_t *dst = out.planes + (int64_t)b * out.stride + wl0;
+        if (whole && kWpl == 2) {
+            // both words of the lane in one 128-bit store: 1 KB per instruction
+            u32x4 v;
+            v.x = static_cast<uint32_t>(word[0]);
+            v.y = static_cast<uint32_t>(word[0] >> 32);
+            v.z = static_cast<uint32_t>(word[kWpl - 1]);
+            v.w = static_cast<uint32_t>(word[kWpl - 1] >> 32);
+            if (h.stream_counts) {
+                asm volatile("");                                   // see counts_store4
+                __builtin_nontemporal_store(v, reinterpret_cast<words2_e *>(dst));
+                asm volatile("");
+            } else {
+                *reinterpret_cast<words2_e *>(dst) = v;
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < kWpl; ++q)
+                if (wl0 + q < W)
+                    dst[q] = word[q];
         }
     }
 }
