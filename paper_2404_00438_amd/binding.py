@@ -48,7 +48,8 @@ class Seg(ctypes.Structure):
 
 
 def load_library(path: Optional[str] = None) -> ctypes.CDLL:
-    """Load ``libdlion.so`` and declare the prototypes; raises if it has not been built."""
+    """Load ``libdlion.so`` (or the build at ``path``), declare the prototypes and make it the library the
+    functions of this module call; raises if the file is missing."""
     global _lib
     if _lib is not None and path is None:
         return _lib
@@ -87,8 +88,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.dlion_status_str.restype = ctypes.c_char_p
     lib.dlion_version.argtypes = []
     lib.dlion_version.restype = ci
-    if path is None:
-        _lib = lib
+    _lib = lib                      # every later call goes to the library loaded last
     return lib
 
 
