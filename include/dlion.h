@@ -156,6 +156,8 @@ dlion_status dlion_worker_step_mt(const dlion_seg *segs_host, const dlion_seg *s
                                   dlion_dtype g_dtype, uint64_t *packed, int64_t packed_stride,
                                   int32_t N, float beta1, float beta2, void *stream);
 
+/* packed: rows as dlion_worker_step_mt writes them (the unused bits of every tensor's last word
+ * are zero); the counts of those padding positions come out as 0. */
 dlion_status dlion_aggregate_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev, int32_t K,
                                 const uint64_t *packed, int64_t packed_stride, int32_t N,
                                 uint16_t *counts, void *stream);

@@ -59,11 +59,11 @@ inline dlion_status launched()
 // reserving (unused) dynamic LDS per workgroup: a compute unit has 160 KB, so a reservation
 // of 160 KB / k admits k workgroups.
 //
-// What was tried and dropped for many workers: 16-wave workgroups walking over the workers
-// in lockstep cut the per-CU translation-cache misses 15x at N = 32 (5.5 M against 84 M per
-// launch) but were 1-3 % slower on the same allocation; the large run-to-run spread at
-// N = 32 (65-76 % of peak) follows the physical placement of the allocation, not the launch
-// shape.
+// What was tried and dropped for many workers in one launch: 16-wave workgroups walking over
+// the workers in lockstep cut the per-CU translation-cache misses 15x at N = 32 (5.5 M against
+// 84 M per launch) but were 1-3 % slower on the same allocation; the large run-to-run spread
+// of one launch at N = 32 (65-76 % of peak) follows the physical placement of the allocation,
+// not the launch shape.  What works is fewer workers per launch (launch_step below).
 struct LaunchShape {
     int unroll;          // workers whose loads are issued back to back (8, 4, 2 or 1)
     int blocks_per_cu;   // resident workgroups per compute unit (0: no cap)
@@ -248,21 +248,30 @@ dlion_status launch_sliced_shape(const FlatAddr &addr, const Hyper &h, bool appl
     return launched();
 }
 
-constexpr int kSlicedMinWorkers = 8;    // below this the per-nibble kernel is cheaper
-constexpr int kSlicedLockstepMinWorkers = 64;   // measured: 1 wave wins at N = 32, 8 waves at N = 256
+// Waves per workgroup of the bit-sliced kernels (they walk the streams in lockstep and write
+// together).  Measured with streaming count stores, N = 16 / 32 / 64 / 256 (d = 350 M, 350 M,
+// 1 G, 1 G), counts only: 1 wave 0.261 / 0.379 / 1.82 / 6.43 ms, 8 waves 0.249 / 0.367 / 1.75 /
+// 5.67 ms, 16 waves 0.270 / 0.395 / 1.74 / 5.45 ms; with the weight update fused 16 waves lose
+// below N = 128 (N = 64: 3.03 against 2.86 ms).
+constexpr int kSlicedWaves = 8;
+constexpr int kSliced16MinWorkers = 128;
 
-// measured crossover: counts only -> N >= 8; with the weight update fused -> N >= 16
-inline bool use_sliced(int32_t N, bool apply)
+// Flat buffers always take the bit-sliced kernel: with 8-wave workgroups and 128-bit streaming
+// count stores it beats the per-nibble kernel at every N (d = 350 M, counts only, N = 2 / 8 / 16:
+// 0.150 / 0.188 / 0.245 ms against 0.391 / 0.313 / 0.433 ms; with the weight update fused
+// 0.471 / 0.520 / 0.592 against 0.540 / 0.580 / 0.697 ms).  The per-nibble kernel serves the
+// tensor lists' fused aggregate + update, whose x lives in separate tensors.
+inline bool use_sliced(int32_t N)
 {
-    const int env_min = env_int("DLION_SLICED_MIN_WORKERS");
-    return N >= (env_min >= 0 ? env_min : (apply ? 2 * kSlicedMinWorkers : kSlicedMinWorkers));
+    const int env_min = env_int("DLION_SLICED_MIN_WORKERS");      // tuning: per-nibble kernel below this N
+    return N >= (env_min >= 0 ? env_min : 1);
 }
 
 template <int kPlanes, bool kAllow16>
 dlion_status launch_sliced_planes(const FlatAddr &addr, const Hyper &h, bool apply, bool counts, hipStream_t s)
 {
     const int env_waves = env_int("DLION_SLICED_WAVES");   // tuning: 1, 8 or 16
-    const int waves = env_waves > 0 ? env_waves : (h.N >= kSlicedLockstepMinWorkers ? 8 : 1);
+    const int waves = env_waves > 0 ? env_waves : (h.N >= kSliced16MinWorkers ? 16 : kSlicedWaves);
     if (waves >= 16 && kAllow16)
         return launch_sliced_shape<kPlanes, kAllow16 ? 16 : 8>(addr, h, apply, counts, s);
     if (waves >= 8)
@@ -315,7 +324,7 @@ template <int kPlanes>
 dlion_status launch_encode_planes(const FlatAddr &addr, const Hyper &h, const DeltaOut &out, hipStream_t s)
 {
     const int env_waves = env_int("DLION_SLICED_WAVES");
-    const int waves = env_waves > 0 ? env_waves : (h.N >= kSlicedLockstepMinWorkers ? 8 : 1);
+    const int waves = env_waves > 0 ? env_waves : kSlicedWaves;
     if (waves >= 8)
         return launch_encode_shape<kPlanes, 8>(addr, h, out, s);
     return launch_encode_shape<kPlanes, 1>(addr, h, out, s);
@@ -481,7 +490,7 @@ dlion_status dlion_aggregate(const uint64_t *packed, int64_t packed_stride, int6
     h.stream_counts = counts_exceed_cache(d);
     const FlatAddr a = flat_addr(nullptr, nullptr, 0, nullptr, 0, d, const_cast<uint64_t *>(packed),
                                  packed_stride, counts);
-    if (use_sliced(N, false))
+    if (use_sliced(N))
         return launch_sliced(a, h, false, true, static_cast<hipStream_t>(stream));
     return launch_aggregate(a, h, false, true, static_cast<hipStream_t>(stream));
 }
@@ -513,7 +522,7 @@ dlion_status dlion_aggregate_apply(float *x, const uint64_t *packed, int64_t pac
     h.stream_counts = counts_or_null ? counts_exceed_cache(d) : 0;
     const FlatAddr a = flat_addr(x, nullptr, 0, nullptr, 0, d, const_cast<uint64_t *>(packed), packed_stride,
                                  counts_or_null);
-    if (use_sliced(N, true))
+    if (use_sliced(N))
         return launch_sliced(a, h, true, counts_or_null != nullptr, static_cast<hipStream_t>(stream));
     return launch_aggregate(a, h, true, counts_or_null != nullptr, static_cast<hipStream_t>(stream));
 }
@@ -589,6 +598,13 @@ dlion_status dlion_aggregate_mt(const dlion_seg *segs_host, const dlion_seg *seg
         return DLION_EALIGN;
     Hyper h = make_hyper(N, DLION_VOTE, 0.0f, 0.0f, 0.0f, 0.0f);
     h.stream_counts = counts_exceed_cache(64 * words);
+    if (use_sliced(N)) {
+        // packed words and counts of a tensor list are laid out by word, the padding bits of every
+        // tensor's last word are zero: counting is the flat problem over 64 * words coordinates
+        const FlatAddr f = flat_addr(nullptr, nullptr, 0, nullptr, 0, 64 * words, const_cast<uint64_t *>(packed),
+                                     packed_stride, counts);
+        return launch_sliced(f, h, false, true, static_cast<hipStream_t>(stream));
+    }
     const SegAddr a = seg_addr(segs_dev, K, tiles, const_cast<uint64_t *>(packed), packed_stride, counts);
     return launch_aggregate(a, h, false, true, static_cast<hipStream_t>(stream));
 }

@@ -295,7 +295,8 @@ def test_tiny_config_full_run():
 def test_many_worker_aggregate_matches_oracle():
     """The bit-sliced server-side kernel (many workers): counts bit-exact, apply within the bar."""
     rng = np.random.default_rng(2024)
-    cases = [(16, 4096), (17, 4097), (31, 1), (32, 63), (33, 10_000), (64, 8192 + 5), (127, 4095),
+    cases = [(1, 300), (2, 8192), (3, 8193), (7, 70_001), (8, 129), (15, 5000),
+             (16, 4096), (17, 4097), (31, 1), (32, 63), (33, 10_000), (64, 8192 + 5), (127, 4095),
              (128, 70_001), (255, 5000), (256, 12_345), (257, 4096 * 3), (511, 300), (512, 4096),
              (1000, 9000), (4095, 700), (4096, 130), (5000, 4100), (65535, 130)]
     for N, d in cases:
@@ -456,6 +457,34 @@ def test_step_split_into_launches_over_few_workers(per, tiles, monkeypatch):
         for k in range(len(numels)):
             assert_f32_equal(to_np(xs[k]), xn[k], f"x[{k}]")
             assert_f32_equal(to_np(ms[k]), mn[k], f"m[{k}]")
+
+
+def test_per_nibble_server_kernel_on_flat_buffers(monkeypatch):
+    """Flat buffers take the bit-sliced server kernel at every N; the per-nibble one (which tensor
+    lists use for the fused aggregate + update) is forced here so that its flat form stays checked."""
+    monkeypatch.setenv("DLION_SLICED_MIN_WORKERS", "100000")
+    rng = np.random.default_rng(515)
+    for N, d in ((1, 1), (2, 63), (3, 257), (8, 4096 + 3), (9, 70_001), (33, 1000), (300, 5000)):
+        W = dl.words_for(d)
+        bits = rng.random((N, W * 64)) < 0.6
+        bits[:, d:] = False
+        words = np.packbits(bits, axis=1, bitorder="little").view("<u8")
+        want = oracle.aggregate_packed(np.ascontiguousarray(words), d)
+        packed = strided_rows(N, W, W + 1, torch.int64, DEV)
+        packed.copy_(torch.from_numpy(words.view(np.int64)))
+        for mode in (dl.VOTE, dl.AVG):
+            announce("per-nibble forced", "N", N, "d", d, "mode", mode)
+            counts = torch.full((d,), -1, dtype=torch.int16, device=DEV)
+            dl.dlion_aggregate(packed, d, counts)
+            xv = rng.normal(0, 0.02, d).astype(np.float32)
+            x = torch.from_numpy(xv).to(DEV)
+            xn = xv.copy()
+            oracle.apply(xn, want, N, mode, 0.25, 0.5)
+            counts2 = torch.full((d,), -1, dtype=torch.int16, device=DEV)
+            dl.dlion_aggregate_apply(x, packed, mode, 0.25, 0.5, counts=counts2)
+            torch.cuda.synchronize()
+            assert np.array_equal(to_np(counts), want) and np.array_equal(to_np(counts2), want)
+            assert_f32_equal(to_np(x), xn, f"N={N} d={d} mode={mode}: x")
 
 
 def test_randomized_shapes_strides_and_flags():
