@@ -678,14 +678,15 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(Addr addr, Hyper h)
     }
 }
 
-// ---------------------------------------------------------------- server side, many workers
+// ---------------------------------------------------------------- server side, bit-sliced
 // Bit-sliced ("vertical") counting.  One wave owns kSlicedWords consecutive packed words;
 // lane l reads kWpl consecutive words of every stream (1 KB contiguous per load instruction)
 // and adds the N words into kPlanes bit-planes with carry-save adders: after the loop, bit c
 // of plane b of a word is bit b of the vote count of that word's coordinate c.  About one
 // bitwise operation per 32 coordinates and input word replaces 32 extract-and-add steps.  The planes
-// are then staged through LDS so that the lanes can switch from "kWpl words each" to "four
-// consecutive coordinates each" and write counts / update x with full-width accesses.
+// are then staged through LDS so that the lanes can switch from "kWpl words each" to "eight
+// consecutive coordinates each" (counts) or "four consecutive coordinates each" (x) and write
+// with 128-bit accesses.
 #ifndef DLION_SLICED_WORDS_PER_LANE
 #define DLION_SLICED_WORDS_PER_LANE 2      // consecutive words of each stream a lane reads (1 or 2)
 #endif
