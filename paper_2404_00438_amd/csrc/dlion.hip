@@ -19,6 +19,13 @@ inline int64_t words_for(int64_t numel) { return (numel + 63) / 64; }
 
 inline bool power_of_two(int32_t n) { return n > 0 && (n & (n - 1)) == 0; }
 
+// Environment overrides for tuning runs (read on every call).
+inline int env_int(const char *name)
+{
+    const char *v = std::getenv(name);
+    return v ? std::atoi(v) : -1;
+}
+
 Hyper make_hyper(int32_t N, int mode, float beta1, float beta2, float lr, float lambda)
 {
     Hyper h;
@@ -35,6 +42,7 @@ Hyper make_hyper(int32_t N, int mode, float beta1, float beta2, float lr, float 
     h.worker_begin = 0;
     h.worker_end = N;
     h.counts_in = 0;
+    h.xcd_quads = 0;
     h.beta1_pw = nullptr;
     h.beta2_pw = nullptr;
     return h;
@@ -43,6 +51,21 @@ Hyper make_hyper(int32_t N, int mode, float beta1, float beta2, float lr, float 
 // The memory-side cache holds 256 MB; a counts array (2 B per coordinate) well below that is
 // still there when the next call reads it.
 inline int32_t counts_exceed_cache(int64_t coords) { return coords * 2 > (int64_t)192 << 20; }
+
+// Rows that do not start on a 128-byte line: a wave's piece of such a row shares its first and
+// last line with the neighbouring tiles.  The worker/fused kernels then put 4 consecutive tiles
+// on one XCD, so that most shared lines meet in one L2 instead of being fetched, and written
+// back in part, by two (d = 50 M, N = 8, row stride d + 1: 61.8 -> 69.6 % of peak; stride d + 16:
+// 71.9 -> 75.2 %).  Aligned rows lose 0-0.7 % with that numbering and keep the plain one.
+inline bool rows_split_lines(const void *base, int64_t stride, size_t elem, int32_t N)
+{
+    return !aligned_to(base, 128) || (N > 1 && (static_cast<uint64_t>(stride) * elem) % 128 != 0);
+}
+inline int32_t step_quads(bool split)
+{
+    const int env = env_int("DLION_STEP_QUADS");           // tuning: 0 / 1 forces the numbering
+    return env >= 0 ? (env > 0) : (split ? 1 : 0);
+}
 
 inline dim3 grid_for(int64_t tiles) { return dim3(static_cast<uint32_t>((tiles + kWavesPerBlock - 1) / kWavesPerBlock)); }
 
@@ -82,12 +105,6 @@ inline size_t lds_reservation(int blocks_per_cu)
     return bytes > kMaxDynamicLds ? kMaxDynamicLds : bytes;
 }
 
-// Environment overrides for tuning runs: DLION_UNROLL, DLION_BLOCKS_PER_CU.
-inline int env_int(const char *name)
-{
-    const char *v = std::getenv(name);
-    return v ? std::atoi(v) : -1;
-}
 
 LaunchShape step_shape(int32_t N, size_t bytes_per_worker_per_wave)
 {
@@ -411,10 +428,12 @@ FlatAddr flat_addr(float *x, float *m, int64_t m_stride, const void *g, int64_t 
 enum SegNeeds { kNeedX = 1, kNeedM = 2, kNeedG = 4 };
 
 dlion_status check_segs(const dlion_seg *segs_host, const dlion_seg *segs_dev, int32_t K, int32_t N,
-                        int needs, dlion_dtype g_dtype, int64_t *total_words, int64_t *total_tiles)
+                        int needs, dlion_dtype g_dtype, int64_t *total_words, int64_t *total_tiles,
+                        bool *rows_split = nullptr)
 {
     if (!segs_host || !segs_dev || K < 1 || N < 1 || N > DLION_MAX_WORKERS)
         return DLION_EINVAL;
+    bool split = false;
     if (!aligned_to(segs_dev, 8))
         return DLION_EALIGN;
     int64_t words = 0, tiles = 0;
@@ -430,10 +449,14 @@ dlion_status check_segs(const dlion_seg *segs_host, const dlion_seg *segs_dev, i
             if (!aligned_to(s.x, 4))
                 return DLION_EALIGN;
         }
-        if (needs & kNeedM)
+        if (needs & kNeedM) {
             DLION_TRY(check_rows(s.m, s.m_stride, s.numel, N, 4));
-        if (needs & kNeedG)
+            split = split || rows_split_lines(s.m, s.m_stride, 4, N);
+        }
+        if (needs & kNeedG) {
             DLION_TRY(check_rows(s.g, s.g_stride, s.numel, N, grad_size(g_dtype)));
+            split = split || rows_split_lines(s.g, s.g_stride, grad_size(g_dtype), N);
+        }
         words += words_for(s.numel);
         tiles += tiles_for(s.numel);
         if (tiles > kMaxTiles)
@@ -441,6 +464,8 @@ dlion_status check_segs(const dlion_seg *segs_host, const dlion_seg *segs_dev, i
     }
     *total_words = words;
     *total_tiles = tiles;
+    if (rows_split)
+        *rows_split = split;
     return DLION_OK;
 }
 
@@ -472,7 +497,8 @@ dlion_status dlion_worker_step(float *m, int64_t m_stride, const void *g, int64_
     DLION_TRY(check_rows(m, m_stride, d, N, 4));
     DLION_TRY(check_rows(g, g_stride, d, N, grad_size(g_dtype)));
     DLION_TRY(check_rows(packed, packed_stride, words_for(d), N, 8));
-    const Hyper h = make_hyper(N, DLION_VOTE, beta1, beta2, 0.0f, 0.0f);
+    Hyper h = make_hyper(N, DLION_VOTE, beta1, beta2, 0.0f, 0.0f);
+    h.xcd_quads = step_quads(rows_split_lines(m, m_stride, 4, N) || rows_split_lines(g, g_stride, grad_size(g_dtype), N));
     const FlatAddr a = flat_addr(nullptr, m, m_stride, g, g_stride, d, packed, packed_stride, nullptr);
     return launch_step<false>(a, h, g_dtype, true, false, static_cast<hipStream_t>(stream));
 }
@@ -543,6 +569,7 @@ dlion_status dlion_step(float *x, float *m, int64_t m_stride, const void *g, int
         DLION_TRY(check_rows(packed_or_null, packed_stride, words_for(d), N, 8));
     Hyper h = make_hyper(N, mode, beta1, beta2, lr, lambda);
     h.stream_counts = counts_or_null ? counts_exceed_cache(d) : 0;
+    h.xcd_quads = step_quads(rows_split_lines(m, m_stride, 4, N) || rows_split_lines(g, g_stride, grad_size(g_dtype), N));
     const FlatAddr a = flat_addr(x, m, m_stride, g, g_stride, d, packed_or_null, packed_stride, counts_or_null);
     return launch_step<true>(a, h, g_dtype, packed_or_null != nullptr, counts_or_null != nullptr,
                              static_cast<hipStream_t>(stream));
@@ -578,9 +605,11 @@ dlion_status dlion_worker_step_mt(const dlion_seg *segs_host, const dlion_seg *s
     if (!dtype_ok(g_dtype))
         return DLION_EINVAL;
     int64_t words, tiles;
-    DLION_TRY(check_segs(segs_host, segs_dev, K, N, kNeedM | kNeedG, g_dtype, &words, &tiles));
+    bool split;
+    DLION_TRY(check_segs(segs_host, segs_dev, K, N, kNeedM | kNeedG, g_dtype, &words, &tiles, &split));
     DLION_TRY(check_rows(packed, packed_stride, words, N, 8));
-    const Hyper h = make_hyper(N, DLION_VOTE, beta1, beta2, 0.0f, 0.0f);
+    Hyper h = make_hyper(N, DLION_VOTE, beta1, beta2, 0.0f, 0.0f);
+    h.xcd_quads = step_quads(split);
     const SegAddr a = seg_addr(segs_dev, K, tiles, packed, packed_stride, nullptr);
     return launch_step<false>(a, h, g_dtype, true, false, static_cast<hipStream_t>(stream));
 }
@@ -652,11 +681,13 @@ dlion_status dlion_step_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev
     if (!aligned_to(counts_or_null, 2))
         return DLION_EALIGN;
     int64_t words, tiles;
-    DLION_TRY(check_segs(segs_host, segs_dev, K, N, kNeedX | kNeedM | kNeedG, g_dtype, &words, &tiles));
+    bool split;
+    DLION_TRY(check_segs(segs_host, segs_dev, K, N, kNeedX | kNeedM | kNeedG, g_dtype, &words, &tiles, &split));
     if (packed_or_null)
         DLION_TRY(check_rows(packed_or_null, packed_stride, words, N, 8));
     Hyper h = make_hyper(N, mode, beta1, beta2, lr, lambda);
     h.stream_counts = counts_or_null ? counts_exceed_cache(64 * words) : 0;
+    h.xcd_quads = step_quads(split);
     const SegAddr a = seg_addr(segs_dev, K, tiles, packed_or_null, packed_stride, counts_or_null);
     return launch_step<true>(a, h, g_dtype, packed_or_null != nullptr, counts_or_null != nullptr,
                              static_cast<hipStream_t>(stream));
@@ -729,6 +760,7 @@ dlion_status dlion_worker_step_pw(float *m, int64_t m_stride, const void *g, int
     Hyper h = make_hyper(N, DLION_VOTE, 0.0f, 0.0f, 0.0f, 0.0f);
     h.beta1_pw = beta1;
     h.beta2_pw = beta2;
+    h.xcd_quads = step_quads(rows_split_lines(m, m_stride, 4, N) || rows_split_lines(g, g_stride, grad_size(g_dtype), N));
     const FlatAddr a = flat_addr(nullptr, m, m_stride, g, g_stride, d, packed, packed_stride, nullptr);
     return launch_step<false>(a, h, g_dtype, true, false, static_cast<hipStream_t>(stream));
 }
@@ -751,6 +783,7 @@ dlion_status dlion_step_pw(float *x, float *m, int64_t m_stride, const void *g, 
     h.beta1_pw = beta1;
     h.beta2_pw = beta2;
     h.stream_counts = counts_or_null ? counts_exceed_cache(d) : 0;
+    h.xcd_quads = step_quads(rows_split_lines(m, m_stride, 4, N) || rows_split_lines(g, g_stride, grad_size(g_dtype), N));
     const FlatAddr a = flat_addr(x, m, m_stride, g, g_stride, d, packed_or_null, packed_stride, counts_or_null);
     return launch_step<true>(a, h, g_dtype, packed_or_null != nullptr, counts_or_null != nullptr,
                              static_cast<hipStream_t>(stream));

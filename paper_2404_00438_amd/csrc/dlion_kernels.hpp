@@ -72,6 +72,7 @@ struct Hyper {
     // counts the earlier launches left in the counts array instead of from zero.
     int32_t worker_begin, worker_end;
     int32_t counts_in;
+    int32_t xcd_quads;   // worker/fused kernels: 4 consecutive tiles per XCD (quad_tile_index)
     const float *beta1_pw;   // per-worker coefficients (device arrays of N floats), or null:
     const float *beta2_pw;   // then beta1/beta2 above are shared by all workers
 };
@@ -550,7 +551,7 @@ __device__ __forceinline__ void step_subtile_guarded(const Problem &p, int64_t t
 template <typename GT, int kUnroll, bool kApply, bool kPacked, bool kCounts, class Addr>
 __global__ __launch_bounds__(kBlock) void step_kernel(Addr addr, Hyper h)
 {
-    const int64_t tile = addr.first_tile + wave_tile_index();
+    const int64_t tile = addr.first_tile + ((kWavesPerBlock == 1 && h.xcd_quads) ? quad_tile_index() : wave_tile_index());
     if (tile >= addr.total_tiles)
         return;
     const int lane = threadIdx.x & 63;
