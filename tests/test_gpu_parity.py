@@ -542,3 +542,30 @@ def test_calls_follow_the_given_stream():
         done.record()
     done.synchronize()
     compare_all("side stream", x, m, packed, counts, xn, mn, pn, cn)
+
+
+def test_step_can_be_captured_in_a_graph(monkeypatch):
+    """The calls allocate nothing and never synchronise, so a step (here split into several launches)
+    can be captured once and replayed; every replay is checked, with eager work in between."""
+    monkeypatch.setenv("DLION_PASS_WORKERS", "3")
+    rng = np.random.default_rng(31)
+    N, d = 7, 70_001
+    x, m, g = draw_state(rng, N, d, torch.bfloat16, d + 3, d + 5)
+    packed = torch.zeros((N, dl.words_for(d)), dtype=torch.int64, device=DEV)
+    counts = torch.zeros(d, dtype=torch.int16, device=DEV)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        dl.dlion_step(x, m, g, dl.AVG, HYP["beta1"], HYP["beta2"], HYP["lr"], HYP["lam"],
+                      packed=packed, counts=counts)
+    for replay in range(3):
+        announce("graph replay", replay)
+        xn, mn, pn, cn = oracle_step(x, m, g, dl.AVG, HYP)
+        graph.replay()
+        torch.cuda.synchronize()
+        compare_all(f"replay {replay}", x, m, packed, counts, xn, mn, pn, cn)
+        # eager work between the replays: new gradients in the same buffer
+        g.copy_(torch.from_numpy(rng.standard_t(3, (N, d)).astype(np.float32) * 1e-3).to(torch.bfloat16))
+        packed.fill_(-1)
+        counts.fill_(-1)
+        torch.cuda.synchronize()
