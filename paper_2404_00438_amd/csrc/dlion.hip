@@ -135,6 +135,9 @@ dlion_status launch_step_flags(const Addr &addr, const Hyper &h, bool packed, bo
                                hipStream_t s)
 {
     const dim3 grid = grid_for(addr.total_tiles - addr.first_tile), block(kBlock);
+    const size_t stage = static_cast<size_t>(kWavesPerBlock) * kLanes * sizeof(uint64_t);
+    if (packed && lds < stage)
+        lds = stage;                                      // packed words are staged in LDS, 512 B per wave
     if (packed && counts)
         hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, true, true, Addr>), grid, block, lds, s, addr, h);
     else if (packed)

@@ -389,9 +389,31 @@ __device__ __forceinline__ uint64_t row_gather_nibbles(uint32_t nibble, int lane
 // Vector path over kR full sub-tiles starting at sub-tile `t`: the loads of kUnroll workers
 // x kR sub-tiles are issued back to back before any arithmetic.
 template <typename GT, int kUnroll, int kR, bool kApply, bool kPacked, bool kCounts>
-__device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t, int lane, const Hyper &h)
+__device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t, int lane, const Hyper &h,
+                                                     uint64_t *stage)
 {
     const int64_t j0 = t * kSubTile + lane * kVec;
+    // packed words wait in `stage` (LDS, private to the wave) until kPackWorkers workers are done
+    constexpr int kPackWorkers = kLanes / (kR * kWordsPerSub);
+    int staged = 0;                                        // uniform
+    auto flush_packed = [&](int i_next) {                  // workers [i_next - staged, i_next)
+        if (!kPacked)
+            return;
+        // the wave's own LDS writes, then its reads: program order is enough inside one wave,
+        // the fences only keep the compiler from moving the accesses
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int worker = lane / (kR * kWordsPerSub);     // lane -> (worker, word of the kR sub-tiles)
+        const int word = lane % (kR * kWordsPerSub);
+        if (worker < staged) {
+            const uint64_t v = stage[lane];
+            p.packed[(int64_t)(i_next - staged + worker) * p.packed_stride + t * kWordsPerSub + word] = v;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        staged = 0;
+    };
     f32x4 xv[kR];
     if (kApply) {
 #pragma unroll
@@ -446,8 +468,12 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
         if (kPacked) {
             const uint32_t nib = (b0 ? 1u : 0u) | (b1 ? 2u : 0u) | (b2 ? 4u : 0u) | (b3 ? 8u : 0u);
             const uint64_t word = row_gather_nibbles(nib, lane);
+            // staged in LDS: one store instruction then writes the words of up to kPackWorkers
+            // workers (a store by 4 scattered lanes per worker costs the kernel 10 % of its time)
             if ((lane & 15) == 0)
-                p.packed[(int64_t)i * p.packed_stride + (t + r) * kWordsPerSub + (lane >> 4)] = word;
+                stage[(staged * kR + r) * kWordsPerSub + (lane >> 4)] = word;
+            if (r == kR - 1 && ++staged == kPackWorkers)
+                flush_packed(i + 1);
         }
     };
 
@@ -490,6 +516,8 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
     }
     c0 = c1;
     }
+    if (kPacked && staged > 0)
+        flush_packed(i_end);
 
 #pragma unroll
     for (int r = 0; r < kR; ++r) {
@@ -555,10 +583,13 @@ __global__ __launch_bounds__(kBlock) void step_kernel(Addr addr, Hyper h)
     if (tile >= addr.total_tiles)
         return;
     const int lane = threadIdx.x & 63;
+    // dynamic LDS: reserved to cap the resident waves; its first 512 bytes per wave stage packed words
+    extern __shared__ uint64_t step_lds[];
+    uint64_t *stage = step_lds + (threadIdx.x >> 6) * kLanes;
     Problem p;
     const int64_t t = addr.resolve(tile, p) * kSubs;      // first sub-tile of this wave
     if ((t + kSubs) * kSubTile <= p.numel) {
-        step_subtiles_vector<GT, kUnroll, kSubs, kApply, kPacked, kCounts>(p, t, lane, h);
+        step_subtiles_vector<GT, kUnroll, kSubs, kApply, kPacked, kCounts>(p, t, lane, h, stage);
         return;
     }
     // ragged end of a tensor
@@ -568,7 +599,7 @@ __global__ __launch_bounds__(kBlock) void step_kernel(Addr addr, Hyper h)
         if (sub * kSubTile >= p.numel)
             break;
         if (kSubs > 1 && (sub + 1) * kSubTile <= p.numel)
-            step_subtiles_vector<GT, kUnroll, 1, kApply, kPacked, kCounts>(p, sub, lane, h);
+            step_subtiles_vector<GT, kUnroll, 1, kApply, kPacked, kCounts>(p, sub, lane, h, stage);
         else
             step_subtile_guarded<GT, kApply, kPacked, kCounts>(p, sub, lane, h);
     }
