@@ -276,22 +276,33 @@ dlion_status launch_sliced_shape(const FlatAddr &addr, const Hyper &h, bool appl
 constexpr int kSlicedWaves = 8;
 constexpr int kSliced16MinWorkers = 128;
 
-// Flat buffers always take the bit-sliced kernel: with 8-wave workgroups and 128-bit streaming
-// count stores it beats the per-nibble kernel at every N (d = 350 M, counts only, N = 2 / 8 / 16:
-// 0.150 / 0.188 / 0.245 ms against 0.391 / 0.313 / 0.433 ms; with the weight update fused
-// 0.471 / 0.520 / 0.592 against 0.540 / 0.580 / 0.697 ms).  The per-nibble kernel serves the
-// tensor lists' fused aggregate + update, whose x lives in separate tensors.
-inline bool use_sliced(int32_t N)
+// Flat buffers take the bit-sliced kernel: with 128-bit streaming count stores it beats the
+// per-nibble kernel at every N (d = 350 M, counts only, N = 2 / 8 / 16: 0.150 / 0.188 / 0.245 ms
+// against 0.391 / 0.313 / 0.433 ms; with the weight update fused 0.471 / 0.520 / 0.592 against
+// 0.540 / 0.580 / 0.697 ms).  The exception is the fused update at small d: a bit-sliced wave owns
+// 8192 coordinates and walks their x in 32 dependent steps, which few waves cannot hide (d = 4 M,
+// N = 8: 21 us against 8 us; d = 16 M: 33 against 27 us; d = 64 M, N = 4: 95 against 120 us).  The
+// per-nibble kernel also serves the tensor lists' fused aggregate + update, whose x lives in
+// separate tensors.
+constexpr int64_t kSlicedMinGroups = 4096;     // groups of 128 words: 33.5 M coordinates
+
+inline int64_t sliced_groups(int64_t numel) { return (words_for(numel) + kSlicedWords - 1) / kSlicedWords; }
+
+inline bool use_sliced(int32_t N, int64_t numel, bool apply)
 {
     const int env_min = env_int("DLION_SLICED_MIN_WORKERS");      // tuning: per-nibble kernel below this N
-    return N >= (env_min >= 0 ? env_min : 1);
+    if (env_min >= 0)
+        return N >= env_min;
+    return !apply || sliced_groups(numel) >= kSlicedMinGroups;
 }
 
 template <int kPlanes, bool kAllow16>
 dlion_status launch_sliced_planes(const FlatAddr &addr, const Hyper &h, bool apply, bool counts, hipStream_t s)
 {
     const int env_waves = env_int("DLION_SLICED_WAVES");   // tuning: 1, 8 or 16
-    const int waves = env_waves > 0 ? env_waves : (h.N >= kSliced16MinWorkers ? 16 : kSlicedWaves);
+    // few groups: one-wave workgroups spread them over more compute units (d = 4 M, N = 32: 7.6 against 12.1 us)
+    const bool small = sliced_groups(addr.p.numel) < kSlicedMinGroups;
+    const int waves = env_waves > 0 ? env_waves : (small ? 1 : (h.N >= kSliced16MinWorkers ? 16 : kSlicedWaves));
     if (waves >= 16 && kAllow16)
         return launch_sliced_shape<kPlanes, kAllow16 ? 16 : 8>(addr, h, apply, counts, s);
     if (waves >= 8)
@@ -344,7 +355,7 @@ template <int kPlanes>
 dlion_status launch_encode_planes(const FlatAddr &addr, const Hyper &h, const DeltaOut &out, hipStream_t s)
 {
     const int env_waves = env_int("DLION_SLICED_WAVES");
-    const int waves = env_waves > 0 ? env_waves : kSlicedWaves;
+    const int waves = env_waves > 0 ? env_waves : (sliced_groups(addr.p.numel) < kSlicedMinGroups ? 1 : kSlicedWaves);
     if (waves >= 8)
         return launch_encode_shape<kPlanes, 8>(addr, h, out, s);
     return launch_encode_shape<kPlanes, 1>(addr, h, out, s);
@@ -519,7 +530,7 @@ dlion_status dlion_aggregate(const uint64_t *packed, int64_t packed_stride, int6
     h.stream_counts = counts_exceed_cache(d);
     const FlatAddr a = flat_addr(nullptr, nullptr, 0, nullptr, 0, d, const_cast<uint64_t *>(packed),
                                  packed_stride, counts);
-    if (use_sliced(N))
+    if (use_sliced(N, d, false))
         return launch_sliced(a, h, false, true, static_cast<hipStream_t>(stream));
     return launch_aggregate(a, h, false, true, static_cast<hipStream_t>(stream));
 }
@@ -551,7 +562,7 @@ dlion_status dlion_aggregate_apply(float *x, const uint64_t *packed, int64_t pac
     h.stream_counts = counts_or_null ? counts_exceed_cache(d) : 0;
     const FlatAddr a = flat_addr(x, nullptr, 0, nullptr, 0, d, const_cast<uint64_t *>(packed), packed_stride,
                                  counts_or_null);
-    if (use_sliced(N))
+    if (use_sliced(N, d, true))
         return launch_sliced(a, h, true, counts_or_null != nullptr, static_cast<hipStream_t>(stream));
     return launch_aggregate(a, h, true, counts_or_null != nullptr, static_cast<hipStream_t>(stream));
 }
@@ -630,7 +641,7 @@ dlion_status dlion_aggregate_mt(const dlion_seg *segs_host, const dlion_seg *seg
         return DLION_EALIGN;
     Hyper h = make_hyper(N, DLION_VOTE, 0.0f, 0.0f, 0.0f, 0.0f);
     h.stream_counts = counts_exceed_cache(64 * words);
-    if (use_sliced(N)) {
+    if (use_sliced(N, 64 * words, false)) {
         // packed words and counts of a tensor list are laid out by word, the padding bits of every
         // tensor's last word are zero: counting is the flat problem over 64 * words coordinates
         const FlatAddr f = flat_addr(nullptr, nullptr, 0, nullptr, 0, 64 * words, const_cast<uint64_t *>(packed),

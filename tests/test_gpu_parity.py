@@ -292,8 +292,13 @@ def test_tiny_config_full_run():
         print("tiny: bit-identical fp32 state:", exact, flush=True)
 
 
-def test_many_worker_aggregate_matches_oracle():
-    """The bit-sliced server-side kernel (many workers): counts bit-exact, apply within the bar."""
+@pytest.mark.parametrize("waves", [1, 8, 16])
+def test_many_worker_aggregate_matches_oracle(waves, monkeypatch):
+    """The bit-sliced server-side kernel: counts bit-exact, apply within the bar.  At these sizes the
+    library would pick one-wave workgroups (and the per-nibble kernel for the fused update), so the
+    bit-sliced kernel and its workgroup size are forced."""
+    monkeypatch.setenv("DLION_SLICED_MIN_WORKERS", "1")
+    monkeypatch.setenv("DLION_SLICED_WAVES", str(waves))
     rng = np.random.default_rng(2024)
     cases = [(1, 300), (2, 8192), (3, 8193), (7, 70_001), (8, 129), (15, 5000),
              (16, 4096), (17, 4097), (31, 1), (32, 63), (33, 10_000), (64, 8192 + 5), (127, 4095),
