@@ -152,3 +152,33 @@ def test_wider_rows_validation(lib):
     assert gl(A, A, 100, A, 128, 0, 128, 4, 0.9, 0.99, 1e-4, 0.1, None, None) == EINVAL
     assert gl(A, A, 128, A, 128, 3, 128, 4, 0.9, 0.99, 1e-4, 0.1, None, None) == EINVAL
     assert gl(A, A, 128, A, 128, 0, 128, 4, 0.9, 0.99, 1e-4, 0.1, A + 4, None) == EALIGN
+
+
+def test_product_and_oracle_do_not_import_each_other():
+    """The HIP path and the oracle share no code: neither package imports the other, and the C
+    sources include nothing of each other's."""
+    import ast
+    import glob
+
+    def imported(path):
+        with open(path) as f:
+            tree = ast.parse(f.read())
+        names = set()
+        for node in ast.walk(tree):
+            if isinstance(node, ast.Import):
+                names.update(a.name.split(".")[0] for a in node.names)
+            elif isinstance(node, ast.ImportFrom) and node.module and node.level == 0:
+                names.add(node.module.split(".")[0])
+        return names
+
+    for path in glob.glob(os.path.join(ROOT, "paper_2404_00438_amd", "*.py")):
+        assert "oracle" not in imported(path), path
+    for path in glob.glob(os.path.join(ROOT, "oracle", "*.py")):
+        assert "paper_2404_00438_amd" not in imported(path), path
+    for path in glob.glob(os.path.join(ROOT, "paper_2404_00438_amd", "csrc", "*")):
+        with open(path) as f:
+            assert "oracle" not in f.read().lower(), path
+    with open(os.path.join(ROOT, "oracle", "dlion_oracle.c")) as f:
+        text = f.read()
+    includes = [line for line in text.splitlines() if line.lstrip().startswith("#include")]
+    assert includes and all("dlion" not in line and "hip" not in line for line in includes), includes
