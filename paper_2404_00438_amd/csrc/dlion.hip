@@ -355,7 +355,12 @@ template <int kPlanes>
 dlion_status launch_encode_planes(const FlatAddr &addr, const Hyper &h, const DeltaOut &out, hipStream_t s)
 {
     const int env_waves = env_int("DLION_SLICED_WAVES");
-    const int waves = env_waves > 0 ? env_waves : (sliced_groups(addr.p.numel) < kSlicedMinGroups ? 1 : kSlicedWaves);
+    // 16 waves from N = 64 on (N = 256, d = 1 G: vote 5.15 -> 5.03 ms, average 6.00 -> 5.49 ms; N = 64:
+    // 1.48 -> 1.44 and 1.69 -> 1.60 ms; at N = 32 and below 8 waves are the better size)
+    const int waves = env_waves > 0 ? env_waves
+                      : (sliced_groups(addr.p.numel) < kSlicedMinGroups ? 1 : (h.N >= 64 ? 16 : kSlicedWaves));
+    if (waves >= 16 && kPlanes <= 9)
+        return launch_encode_shape<kPlanes, kPlanes <= 9 ? 16 : 8>(addr, h, out, s);
     if (waves >= 8)
         return launch_encode_shape<kPlanes, 8>(addr, h, out, s);
     return launch_encode_shape<kPlanes, 1>(addr, h, out, s);

@@ -23,7 +23,7 @@ def random_words(rng, N, d, p_one):
     return np.packbits(bits, axis=1, bitorder="little").view("<u8")
 
 
-@pytest.mark.parametrize("waves", [1, 8])
+@pytest.mark.parametrize("waves", [1, 8, 16])
 def test_down_link_planes_match_oracle(waves, monkeypatch):
     monkeypatch.setenv("DLION_SLICED_WAVES", str(waves))     # workgroup size of the encoder, forced
     rng = np.random.default_rng(77)
