@@ -117,8 +117,10 @@ def main() -> int:
     bytes_per_launch = algorithmic_bytes_per_step(w.d, w.N, g_bytes)
     x = m = g = None
     # From 16 workers on the library runs the step as consecutive launches over 8 workers each when
-    # it is given a counts array to carry the votes in; the counts then are an output of the step.
-    with_counts = w.N >= 16
+    # it has somewhere to carry the votes: a workspace (flat buffers), else a counts array (tensor
+    # lists), which then is an output of the step.
+    ws_bytes = dl.dlion_step_workspace_bytes(w.d, w.N) if w.shapes is None else 0
+    with_counts = w.N >= 16 and w.shapes is not None
     if w.g_dist == "packed_bernoulli":
         # vote-only pass: N pre-packed sign streams in, counts out
         W = dl.words_for(w.d)
@@ -145,15 +147,20 @@ def main() -> int:
         x = wl.init_x(w, dev)
         m = wl.init_m(w, dev)
         g = wl.make_grads(w, 0, dev)
-        counts = torch.empty(w.d, dtype=torch.int16, device=dev) if with_counts else None
+        workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
 
         def step():
-            dl.dlion_step(x, m, g, w.mode, w.beta1, w.beta2, w.lr, w.lam, counts=counts)
-    if with_counts and w.g_dist != "packed_bernoulli":
-        kernel += ", counts output; launches over 8 workers each, 33.5 M coordinates at a time)"
-        bytes_per_launch += 2 * w.d                  # the counts the step hands back
-    else:
-        kernel += ", no packed/counts output)" if w.g_dist != "packed_bernoulli" else ""
+            dl.dlion_step_ws(x, m, g, w.mode, w.beta1, w.beta2, w.lr, w.lam, workspace)
+    if w.g_dist != "packed_bernoulli":
+        if with_counts:
+            kernel += ", counts output; launches over 8 workers each, 33.5 M coordinates at a time)"
+            bytes_per_launch += 2 * w.d              # the counts the step hands back
+        elif ws_bytes:
+            kernel = kernel.replace("dlion_step ", "dlion_step_ws ")
+            kernel += (f", no packed/counts output; launches over 8 workers each, 33.5 M coordinates at a time, "
+                       f"votes carried in a {ws_bytes >> 20} MiB workspace)")
+        else:
+            kernel += ", no packed/counts output)"
     torch.cuda.synchronize()
 
     for _ in range(args.warmup):

@@ -116,13 +116,37 @@ dlion_status dlion_aggregate_apply(float *x, const uint64_t *packed, int64_t pac
  * With 16 or more workers and d beyond ~16 M a counts array also makes the call
  * faster: the step is then enqueued as consecutive launches over 8 workers each
  * that carry the votes in counts (same results; counts holds partial sums until
- * the last launch has run).  Without it the step stays one launch: the library
- * owns no memory.  The same holds for the _mt and _pw variants.
+ * the last launch has run).  Without it the step stays one launch (the library
+ * owns no memory) unless dlion_step_ws is given a workspace.  The same holds for
+ * the _mt and _pw variants, which have no workspace form.
  */
 dlion_status dlion_step(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
                         dlion_dtype g_dtype, int64_t d, int32_t N, dlion_mode mode, float beta1,
                         float beta2, float lr, float lambda, uint64_t *packed_or_null,
                         int64_t packed_stride, uint16_t *counts_or_null, void *stream);
+
+/*
+ * dlion_step with a caller-owned workspace (Algorithm 1, the same iteration): same
+ * arguments, same results bit for bit.  With 16 or more workers and no counts array
+ * the launches over 8 workers each carry the votes in the workspace instead, 33.5 M
+ * coordinates at a time.
+ *   workspace_or_null  device memory, 16-byte aligned, at least workspace_bytes long;
+ *                      scratch: its contents before and after the call mean nothing.
+ *                      Calls that share a workspace must be ordered (same stream).
+ *   workspace_bytes    dlion_step_workspace_bytes(d, N) gives the full benefit; less is
+ *                      accepted (smaller blocks), below 16 MB it is ignored and the
+ *                      step runs as one launch, as it does with NULL / 0.
+ * dlion_step_workspace_bytes returns 0 when no workspace would be used (N < 16, small d).
+ * Errors: as dlion_step; DLION_EINVAL for a negative size or a size without a pointer,
+ * DLION_EALIGN for a workspace that is not 16-byte aligned.
+ */
+dlion_status dlion_step_ws(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
+                           dlion_dtype g_dtype, int64_t d, int32_t N, dlion_mode mode, float beta1,
+                           float beta2, float lr, float lambda, uint64_t *packed_or_null,
+                           int64_t packed_stride, uint16_t *counts_or_null,
+                           void *workspace_or_null, int64_t workspace_bytes, void *stream);
+
+int64_t dlion_step_workspace_bytes(int64_t d, int32_t N);
 
 /* ------------------------------------------------------------------------- *
  * Multi-tensor form: the model is a list of K tensors instead of one flat

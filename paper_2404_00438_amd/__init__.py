@@ -25,6 +25,8 @@ from .binding import (  # noqa: F401
     dlion_apply_mt,
     dlion_step,
     dlion_step_mt,
+    dlion_step_workspace_bytes,
+    dlion_step_ws,
     dlion_version,
     dlion_worker_step,
     dlion_worker_step_mt,

@@ -28,7 +28,7 @@ EXPORTS = (
     "dlion_mt_layout", "dlion_worker_step_mt", "dlion_aggregate_mt", "dlion_apply_mt",
     "dlion_aggregate_apply_mt", "dlion_step_mt", "dlion_status_str", "dlion_version",
     "dlion_delta_planes", "dlion_aggregate_encode", "dlion_apply_encoded", "dlion_worker_step_pw",
-    "dlion_step_pw", "dlion_global_lion_step",
+    "dlion_step_pw", "dlion_global_lion_step", "dlion_step_ws", "dlion_step_workspace_bytes",
 )
 
 
@@ -67,6 +67,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "dlion_apply": [vp, vp, i64, i32, ci, f32, f32, vp],
         "dlion_aggregate_apply": [vp, vp, i64, i64, i32, ci, f32, f32, vp, vp],
         "dlion_step": [vp, vp, i64, vp, i64, ci, i64, i32, ci, f32, f32, f32, f32, vp, i64, vp, vp],
+        "dlion_step_ws": [vp, vp, i64, vp, i64, ci, i64, i32, ci, f32, f32, f32, f32, vp, i64, vp, vp, i64, vp],
         "dlion_mt_layout": [segp, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)],
         "dlion_worker_step_mt": [segp, vp, i32, ci, vp, i64, i32, f32, f32, vp],
         "dlion_aggregate_mt": [segp, vp, i32, vp, i64, i32, vp, vp],
@@ -88,6 +89,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.dlion_status_str.restype = ctypes.c_char_p
     lib.dlion_version.argtypes = []
     lib.dlion_version.restype = ci
+    lib.dlion_step_workspace_bytes.argtypes = [i64, i32]
+    lib.dlion_step_workspace_bytes.restype = i64
     _lib = lib                      # every later call goes to the library loaded last
     return lib
 
@@ -182,7 +185,7 @@ def dlion_aggregate_apply(x, packed, mode, lr, lam, counts=None, stream=None):
            "dlion_aggregate_apply")
 
 
-def dlion_step(x, m, g, mode, beta1, beta2, lr, lam, packed=None, counts=None, stream=None):
+def _step_args(x, m, g, packed, counts):
     xp = _flat(x, "x", torch.float32)
     mp, ms, N, d = _rows(m, "m")
     gp, gs, Ng, dg = _rows(g, "g")
@@ -194,8 +197,30 @@ def dlion_step(x, m, g, mode, beta1, beta2, lr, lam, packed=None, counts=None, s
         if Np != N:
             raise ValueError("packed must have N rows")
     cp = _as_u16(counts, "counts").data_ptr() if counts is not None else None
-    _check(load_library().dlion_step(xp, mp, ms, gp, gs, _gdtype(g), d, N, mode, beta1, beta2, lr, lam,
+    return xp, mp, ms, gp, gs, _gdtype(g), d, N, pp, ps, cp
+
+
+def dlion_step(x, m, g, mode, beta1, beta2, lr, lam, packed=None, counts=None, stream=None):
+    xp, mp, ms, gp, gs, gt, d, N, pp, ps, cp = _step_args(x, m, g, packed, counts)
+    _check(load_library().dlion_step(xp, mp, ms, gp, gs, gt, d, N, mode, beta1, beta2, lr, lam,
                                      pp, ps, cp, _stream(stream)), "dlion_step")
+
+
+def dlion_step_ws(x, m, g, mode, beta1, beta2, lr, lam, workspace, packed=None, counts=None, stream=None):
+    """``dlion_step`` with a caller-owned scratch tensor (any dtype; its size in bytes is what counts)."""
+    xp, mp, ms, gp, gs, gt, d, N, pp, ps, cp = _step_args(x, m, g, packed, counts)
+    wp, wb = (None, 0)
+    if workspace is not None:
+        if not workspace.is_cuda or not workspace.is_contiguous():
+            raise ValueError("workspace must be a contiguous device tensor")
+        wp, wb = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    _check(load_library().dlion_step_ws(xp, mp, ms, gp, gs, gt, d, N, mode, beta1, beta2, lr, lam,
+                                        pp, ps, cp, wp, wb, _stream(stream)), "dlion_step_ws")
+
+
+def dlion_step_workspace_bytes(d: int, N: int) -> int:
+    """Size of the workspace that lets ``dlion_step(..., workspace=...)`` split a step over many workers."""
+    return int(load_library().dlion_step_workspace_bytes(d, N))
 
 
 class SegTable:

@@ -184,22 +184,45 @@ dlion_status launch_step_once(const Addr &addr, const Hyper &h, dlion_dtype g_dt
 // launch -> launches over 8 workers: d = 350 M, N = 32: 21.3 -> 19.7 ms; d = 85.6 M, N = 16:
 // 2.38 -> 2.28 ms; d = 100 M, N = 64: 12.2 -> 10.5 ms; worker step, d = 350 M, N = 32:
 // 24.0 -> 19.7 ms.  N = 12 gains nothing, and below ~16 M coordinates the extra launches cost
-// what they save.  The worker step needs no carry at all; the fused step needs the caller's
-// counts array as the accumulator and stays one launch without it (the library owns no memory).
+// what they save.  The worker step needs no carry at all; the fused step carries the votes in
+// the caller's counts array or, without one, in the caller's workspace (flat buffers only), and
+// stays one launch when it has neither: the library owns no memory.
 constexpr int kPassWorkers = 8;
 constexpr int kPassMinN = 16;
 constexpr int64_t kPassMinTiles = 8 * kResidentWaves;
 constexpr int64_t kPassTiles = 16 * kResidentWaves;      // 33.5 M coordinates
+constexpr int64_t kPassMinBlockTiles = 4 * kResidentWaves;   // a workspace below 16 MB is not used
+
+// Where the votes wait between the launches of one block of tiles.
+struct Workspace {
+    uint16_t *base = nullptr;
+    int64_t coords = 0;          // capacity in coordinates
+};
+
+// Points the carry (and, for the launches that only hand the votes on, the counts output) of a
+// flat problem at the workspace, which holds the block of coordinates that starts at `origin`.
+inline void carry_in_workspace(FlatAddr &a, const Workspace &ws, int64_t origin, bool hand_on)
+{
+    uint16_t *shifted = reinterpret_cast<uint16_t *>(reinterpret_cast<uintptr_t>(ws.base) -
+                                                     static_cast<uintptr_t>(origin) * sizeof(uint16_t));
+    a.p.carry = shifted;
+    a.p.counts = hand_on ? shifted : nullptr;
+}
+inline void carry_in_workspace(SegAddr &, const Workspace &, int64_t, bool) {}   // tensor lists: counts only
+inline bool workspace_usable(const FlatAddr &, const Workspace &ws) { return ws.base && ws.coords >= kPassMinBlockTiles * kTile; }
+inline bool workspace_usable(const SegAddr &, const Workspace &) { return false; }
 
 template <bool kApply, class Addr>
 dlion_status launch_step(const Addr &addr, const Hyper &h0, dlion_dtype g_dtype, bool packed, bool counts,
-                         hipStream_t s)
+                         hipStream_t s, const Workspace &ws = Workspace())
 {
     const int N = h0.N;
     int per = env_int("DLION_PASS_WORKERS");             // tuning: 0 = always one launch
     if (per < 0)
         per = (N >= kPassMinN && addr.total_tiles >= kPassMinTiles) ? kPassWorkers : 0;
-    if (kApply && !counts)
+    // the fused step needs somewhere to carry the votes: the counts output, else the workspace
+    const bool in_ws = kApply && !counts && workspace_usable(addr, ws);
+    if (kApply && !counts && !in_ws)
         per = 0;
     if (per <= 0 || per >= N)
         return launch_step_once<kApply, Addr>(addr, h0, g_dtype, packed, counts, s);
@@ -210,8 +233,10 @@ dlion_status launch_step(const Addr &addr, const Hyper &h0, dlion_dtype g_dtype,
     int64_t block = env_int("DLION_PASS_TILES");          // tuning: 0 = all tiles in one block
     if (block < 0)
         block = kPassTiles;
-    if (!counts || block == 0)
+    if ((!counts && !in_ws) || block == 0)
         block = addr.total_tiles;
+    if (in_ws && block > ws.coords / kTile)
+        block = ws.coords / kTile;
     Hyper h = h0;
     Addr a = addr;
     for (int64_t first = 0; first < addr.total_tiles; first += block) {
@@ -221,15 +246,20 @@ dlion_status launch_step(const Addr &addr, const Hyper &h0, dlion_dtype g_dtype,
             // spread evenly: N = 30 runs as 8, 8, 7, 7
             h.worker_begin = static_cast<int32_t>((int64_t)N * pass / passes);
             h.worker_end = static_cast<int32_t>((int64_t)N * (pass + 1) / passes);
-            h.counts_in = (counts && pass > 0) ? 1 : 0;
+            h.counts_in = ((counts || in_ws) && pass > 0) ? 1 : 0;
             const bool last = pass == passes - 1;
             // the carry is read again right away: keep it cached; the result follows the caller's hint
             h.stream_counts = (last || block == addr.total_tiles) ? h0.stream_counts : 0;
+            if (in_ws) {
+                carry_in_workspace(a, ws, first * kTile, !last);
+                h.stream_counts = 0;
+            }
+            const bool counts_out = in_ws ? !last : counts;
             dlion_status st;
             if (kApply && last)
-                st = launch_step_once<true, Addr>(a, h, g_dtype, packed, counts, s);
+                st = launch_step_once<true, Addr>(a, h, g_dtype, packed, counts_out, s);
             else
-                st = launch_step_once<false, Addr>(a, h, g_dtype, packed, counts, s);
+                st = launch_step_once<false, Addr>(a, h, g_dtype, packed, counts_out, s);
             if (st != DLION_OK)
                 return st;
         }
@@ -437,6 +467,7 @@ FlatAddr flat_addr(float *x, float *m, int64_t m_stride, const void *g, int64_t 
     a.p.packed = packed;
     a.p.packed_stride = packed_stride;
     a.p.counts = counts;
+    a.p.carry = counts;
     a.p.counts_end = d;
     a.total_tiles = tiles_for(d);
     a.first_tile = 0;
@@ -572,15 +603,35 @@ dlion_status dlion_aggregate_apply(float *x, const uint64_t *packed, int64_t pac
     return launch_aggregate(a, h, true, counts_or_null != nullptr, static_cast<hipStream_t>(stream));
 }
 
+int64_t dlion_step_workspace_bytes(int64_t d, int32_t N)
+{
+    if (d <= 0 || N < kPassMinN || tiles_for(d) < kPassMinTiles)
+        return 0;
+    const int64_t tiles = tiles_for(d) < kPassTiles ? tiles_for(d) : kPassTiles;
+    return tiles * kTile * static_cast<int64_t>(sizeof(uint16_t));
+}
+
 dlion_status dlion_step(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
                         dlion_dtype g_dtype, int64_t d, int32_t N, dlion_mode mode, float beta1, float beta2,
                         float lr, float lambda, uint64_t *packed_or_null, int64_t packed_stride,
                         uint16_t *counts_or_null, void *stream)
 {
+    return dlion_step_ws(x, m, m_stride, g, g_stride, g_dtype, d, N, mode, beta1, beta2, lr, lambda, packed_or_null,
+                         packed_stride, counts_or_null, nullptr, 0, stream);
+}
+
+dlion_status dlion_step_ws(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
+                           dlion_dtype g_dtype, int64_t d, int32_t N, dlion_mode mode, float beta1, float beta2,
+                           float lr, float lambda, uint64_t *packed_or_null, int64_t packed_stride,
+                           uint16_t *counts_or_null, void *workspace_or_null, int64_t workspace_bytes,
+                           void *stream)
+{
     DLION_TRY(check_common(d, N));
     if (!dtype_ok(g_dtype) || !mode_ok(mode) || !x)
         return DLION_EINVAL;
-    if (!aligned_to(x, 4) || !aligned_to(counts_or_null, 2))
+    if (workspace_bytes < 0 || (workspace_or_null == nullptr && workspace_bytes != 0))
+        return DLION_EINVAL;
+    if (!aligned_to(x, 4) || !aligned_to(counts_or_null, 2) || !aligned_to(workspace_or_null, 16))
         return DLION_EALIGN;
     DLION_TRY(check_rows(m, m_stride, d, N, 4));
     DLION_TRY(check_rows(g, g_stride, d, N, grad_size(g_dtype)));
@@ -590,8 +641,11 @@ dlion_status dlion_step(float *x, float *m, int64_t m_stride, const void *g, int
     h.stream_counts = counts_or_null ? counts_exceed_cache(d) : 0;
     h.xcd_quads = step_quads(rows_split_lines(m, m_stride, 4, N) || rows_split_lines(g, g_stride, grad_size(g_dtype), N));
     const FlatAddr a = flat_addr(x, m, m_stride, g, g_stride, d, packed_or_null, packed_stride, counts_or_null);
+    Workspace ws;
+    ws.base = static_cast<uint16_t *>(workspace_or_null);
+    ws.coords = workspace_bytes / static_cast<int64_t>(sizeof(uint16_t));
     return launch_step<true>(a, h, g_dtype, packed_or_null != nullptr, counts_or_null != nullptr,
-                             static_cast<hipStream_t>(stream));
+                             static_cast<hipStream_t>(stream), ws);
 }
 
 // ----------------------------------------------------------------------- tensor lists

@@ -92,6 +92,8 @@ struct Problem {
     uint64_t *packed;       // worker 0, first word of this tensor (may be null)
     int64_t packed_stride;
     uint16_t *counts;       // first count of this tensor (may be null)
+    const uint16_t *carry;  // counts_in: the votes left by the launches over the earlier workers, indexed
+                            // like counts (the counts array itself, or a workspace)
     int64_t counts_end;     // counts[0..counts_end) may be written: numel (flat buffer) or
                             // numel rounded up to a whole word (tensor list)
 };
@@ -140,6 +142,7 @@ struct SegAddr {
         out.packed = packed ? packed + s.word_begin : nullptr;
         out.packed_stride = packed_stride;
         out.counts = counts ? counts + 64 * s.word_begin : nullptr;
+        out.carry = out.counts;
         out.counts_end = ((s.numel + 63) >> 6) << 6;
         return tile - s.tile_begin;
     }
@@ -425,7 +428,7 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
     for (int r = 0; r < kR; ++r) {
         cnt[r][0] = cnt[r][1] = cnt[r][2] = cnt[r][3] = 0;
         if (h.counts_in) {                              // uniform
-            const u16x4 c = counts_load4(p.counts + j0 + r * kSubTile);
+            const u16x4 c = counts_load4(p.carry + j0 + r * kSubTile);
             cnt[r][0] = c.x;
             cnt[r][1] = c.y;
             cnt[r][2] = c.z;
@@ -552,7 +555,7 @@ __device__ __forceinline__ void step_subtile_guarded(const Problem &p, int64_t t
             break;                                   // uniform: whole wave leaves together
         const int64_t j = w * 64 + lane;
         const bool valid = j < p.numel;
-        uint32_t cnt = (h.counts_in && valid) ? p.counts[j] : 0u;
+        uint32_t cnt = (h.counts_in && valid) ? p.carry[j] : 0u;
         for (int i = h.worker_begin; i < h.worker_end; ++i) {
             bool plus = false;
             if (valid) {

@@ -182,3 +182,18 @@ def test_product_and_oracle_do_not_import_each_other():
         text = f.read()
     includes = [line for line in text.splitlines() if line.lstrip().startswith("#include")]
     assert includes and all("dlion" not in line and "hip" not in line for line in includes), includes
+
+
+def test_workspace_entry_point_validation(lib):
+    """dlion_step_ws rejects a bad workspace before anything is launched; the size helper is host-only."""
+    EINVAL, EALIGN = 1, 2
+
+    def call(ws, nbytes):
+        return lib.dlion_step_ws(A, A, 1024, A, 1024, 0, 1024, 4, 0, 0.9, 0.99, 1e-3, 0.1, None, 0, None, ws, nbytes, None)
+
+    assert call(A, -1) == EINVAL              # negative size
+    assert call(None, 4096) == EINVAL         # a size without a pointer
+    assert call(A + 8, 4096) == EALIGN        # workspace not 16-byte aligned
+    assert lib.dlion_step_workspace_bytes(1000, 4) == 0
+    assert lib.dlion_step_workspace_bytes(-5, 32) == 0
+    assert lib.dlion_step_workspace_bytes(350_000_000, 32) == 131072 * 256 * 2

@@ -77,6 +77,8 @@ def run_flat_workload(w: wl.Workload, n_chunks: int = 24, steps=None):
     xh, mh = to_np(gather(x, ranges)), to_np(gather(m, ranges))
     W = dl.words_for(d)
     exact = True
+    ws_bytes = dl.dlion_step_workspace_bytes(d, N)
+    workspace = torch.full((ws_bytes,), 0xA5, dtype=torch.uint8, device=DEV) if ws_bytes else None
     for t in range(steps):
         wl.make_grads(w, t, DEV, out=g)
         gh = to_np(gather(g, ranges))
@@ -87,6 +89,9 @@ def run_flat_workload(w: wl.Workload, n_chunks: int = 24, steps=None):
             packed = torch.empty((N, W), dtype=torch.int64, device=DEV)
             counts = torch.empty(d, dtype=torch.int16, device=DEV)
             dl.dlion_step(x, m, g, w.mode, w.beta1, w.beta2, w.lr, w.lam, packed=packed, counts=counts)
+        elif workspace is not None:
+            # exactly what bench.py launches for many workers: the votes carried in a workspace
+            dl.dlion_step_ws(x, m, g, w.mode, w.beta1, w.beta2, w.lr, w.lam, workspace)
         else:
             # exactly what bench.py launches
             dl.dlion_step(x, m, g, w.mode, w.beta1, w.beta2, w.lr, w.lam)

@@ -492,6 +492,36 @@ def test_per_nibble_server_kernel_on_flat_buffers(monkeypatch):
             assert_f32_equal(to_np(x), xn, f"N={N} d={d} mode={mode}: x")
 
 
+@pytest.mark.parametrize("per,tiles", [(3, 3), (8, 0)])
+def test_step_with_votes_carried_in_a_workspace(per, tiles, monkeypatch):
+    """dlion_step_ws without a counts array: the launches over a few workers hand the votes on
+    through the caller's workspace, block of tiles by block of tiles (forced at small sizes)."""
+    monkeypatch.setenv("DLION_PASS_WORKERS", str(per))
+    monkeypatch.setenv("DLION_PASS_TILES", str(tiles))
+    rng = np.random.default_rng(99 + per)
+    workspace = torch.full((16 << 20,), 0x5A, dtype=torch.uint8, device=DEV)       # the smallest size that is used
+    small = torch.zeros(1 << 20, dtype=torch.uint8, device=DEV)                    # too small: one launch
+    for (d, N), mode, g_dtype in itertools.product(((1000, 4), (4099, 9), (70_001, 33), (700, 70)),
+                                                   (dl.VOTE, dl.AVG), (torch.float32, torch.bfloat16)):
+        announce("workspace carry", per, tiles, g_dtype, "d", d, "N", N, "mode", mode)
+        x, m, g = draw_state(rng, N, d, g_dtype, d + 3, d + 3)
+        W = dl.words_for(d)
+        packed = strided_rows(N, W, W + 1, torch.int64, DEV)
+        counts = torch.full((d,), -1, dtype=torch.int16, device=DEV)
+        for step, (ws, want_packed, want_counts) in enumerate(((workspace, False, False), (workspace, True, False),
+                                                               (workspace, True, True), (small, False, False),
+                                                               (None, True, False))):
+            xn, mn, pn, cn = oracle_step(x, m, g, mode, HYP)
+            dl.dlion_step_ws(x, m, g, mode, HYP["beta1"], HYP["beta2"], HYP["lr"], HYP["lam"], ws,
+                             packed=packed if want_packed else None, counts=counts if want_counts else None)
+            torch.cuda.synchronize()
+            compare_all(f"d={d} N={N} step={step}", x, m, packed if want_packed else None,
+                        counts if want_counts else None, xn, mn, pn, cn)
+    assert dl.dlion_step_workspace_bytes(1000, 4) == 0 and dl.dlion_step_workspace_bytes(350_000_000, 8) == 0
+    assert dl.dlion_step_workspace_bytes(350_000_000, 32) == 131072 * 256 * 2
+    assert dl.dlion_step_workspace_bytes(20_000_000, 16) == 78125 * 256 * 2
+
+
 def test_randomized_shapes_strides_and_flags():
     """Seeded random sweep over d, N, row strides (aligned or not), gradient dtype, aggregation and
     optional outputs, two steps each, fused and unfused, against the oracle."""
