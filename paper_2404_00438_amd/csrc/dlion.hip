@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdlib>
+#include <type_traits>
 
 namespace {
 
@@ -76,8 +77,12 @@ inline dlion_status launched()
 
 // ------------------------------------------------------------------ launch shape
 // HBM delivers the most when the chip keeps only a modest, compact window of addresses in
-// flight: roughly 24 KB of outstanding loads per compute unit (a little less with many
-// workers).  A wave of the fused kernel has `unroll` workers' loads outstanding at once, so
+// flight: roughly 28 KB of outstanding loads per compute unit (a little less with many
+// workers in one launch): bf16 gradients, 3 KB per wave, 8 / 9 / 10 waves per compute unit give
+// 79.5 / 80.3 / 80.0 % of peak at N = 8; fp32 gradients, 4 KB per wave, 6 / 7 / 8 waves give
+// 79.4 / 79.9 / 78.2 %; 5 waves lose a quarter.  A tensor list takes one wave more: its waves
+// start with a table lookup during which they have nothing in flight (148 tensors, fp32,
+// N = 16: 7 waves 78.8 %, 8 waves 79.4 %).  A wave of the fused kernel has `unroll` workers' loads outstanding at once, so
 // the number of resident waves per compute unit is capped accordingly.  The cap is applied by
 // reserving (unused) dynamic LDS per workgroup: a compute unit has 160 KB, so a reservation
 // of 160 KB / k admits k workgroups.
@@ -121,7 +126,7 @@ LaunchShape step_shape(int32_t N, size_t bytes_per_worker_per_wave)
     if (env_blocks >= 0) {
         s.blocks_per_cu = env_blocks;
     } else {
-        const size_t target = (N >= kManyWorkers ? 18 : 24) * 1024;
+        const size_t target = (N >= kManyWorkers ? 18 : 28) * 1024;
         const size_t in_flight = bytes_per_worker_per_wave * static_cast<size_t>(s.unroll);
         int k = static_cast<int>((target + in_flight / 2) / in_flight);
         s.blocks_per_cu = k < 3 ? 3 : (k > 32 ? 0 : k);
@@ -156,8 +161,12 @@ dlion_status launch_step_unroll(const Addr &addr, const Hyper &h, bool packed, b
     // A problem whose waves all fit on the chip at once never reaches the steady state the cap
     // is tuned for; it is latency-bound and wants every wave resident (d = 1,000,003, N = 4:
     // 12.7 -> 10.4 us).
-    if (env_int("DLION_BLOCKS_PER_CU") < 0 && addr.total_tiles - addr.first_tile <= kResidentWaves)
-        shape.blocks_per_cu = 0;
+    if (env_int("DLION_BLOCKS_PER_CU") < 0) {
+        if (addr.total_tiles - addr.first_tile <= kResidentWaves)
+            shape.blocks_per_cu = 0;
+        else if (shape.blocks_per_cu > 0 && std::is_same<Addr, SegAddr>::value)
+            shape.blocks_per_cu += 1;
+    }
     const size_t lds = lds_reservation(shape.blocks_per_cu);
     switch (shape.unroll) {
     case 8: return launch_step_flags<GT, 8, kApply, Addr>(addr, h, packed, counts, lds, s);
