@@ -907,6 +907,6 @@ const char *dlion_status_str(dlion_status s)
     return "unknown status";
 }
 
-int dlion_version(void) { return 100; }
+int dlion_version(void) { return 101; }
 
 }  // extern "C"
