@@ -197,3 +197,13 @@ def test_workspace_entry_point_validation(lib):
     assert lib.dlion_step_workspace_bytes(1000, 4) == 0
     assert lib.dlion_step_workspace_bytes(-5, 32) == 0
     assert lib.dlion_step_workspace_bytes(350_000_000, 32) == 131072 * 256 * 2
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU and says so when asked for more (no GPU needed for that)."""
+    import subprocess
+    import sys
+
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode != 0
+    assert "one GPU" in res.stderr and res.stdout.strip() == ""
