@@ -12,8 +12,10 @@
  * Conventions shared by every entry point
  * ---------------------------------------
  * Memory.   Every pointer is a DEVICE pointer unless its comment says "host".
- *           The caller owns all memory; the library allocates nothing, keeps no
- *           state between calls and is re-entrant across streams.
+ *           The caller owns all memory; the library allocates nothing and keeps
+ *           no state between calls other than the launch-shape overrides of
+ *           dlion_set_tuning (by default: none); calls are re-entrant across
+ *           streams.
  * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default
  *           stream).  Calls only enqueue work and return; they never synchronise.
  * Types.    x and m are fp32.  g is fp32 or bf16 (`g_dtype`); bf16 is widened
@@ -40,9 +42,17 @@
  *           weight-decay term.
  * Average.  Delta = (float)S / (float)N, one correctly rounded fp32 division.
  * Errors.   Arguments are validated on the host before anything is enqueued;
- *           on error nothing is launched and a dlion_status other than DLION_OK
- *           comes back.  No call aborts or throws.  NaN/Inf inputs are not
- *           errors: they propagate through the arithmetic.
+ *           on DLION_EINVAL / DLION_EALIGN / DLION_EUNSUPPORTED nothing has been
+ *           launched.  DLION_ELAUNCH means the HIP runtime refused a launch (the
+ *           status is that launch call's own return value; an error left behind
+ *           by an earlier call of the thread is neither reported nor cleared).
+ *           A call that enqueues several launches (large d, many workers) may
+ *           already have enqueued some of them when a later one is refused:
+ *           m is then advanced for some workers / coordinates and not others,
+ *           counts, packed and the workspace hold partial results and x may be
+ *           updated for some blocks of coordinates only -- the state is not
+ *           usable and the step cannot be retried.  No call aborts or throws.
+ *           NaN/Inf inputs are not errors: they propagate through the arithmetic.
  * Alignment x, m, g must be aligned to their element size, packed to 8 bytes,
  *           counts to 2 bytes (DLION_EALIGN otherwise).
  * Aliasing. m and x are updated in place; g and packed inputs are read-only;
@@ -62,7 +72,7 @@ typedef enum dlion_status {
     DLION_OK = 0,
     DLION_EINVAL = 1,       /* a size, stride, count or enum is out of range, or a pointer is NULL */
     DLION_EALIGN = 2,       /* a pointer is not aligned to its element type */
-    DLION_ELAUNCH = 3,      /* the HIP runtime refused the launch (hipGetLastError != success) */
+    DLION_ELAUNCH = 3,      /* the HIP runtime refused a launch (hipLaunchKernel != hipSuccess) */
     DLION_EUNSUPPORTED = 4  /* valid request outside what this build implements */
 } dlion_status;
 
@@ -100,25 +110,28 @@ dlion_status dlion_apply(float *x, const uint16_t *counts, int64_t d, int32_t N,
                          float lr, float lambda, void *stream);
 
 /*
- * dlion_aggregate and dlion_apply in one pass over the packed streams: Delta
- * never leaves registers.  counts_or_null, if not NULL, also receives p_j.
+ * Server side and weight update in one pass over the packed streams (Section 3.2,
+ * definition of S_t, second and third displays; Algorithm 1, server-side lines and
+ * the x update): dlion_aggregate followed by dlion_apply, except that Delta never
+ * leaves registers.  counts_or_null, if not NULL, also receives p_j.
+ *   x [d] fp32, in/out        packed [N rows of W] uint64, in
  */
 dlion_status dlion_aggregate_apply(float *x, const uint64_t *packed, int64_t packed_stride,
                                    int64_t d, int32_t N, dlion_mode mode, float lr, float lambda,
                                    uint16_t *counts_or_null, void *stream);
 
 /*
- * The whole iteration (Algorithm 1, one pass of the loop body) in one kernel:
- * worker step for all N workers, vote count, aggregation and weight update.
- * Per coordinate it moves m in, m out and g in for each worker and x in and out
+ * The whole iteration (Algorithm 1, one pass of the loop body; Section 3.2, all three
+ * displays): worker step for all N workers, vote count, aggregation and weight update,
+ * fused.  Per coordinate it moves m in, m out and g in for each worker and x in and out
  * once.  packed_or_null / counts_or_null, if not NULL, also receive the packed
  * updates and the counts exactly as the unfused calls would write them.
- * With 16 or more workers and d beyond ~16 M a counts array also makes the call
- * faster: the step is then enqueued as consecutive launches over 8 workers each
- * that carry the votes in counts (same results; counts holds partial sums until
- * the last launch has run).  Without it the step stays one launch (the library
- * owns no memory) unless dlion_step_ws is given a workspace.  The same holds for
- * the _mt and _pw variants, which have no workspace form.
+ * Large problems are enqueued as several launches of the same kernel, 67 M coordinates
+ * at a time.  With 16 or more workers and d beyond ~16 M the step is faster when each
+ * such block is also cut into launches over 8 workers each that hand the votes on (same
+ * results bit for bit): in the workspace of dlion_step_ws, else in the counts array
+ * (which then holds partial sums until the last launch of a block has run); with
+ * neither, each block stays one launch: the library owns no memory.
  */
 dlion_status dlion_step(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
                         dlion_dtype g_dtype, int64_t d, int32_t N, dlion_mode mode, float beta1,
@@ -127,15 +140,16 @@ dlion_status dlion_step(float *x, float *m, int64_t m_stride, const void *g, int
 
 /*
  * dlion_step with a caller-owned workspace (Algorithm 1, the same iteration): same
- * arguments, same results bit for bit.  With 16 or more workers and no counts array
- * the launches over 8 workers each carry the votes in the workspace instead, 33.5 M
- * coordinates at a time.
+ * arguments, same results bit for bit.  With 16 or more workers the launches over 8
+ * workers each hand the votes on in the workspace (half a byte per coordinate and
+ * launch for up to 64 workers, 2 + 2 bytes beyond), a block of coordinates at a time.
  *   workspace_or_null  device memory, 16-byte aligned, at least workspace_bytes long;
  *                      scratch: its contents before and after the call mean nothing.
  *                      Calls that share a workspace must be ordered (same stream).
  *   workspace_bytes    dlion_step_workspace_bytes(d, N) gives the full benefit; less is
- *                      accepted (smaller blocks), below 16 MB it is ignored and the
- *                      step runs as one launch, as it does with NULL / 0.
+ *                      accepted (smaller blocks), and when it holds fewer than 32768
+ *                      tiles of 256 coordinates it is ignored: the step then runs as
+ *                      it does with NULL / 0.
  * dlion_step_workspace_bytes returns 0 when no workspace would be used (N < 16, small d).
  * Errors: as dlion_step; DLION_EINVAL for a negative size or a size without a pointer,
  * DLION_EALIGN for a workspace that is not 16-byte aligned.
@@ -169,38 +183,71 @@ typedef struct dlion_seg {
 } dlion_seg;
 
 /*
- * Host-only helper: fills word_begin / tile_begin of segs_host[0..K) (a HOST
- * array) and returns the total words per worker row and the total tile count.
- * The caller then copies the table to device memory (K*sizeof(dlion_seg)
- * bytes, 8-byte aligned) and passes both copies to the _mt calls: the host
- * copy is what gets validated, the device copy is what the kernels read.
+ * Host-only helper (no passage of the paper: the layout of a tensor list is this
+ * library's own; Section 5's models are lists of tensors): fills word_begin /
+ * tile_begin of segs_host[0..K) (a HOST array) and returns the total words per
+ * worker row and the total tile count.  The caller then copies the table to device
+ * memory (K*sizeof(dlion_seg) bytes, 8-byte aligned) and passes both copies to the
+ * _mt calls: the host copy is what gets validated, the device copy is what the
+ * kernels read.  Errors: DLION_EINVAL (null table, K < 1, a numel <= 0),
+ * DLION_EUNSUPPORTED (more than 2^31 - 1 tiles of 256 coordinates).
  */
 dlion_status dlion_mt_layout(dlion_seg *segs_host, int32_t K, int64_t *total_words,
                              int64_t *total_tiles);
 
+/*
+ * Worker side for a tensor list (Section 3.2, first display; Algorithm 1, worker-side),
+ * as dlion_worker_step on every tensor:  packed [N rows of W_total] uint64, out.
+ */
 dlion_status dlion_worker_step_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev, int32_t K,
                                   dlion_dtype g_dtype, uint64_t *packed, int64_t packed_stride,
                                   int32_t N, float beta1, float beta2, void *stream);
 
-/* packed: rows as dlion_worker_step_mt writes them (the unused bits of every tensor's last word
- * are zero); the counts of those padding positions come out as 0. */
+/*
+ * Server-side sum for a tensor list (Section 3.2, definition of S_t), as dlion_aggregate.
+ * packed: rows as dlion_worker_step_mt writes them (the unused bits of every tensor's last
+ * word are zero); counts [64*W_total] uint16, out: the counts of those padding positions
+ * come out as 0.  Only numel of each segment is read from the table.
+ */
 dlion_status dlion_aggregate_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev, int32_t K,
                                 const uint64_t *packed, int64_t packed_stride, int32_t N,
                                 uint16_t *counts, void *stream);
 
+/*
+ * Aggregation and weight update from counts for a tensor list (Section 3.2, second and
+ * third displays), as dlion_apply:  counts [64*W_total] uint16, in; every x in/out.
+ */
 dlion_status dlion_apply_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev, int32_t K,
                             const uint16_t *counts, int32_t N, dlion_mode mode, float lr,
                             float lambda, void *stream);
 
+/*
+ * Server side and weight update in one pass for a tensor list (Section 3.2, definition of
+ * S_t, second and third displays), as dlion_aggregate_apply.
+ */
 dlion_status dlion_aggregate_apply_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev,
                                       int32_t K, const uint64_t *packed, int64_t packed_stride,
                                       int32_t N, dlion_mode mode, float lr, float lambda,
                                       uint16_t *counts_or_null, void *stream);
 
+/*
+ * The whole iteration for a tensor list (Algorithm 1, one pass of the loop body), as
+ * dlion_step / dlion_step_ws: one fused kernel over all tensors.  The workspace form
+ * hands the votes of 16 or more workers on exactly as dlion_step_ws does;
+ * dlion_step_mt_workspace_bytes takes the total tile count that dlion_mt_layout returned.
+ */
 dlion_status dlion_step_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev, int32_t K,
                            dlion_dtype g_dtype, int32_t N, dlion_mode mode, float beta1,
                            float beta2, float lr, float lambda, uint64_t *packed_or_null,
                            int64_t packed_stride, uint16_t *counts_or_null, void *stream);
+
+dlion_status dlion_step_mt_ws(const dlion_seg *segs_host, const dlion_seg *segs_dev, int32_t K,
+                              dlion_dtype g_dtype, int32_t N, dlion_mode mode, float beta1,
+                              float beta2, float lr, float lambda, uint64_t *packed_or_null,
+                              int64_t packed_stride, uint16_t *counts_or_null,
+                              void *workspace_or_null, int64_t workspace_bytes, void *stream);
+
+int64_t dlion_step_mt_workspace_bytes(int64_t total_tiles, int32_t N);
 
 /* ------------------------------------------------------------------------- *
  * Wider rows around the hot path.
@@ -271,6 +318,34 @@ const char *dlion_status_str(dlion_status s);
 
 /* Library version, major*10000 + minor*100 + patch. */
 int dlion_version(void);
+
+/* ------------------------------------------------------------------------- *
+ * Launch-shape overrides, for tuning runs and for tests that must reach a
+ * variant the library would not pick at their sizes.  Nothing here changes a
+ * result.  Every field: -1 = the library decides (the default).
+ * ------------------------------------------------------------------------- */
+typedef struct dlion_tuning {
+    int32_t unroll;             /* worker/fused kernels: workers whose loads a wave issues back to back (1, 2, 4, 8) */
+    int32_t blocks_per_cu;      /* worker/fused kernels: resident one-wave workgroups per compute unit, 0 = no cap     */
+    int32_t pass_workers;       /* workers per launch of a step, 0 = all workers in one launch                        */
+    int32_t step_quads;         /* worker/fused kernels: 1 = four consecutive tiles per XCD, 0 = plain numbering      */
+    int32_t sliced_waves;       /* bit-sliced server kernels: waves per workgroup (1, 8, 16)                          */
+    int32_t sliced_min_workers; /* server side: the per-nibble kernel below this N, the bit-sliced one from it on     */
+    int32_t apply_blocks;       /* dlion_apply_encoded: resident workgroups per compute unit, 0 = no cap              */
+    int32_t reserved;           /* ignored                                                                           */
+    int64_t block_tiles;        /* worker/fused kernels: tiles (256 coordinates) per launch, 0 = all in one launch    */
+} dlion_tuning;
+
+/* Fills *t with -1 everywhere. */
+void dlion_tuning_defaults(dlion_tuning *t);
+
+/*
+ * Installs the overrides for every later call in this process (NULL = back to the
+ * defaults).  Host-only, not thread-safe: do not call it while another thread is
+ * inside the library.  DLION_EINVAL for a value outside the ranges above.
+ */
+dlion_status dlion_set_tuning(const dlion_tuning *t);
+void dlion_get_tuning(dlion_tuning *t);
 
 #ifdef __cplusplus
 }

@@ -25,6 +25,11 @@ from .binding import (  # noqa: F401
     dlion_apply_mt,
     dlion_step,
     dlion_step_mt,
+    dlion_step_mt_workspace_bytes,
+    dlion_get_tuning,
+    dlion_set_tuning,
+    tuned,
+    Tuning,
     dlion_step_workspace_bytes,
     dlion_step_ws,
     dlion_version,

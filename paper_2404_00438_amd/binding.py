@@ -29,6 +29,8 @@ EXPORTS = (
     "dlion_aggregate_apply_mt", "dlion_step_mt", "dlion_status_str", "dlion_version",
     "dlion_delta_planes", "dlion_aggregate_encode", "dlion_apply_encoded", "dlion_worker_step_pw",
     "dlion_step_pw", "dlion_global_lion_step", "dlion_step_ws", "dlion_step_workspace_bytes",
+    "dlion_step_mt_ws", "dlion_step_mt_workspace_bytes", "dlion_tuning_defaults", "dlion_set_tuning",
+    "dlion_get_tuning",
 )
 
 
@@ -44,6 +46,15 @@ class Seg(ctypes.Structure):
         ("x", ctypes.c_void_p), ("m", ctypes.c_void_p), ("g", ctypes.c_void_p),
         ("m_stride", ctypes.c_int64), ("g_stride", ctypes.c_int64), ("numel", ctypes.c_int64),
         ("word_begin", ctypes.c_int64), ("tile_begin", ctypes.c_int64),
+    ]
+
+
+class Tuning(ctypes.Structure):
+    """Mirror of ``dlion_tuning``: launch-shape overrides, -1 = the library decides."""
+    _fields_ = [
+        ("unroll", ctypes.c_int32), ("blocks_per_cu", ctypes.c_int32), ("pass_workers", ctypes.c_int32),
+        ("step_quads", ctypes.c_int32), ("sliced_waves", ctypes.c_int32), ("sliced_min_workers", ctypes.c_int32),
+        ("apply_blocks", ctypes.c_int32), ("reserved", ctypes.c_int32), ("block_tiles", ctypes.c_int64),
     ]
 
 
@@ -74,6 +85,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "dlion_apply_mt": [segp, vp, i32, vp, i32, ci, f32, f32, vp],
         "dlion_aggregate_apply_mt": [segp, vp, i32, vp, i64, i32, ci, f32, f32, vp, vp],
         "dlion_step_mt": [segp, vp, i32, ci, i32, ci, f32, f32, f32, f32, vp, i64, vp, vp],
+        "dlion_step_mt_ws": [segp, vp, i32, ci, i32, ci, f32, f32, f32, f32, vp, i64, vp, vp, i64, vp],
+        "dlion_set_tuning": [ctypes.POINTER(Tuning)],
         "dlion_delta_planes": [i32, ci],
         "dlion_aggregate_encode": [vp, i64, i64, i32, ci, vp, i64, vp],
         "dlion_apply_encoded": [vp, vp, i64, i64, i32, ci, f32, f32, vp],
@@ -91,6 +104,11 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.dlion_version.restype = ci
     lib.dlion_step_workspace_bytes.argtypes = [i64, i32]
     lib.dlion_step_workspace_bytes.restype = i64
+    lib.dlion_step_mt_workspace_bytes.argtypes = [i64, i32]
+    lib.dlion_step_mt_workspace_bytes.restype = i64
+    for name in ("dlion_tuning_defaults", "dlion_get_tuning"):
+        getattr(lib, name).argtypes = [ctypes.POINTER(Tuning)]
+        getattr(lib, name).restype = None
     _lib = lib                      # every later call goes to the library loaded last
     return lib
 
@@ -118,17 +136,21 @@ def _stream(stream) -> int:
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
 
 
+def _on_device(t: torch.Tensor) -> bool:
+    return t.is_cuda
+
+
 def _rows(t: torch.Tensor, name: str):
     """``[N, d]`` tensor with unit inner stride -> (pointer, row stride in elements, N, d)."""
     if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
         raise ValueError(f"{name} must be [N, d] with contiguous rows")
-    if not t.is_cuda:
+    if not _on_device(t):
         raise ValueError(f"{name} must be a device tensor")
     return t.data_ptr(), t.stride(0), t.shape[0], t.shape[1]
 
 
 def _flat(t: torch.Tensor, name: str, dtype: torch.dtype):
-    if t.dtype != dtype or t.dim() != 1 or (t.numel() > 1 and t.stride(0) != 1) or not t.is_cuda:
+    if t.dtype != dtype or t.dim() != 1 or (t.numel() > 1 and t.stride(0) != 1) or not _on_device(t):
         raise ValueError(f"{name} must be a contiguous 1-D {dtype} device tensor")
     return t.data_ptr()
 
@@ -148,55 +170,84 @@ def _as_u64(t: torch.Tensor, name: str):
     return t
 
 
-def _as_u16(t: torch.Tensor, name: str):
+def _packed(t: torch.Tensor, name: str, words: int, N: Optional[int] = None):
+    """``[N, >= words]`` uint64 rows -> (pointer, row stride, N); the C ABI cannot see extents, so they are
+    checked here: a short tensor would be a device access out of bounds."""
+    pp, ps, Np, width = _rows(_as_u64(t, name), name)
+    if width < words:
+        raise ValueError(f"{name} rows hold {width} words, {words} are needed")
+    if N is not None and Np != N:
+        raise ValueError(f"{name} must have {N} rows, has {Np}")
+    return pp, ps, Np
+
+
+def _counts(t: torch.Tensor, name: str, need: int) -> int:
+    """contiguous 1-D uint16 device tensor of at least ``need`` entries -> pointer"""
     if t.dtype not in (torch.int16, torch.uint16):
         raise TypeError(f"{name} must be int16/uint16 (uint16 counts)")
-    return t
+    if not _on_device(t) or t.dim() != 1 or (t.numel() > 1 and t.stride(0) != 1):
+        raise ValueError(f"{name} must be a contiguous 1-D device tensor")
+    if t.numel() < need:
+        raise ValueError(f"{name} holds {t.numel()} entries, {need} are needed")
+    return t.data_ptr()
+
+
+def _workspace(t: Optional[torch.Tensor]):
+    if t is None:
+        return None, 0
+    if not _on_device(t) or not t.is_contiguous():
+        raise ValueError("workspace must be a contiguous device tensor")
+    return t.data_ptr(), t.numel() * t.element_size()
+
+
+def _workers(m, g):
+    """``m``, ``g`` as ``[N, d]`` rows -> (m pointer, m stride, g pointer, g stride, N, d)"""
+    mp, ms, N, d = _rows(m, "m")
+    gp, gs, Ng, dg = _rows(g, "g")
+    if m.dtype != torch.float32 or (N, d) != (Ng, dg):
+        raise ValueError("m must be fp32 and m, g must agree on N and d")
+    return mp, ms, gp, gs, N, d
 
 
 def dlion_worker_step(m, g, packed, beta1, beta2, d=None, stream=None):
-    mp, ms, N, dd = _rows(m, "m")
-    gp, gs, Ng, dg = _rows(g, "g")
-    pp, ps, Np, _ = _rows(_as_u64(packed, "packed"), "packed")
-    if m.dtype != torch.float32 or (N, dd) != (Ng, dg) or Np != N:
-        raise ValueError("m must be fp32 and m, g, packed must agree on N and d")
-    d = dd if d is None else d
+    mp, ms, gp, gs, N, dd = _workers(m, g)
+    d = dd if d is None else int(d)
+    if not 0 < d <= dd:
+        raise ValueError(f"d = {d} is outside the rows' {dd} elements")
+    pp, ps, _ = _packed(packed, "packed", words_for(d), N)
     _check(load_library().dlion_worker_step(mp, ms, gp, gs, _gdtype(g), pp, ps, d, N, beta1, beta2,
                                             _stream(stream)), "dlion_worker_step")
 
 
 def dlion_aggregate(packed, d, counts, stream=None):
-    pp, ps, N, _ = _rows(_as_u64(packed, "packed"), "packed")
-    cp = _as_u16(counts, "counts").data_ptr()
+    pp, ps, N = _packed(packed, "packed", words_for(d))
+    cp = _counts(counts, "counts", d)
     _check(load_library().dlion_aggregate(pp, ps, d, N, cp, _stream(stream)), "dlion_aggregate")
 
 
 def dlion_apply(x, counts, N, mode, lr, lam, stream=None):
     xp = _flat(x, "x", torch.float32)
-    cp = _as_u16(counts, "counts").data_ptr()
+    cp = _counts(counts, "counts", x.numel())
     _check(load_library().dlion_apply(xp, cp, x.numel(), N, mode, lr, lam, _stream(stream)), "dlion_apply")
 
 
 def dlion_aggregate_apply(x, packed, mode, lr, lam, counts=None, stream=None):
     xp = _flat(x, "x", torch.float32)
-    pp, ps, N, _ = _rows(_as_u64(packed, "packed"), "packed")
-    cp = _as_u16(counts, "counts").data_ptr() if counts is not None else None
+    pp, ps, N = _packed(packed, "packed", words_for(x.numel()))
+    cp = _counts(counts, "counts", x.numel()) if counts is not None else None
     _check(load_library().dlion_aggregate_apply(xp, pp, ps, x.numel(), N, mode, lr, lam, cp, _stream(stream)),
            "dlion_aggregate_apply")
 
 
 def _step_args(x, m, g, packed, counts):
     xp = _flat(x, "x", torch.float32)
-    mp, ms, N, d = _rows(m, "m")
-    gp, gs, Ng, dg = _rows(g, "g")
-    if m.dtype != torch.float32 or (N, d) != (Ng, dg) or x.numel() != d:
-        raise ValueError("m must be fp32 and x, m, g must agree on N and d")
+    mp, ms, gp, gs, N, d = _workers(m, g)
+    if x.numel() != d:
+        raise ValueError("x, m, g must agree on d")
     pp, ps = (None, 0)
     if packed is not None:
-        pp, ps, Np, _ = _rows(_as_u64(packed, "packed"), "packed")
-        if Np != N:
-            raise ValueError("packed must have N rows")
-    cp = _as_u16(counts, "counts").data_ptr() if counts is not None else None
+        pp, ps, _ = _packed(packed, "packed", words_for(d), N)
+    cp = _counts(counts, "counts", d) if counts is not None else None
     return xp, mp, ms, gp, gs, _gdtype(g), d, N, pp, ps, cp
 
 
@@ -209,18 +260,54 @@ def dlion_step(x, m, g, mode, beta1, beta2, lr, lam, packed=None, counts=None, s
 def dlion_step_ws(x, m, g, mode, beta1, beta2, lr, lam, workspace, packed=None, counts=None, stream=None):
     """``dlion_step`` with a caller-owned scratch tensor (any dtype; its size in bytes is what counts)."""
     xp, mp, ms, gp, gs, gt, d, N, pp, ps, cp = _step_args(x, m, g, packed, counts)
-    wp, wb = (None, 0)
-    if workspace is not None:
-        if not workspace.is_cuda or not workspace.is_contiguous():
-            raise ValueError("workspace must be a contiguous device tensor")
-        wp, wb = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    wp, wb = _workspace(workspace)
     _check(load_library().dlion_step_ws(xp, mp, ms, gp, gs, gt, d, N, mode, beta1, beta2, lr, lam,
                                         pp, ps, cp, wp, wb, _stream(stream)), "dlion_step_ws")
 
 
 def dlion_step_workspace_bytes(d: int, N: int) -> int:
-    """Size of the workspace that lets ``dlion_step(..., workspace=...)`` split a step over many workers."""
+    """Size of the workspace with which ``dlion_step_ws`` splits a step over many workers (0: none is used)."""
     return int(load_library().dlion_step_workspace_bytes(d, N))
+
+
+def dlion_step_mt_workspace_bytes(total_tiles: int, N: int) -> int:
+    return int(load_library().dlion_step_mt_workspace_bytes(total_tiles, N))
+
+
+def dlion_get_tuning() -> Tuning:
+    t = Tuning()
+    load_library().dlion_get_tuning(ctypes.byref(t))
+    return t
+
+
+def dlion_set_tuning(t: Optional[Tuning] = None, **fields) -> None:
+    """Install launch-shape overrides (``None`` and no fields: back to the defaults).  Fields given by
+    name override the library's defaults, e.g. ``dlion_set_tuning(pass_workers=3, block_tiles=5)``."""
+    if t is None and fields:
+        t = Tuning()
+        load_library().dlion_tuning_defaults(ctypes.byref(t))
+    for k, v in fields.items():
+        if k not in dict(Tuning._fields_) or k == "reserved":
+            raise TypeError(f"dlion_tuning has no field {k}")
+        setattr(t, k, int(v))
+    _check(load_library().dlion_set_tuning(ctypes.byref(t) if t is not None else None), "dlion_set_tuning")
+
+
+class tuned:
+    """``with tuned(pass_workers=3): ...`` -- overrides for the calls inside, the previous ones after."""
+
+    def __init__(self, **fields):
+        self.fields = fields
+
+    def __enter__(self):
+        self.before = dlion_get_tuning()
+        now = dlion_get_tuning()
+        dlion_set_tuning(now, **self.fields)
+        return self
+
+    def __exit__(self, *exc):
+        dlion_set_tuning(self.before)
+        return False
 
 
 class SegTable:
@@ -289,41 +376,49 @@ class SegTable:
         return self.dev.data_ptr()
 
 
+def _table_workers(table: SegTable, N: int) -> None:
+    if table.N is not None and table.N != N:
+        raise ValueError(f"the table's tensors have {table.N} worker rows, the call says N = {N}")
+
+
 def dlion_worker_step_mt(table: SegTable, packed, beta1, beta2, stream=None):
-    pp, ps, N, _ = _rows(_as_u64(packed, "packed"), "packed")
+    pp, ps, N = _packed(packed, "packed", table.total_words)
+    _table_workers(table, N)
     _check(load_library().dlion_worker_step_mt(table.host, table.dev_ptr, table.K, table.g_dtype, pp, ps, N,
                                                beta1, beta2, _stream(stream)), "dlion_worker_step_mt")
 
 
 def dlion_aggregate_mt(table: SegTable, packed, counts, stream=None):
-    pp, ps, N, _ = _rows(_as_u64(packed, "packed"), "packed")
-    cp = _as_u16(counts, "counts").data_ptr()
+    pp, ps, N = _packed(packed, "packed", table.total_words)
+    cp = _counts(counts, "counts", 64 * table.total_words)
     _check(load_library().dlion_aggregate_mt(table.host, table.dev_ptr, table.K, pp, ps, N, cp,
                                              _stream(stream)), "dlion_aggregate_mt")
 
 
 def dlion_apply_mt(table: SegTable, counts, N, mode, lr, lam, stream=None):
-    cp = _as_u16(counts, "counts").data_ptr()
+    cp = _counts(counts, "counts", 64 * table.total_words)
     _check(load_library().dlion_apply_mt(table.host, table.dev_ptr, table.K, cp, N, mode, lr, lam,
                                          _stream(stream)), "dlion_apply_mt")
 
 
 def dlion_aggregate_apply_mt(table: SegTable, packed, mode, lr, lam, counts=None, stream=None):
-    pp, ps, N, _ = _rows(_as_u64(packed, "packed"), "packed")
-    cp = _as_u16(counts, "counts").data_ptr() if counts is not None else None
+    pp, ps, N = _packed(packed, "packed", table.total_words)
+    cp = _counts(counts, "counts", 64 * table.total_words) if counts is not None else None
     _check(load_library().dlion_aggregate_apply_mt(table.host, table.dev_ptr, table.K, pp, ps, N, mode, lr, lam,
                                                    cp, _stream(stream)), "dlion_aggregate_apply_mt")
 
 
-def dlion_step_mt(table: SegTable, N, mode, beta1, beta2, lr, lam, packed=None, counts=None, stream=None):
+def dlion_step_mt(table: SegTable, N, mode, beta1, beta2, lr, lam, packed=None, counts=None, workspace=None,
+                  stream=None):
+    """``dlion_step_mt``; with a ``workspace`` tensor, ``dlion_step_mt_ws``."""
+    _table_workers(table, N)
     pp, ps = (None, 0)
     if packed is not None:
-        pp, ps, Np, _ = _rows(_as_u64(packed, "packed"), "packed")
-        if Np != N:
-            raise ValueError("packed must have N rows")
-    cp = _as_u16(counts, "counts").data_ptr() if counts is not None else None
-    _check(load_library().dlion_step_mt(table.host, table.dev_ptr, table.K, table.g_dtype, N, mode, beta1, beta2,
-                                        lr, lam, pp, ps, cp, _stream(stream)), "dlion_step_mt")
+        pp, ps, _ = _packed(packed, "packed", table.total_words, N)
+    cp = _counts(counts, "counts", 64 * table.total_words) if counts is not None else None
+    wp, wb = _workspace(workspace)
+    _check(load_library().dlion_step_mt_ws(table.host, table.dev_ptr, table.K, table.g_dtype, N, mode, beta1, beta2,
+                                           lr, lam, pp, ps, cp, wp, wb, _stream(stream)), "dlion_step_mt")
 
 
 def dlion_delta_planes(N: int, mode: int) -> int:
@@ -331,69 +426,49 @@ def dlion_delta_planes(N: int, mode: int) -> int:
 
 
 def dlion_aggregate_encode(packed, d, mode, delta, stream=None):
-    pp, ps, N, _ = _rows(_as_u64(packed, "packed"), "packed")
-    dp, ds, P, _ = _rows(_as_u64(delta, "delta"), "delta")
-    if P != dlion_delta_planes(N, mode):
-        raise ValueError("delta must have dlion_delta_planes(N, mode) rows")
+    pp, ps, N = _packed(packed, "packed", words_for(d))
+    dp, ds, _ = _packed(delta, "delta", words_for(d), dlion_delta_planes(N, mode))
     _check(load_library().dlion_aggregate_encode(pp, ps, d, N, mode, dp, ds, _stream(stream)),
            "dlion_aggregate_encode")
 
 
 def dlion_apply_encoded(x, delta, N, mode, lr, lam, stream=None):
     xp = _flat(x, "x", torch.float32)
-    dp, ds, P, _ = _rows(_as_u64(delta, "delta"), "delta")
-    if P != dlion_delta_planes(N, mode):
-        raise ValueError("delta must have dlion_delta_planes(N, mode) rows")
+    dp, ds, _ = _packed(delta, "delta", words_for(x.numel()), dlion_delta_planes(N, mode))
     _check(load_library().dlion_apply_encoded(xp, dp, ds, x.numel(), N, mode, lr, lam, _stream(stream)),
            "dlion_apply_encoded")
 
 
 def _betas(beta1, beta2, N):
     for b in (beta1, beta2):
-        if b.dtype != torch.float32 or b.dim() != 1 or b.numel() != N or not b.is_cuda or \
+        if b.dtype != torch.float32 or b.dim() != 1 or b.numel() != N or not _on_device(b) or \
                 (N > 1 and b.stride(0) != 1):
             raise ValueError("beta1/beta2 must be contiguous float32 device tensors of N elements")
     return beta1.data_ptr(), beta2.data_ptr()
 
 
 def dlion_worker_step_pw(m, g, packed, beta1, beta2, stream=None):
-    mp, ms, N, d = _rows(m, "m")
-    gp, gs, Ng, dg = _rows(g, "g")
-    pp, ps, Np, _ = _rows(_as_u64(packed, "packed"), "packed")
-    if m.dtype != torch.float32 or (N, d) != (Ng, dg) or Np != N:
-        raise ValueError("m must be fp32 and m, g, packed must agree on N and d")
+    mp, ms, gp, gs, N, d = _workers(m, g)
+    pp, ps, _ = _packed(packed, "packed", words_for(d), N)
     b1, b2 = _betas(beta1, beta2, N)
     _check(load_library().dlion_worker_step_pw(mp, ms, gp, gs, _gdtype(g), pp, ps, d, N, b1, b2,
                                                _stream(stream)), "dlion_worker_step_pw")
 
 
 def dlion_step_pw(x, m, g, mode, beta1, beta2, lr, lam, packed=None, counts=None, stream=None):
-    xp = _flat(x, "x", torch.float32)
-    mp, ms, N, d = _rows(m, "m")
-    gp, gs, Ng, dg = _rows(g, "g")
-    if m.dtype != torch.float32 or (N, d) != (Ng, dg) or x.numel() != d:
-        raise ValueError("m must be fp32 and x, m, g must agree on N and d")
-    pp, ps = (None, 0)
-    if packed is not None:
-        pp, ps, Np, _ = _rows(_as_u64(packed, "packed"), "packed")
-        if Np != N:
-            raise ValueError("packed must have N rows")
-    cp = _as_u16(counts, "counts").data_ptr() if counts is not None else None
+    xp, mp, ms, gp, gs, gt, d, N, pp, ps, cp = _step_args(x, m, g, packed, counts)
     b1, b2 = _betas(beta1, beta2, N)
-    _check(load_library().dlion_step_pw(xp, mp, ms, gp, gs, _gdtype(g), d, N, mode, b1, b2, lr, lam,
+    _check(load_library().dlion_step_pw(xp, mp, ms, gp, gs, gt, d, N, mode, b1, b2, lr, lam,
                                         pp, ps, cp, _stream(stream)), "dlion_step_pw")
 
 
 def dlion_global_lion_step(x, m, g, beta1, beta2, lr, lam, sign_bits=None, stream=None):
-    xp = _flat(x, "x", torch.float32)
-    mp, ms, N, d = _rows(m, "m")
-    gp, gs, Ng, dg = _rows(g, "g")
-    if m.dtype != torch.float32 or (N, d) != (Ng, dg) or x.numel() != d:
-        raise ValueError("m must be fp32 and x, m, g must agree on N and d")
+    xp, mp, ms, gp, gs, gt, d, N, _, _, _ = _step_args(x, m, g, None, None)
     sp = None
     if sign_bits is not None:
-        if _as_u64(sign_bits, "sign_bits").numel() < words_for(d) or sign_bits.dim() != 1:
-            raise ValueError("sign_bits must be a 1-D tensor of at least W words")
+        if _as_u64(sign_bits, "sign_bits").dim() != 1 or sign_bits.numel() < words_for(d) or \
+                not _on_device(sign_bits) or (sign_bits.numel() > 1 and sign_bits.stride(0) != 1):
+            raise ValueError("sign_bits must be a contiguous 1-D device tensor of at least W words")
         sp = sign_bits.data_ptr()
-    _check(load_library().dlion_global_lion_step(xp, mp, ms, gp, gs, _gdtype(g), d, N, beta1, beta2, lr, lam,
+    _check(load_library().dlion_global_lion_step(xp, mp, ms, gp, gs, gt, d, N, beta1, beta2, lr, lam,
                                                  sp, _stream(stream)), "dlion_global_lion_step")

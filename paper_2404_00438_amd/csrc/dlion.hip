@@ -4,7 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
-#include <cstdlib>
+#include <mutex>
 #include <type_traits>
 
 namespace {
@@ -20,12 +20,9 @@ inline int64_t words_for(int64_t numel) { return (numel + 63) / 64; }
 
 inline bool power_of_two(int32_t n) { return n > 0 && (n & (n - 1)) == 0; }
 
-// Environment overrides for tuning runs (read on every call).
-inline int env_int(const char *name)
-{
-    const char *v = std::getenv(name);
-    return v ? std::atoi(v) : -1;
-}
+// Launch-shape overrides (dlion_set_tuning); every field -1 = the library decides.
+dlion_tuning g_tuning = {-1, -1, -1, -1, -1, -1, -1, -1, -1};
+inline const dlion_tuning &tuning() { return g_tuning; }
 
 Hyper make_hyper(int32_t N, int mode, float beta1, float beta2, float lr, float lambda)
 {
@@ -42,7 +39,9 @@ Hyper make_hyper(int32_t N, int mode, float beta1, float beta2, float lr, float 
     h.stream_counts = 0;
     h.worker_begin = 0;
     h.worker_end = N;
-    h.counts_in = 0;
+    h.carry = kCarryNone;
+    h.carry_in = 0;
+    h.carry_out = 0;
     h.xcd_quads = 0;
     h.beta1_pw = nullptr;
     h.beta2_pw = nullptr;
@@ -64,15 +63,21 @@ inline bool rows_split_lines(const void *base, int64_t stride, size_t elem, int3
 }
 inline int32_t step_quads(bool split)
 {
-    const int env = env_int("DLION_STEP_QUADS");           // tuning: 0 / 1 forces the numbering
-    return env >= 0 ? (env > 0) : (split ? 1 : 0);
+    const int forced = tuning().step_quads;
+    return forced >= 0 ? (forced > 0) : (split ? 1 : 0);
 }
 
-inline dim3 grid_for(int64_t tiles) { return dim3(static_cast<uint32_t>((tiles + kWavesPerBlock - 1) / kWavesPerBlock)); }
+inline dim3 grid_for(int64_t tiles) { return dim3(static_cast<uint32_t>(tiles)); }
 
-inline dlion_status launched()
+// Enqueues one kernel and reports what the launch call itself returned: an error that an earlier
+// call of this thread left behind is neither reported as ours nor cleared.
+template <typename T> struct same { using type = T; };
+template <typename... P>
+dlion_status launch(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds, hipStream_t s, typename same<P>::type... args)
 {
-    return hipGetLastError() == hipSuccess ? DLION_OK : DLION_ELAUNCH;
+    void *argv[] = {static_cast<void *>(&args)...};
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, argv, lds, s);
+    return e == hipSuccess ? DLION_OK : DLION_ELAUNCH;
 }
 
 // ------------------------------------------------------------------ launch shape
@@ -90,8 +95,8 @@ inline dlion_status launched()
 // What was tried and dropped for many workers in one launch: 16-wave workgroups walking over
 // the workers in lockstep cut the per-CU translation-cache misses 15x at N = 32 (5.5 M against
 // 84 M per launch) but were 1-3 % slower on the same allocation; the large run-to-run spread
-// of one launch at N = 32 (65-76 % of peak) follows the physical placement of the allocation,
-// not the launch shape.  What works is fewer workers per launch (launch_step below).
+// of one launch at N = 32 (65-76 % of peak) follows the row stride (a multiple of 4 KB is the
+// slow case), not the launch shape.  What works is fewer workers per launch (launch_step below).
 struct LaunchShape {
     int unroll;          // workers whose loads are issued back to back (8, 4, 2 or 1)
     int blocks_per_cu;   // resident workgroups per compute unit (0: no cap)
@@ -110,21 +115,17 @@ inline size_t lds_reservation(int blocks_per_cu)
     return bytes > kMaxDynamicLds ? kMaxDynamicLds : bytes;
 }
 
-
 LaunchShape step_shape(int32_t N, size_t bytes_per_worker_per_wave)
 {
-    // read on every call (a getenv is nothing next to a launch) so that a tuning run can
-    // switch shapes inside one process, on the same allocation
-    const int env_unroll = env_int("DLION_UNROLL");
-    const int env_blocks = env_int("DLION_BLOCKS_PER_CU");
+    const dlion_tuning &tn = tuning();
     LaunchShape s;
-    s.unroll = env_unroll > 0 ? env_unroll : 2;
+    s.unroll = tn.unroll > 0 ? tn.unroll : 2;
     while (s.unroll > N)
         s.unroll >>= 1;
     if (s.unroll < 1)
         s.unroll = 1;
-    if (env_blocks >= 0) {
-        s.blocks_per_cu = env_blocks;
+    if (tn.blocks_per_cu >= 0) {
+        s.blocks_per_cu = tn.blocks_per_cu;
     } else {
         const size_t target = (N >= kManyWorkers ? 18 : 28) * 1024;
         const size_t in_flight = bytes_per_worker_per_wave * static_cast<size_t>(s.unroll);
@@ -139,30 +140,29 @@ template <typename GT, int kUnroll, bool kApply, class Addr>
 dlion_status launch_step_flags(const Addr &addr, const Hyper &h, bool packed, bool counts, size_t lds,
                                hipStream_t s)
 {
-    const dim3 grid = grid_for(addr.total_tiles - addr.first_tile), block(kBlock);
-    const size_t stage = static_cast<size_t>(kWavesPerBlock) * kLanes * sizeof(uint64_t);
+    const dim3 grid = grid_for(addr.total_tiles - addr.first_tile), block(kLanes);
+    const size_t stage = kLanes * sizeof(uint64_t);
     if (packed && lds < stage)
         lds = stage;                                      // packed words are staged in LDS, 512 B per wave
     if (packed && counts)
-        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, true, true, Addr>), grid, block, lds, s, addr, h);
-    else if (packed)
-        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, true, false, Addr>), grid, block, lds, s, addr, h);
-    else if (counts)
-        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, false, true, Addr>), grid, block, lds, s, addr, h);
-    else
-        hipLaunchKernelGGL((step_kernel<GT, kUnroll, kApply, false, false, Addr>), grid, block, lds, s, addr, h);
-    return launched();
+        return launch(step_kernel<GT, kUnroll, kApply, true, true, Addr>, grid, block, lds, s, addr, h);
+    if (packed)
+        return launch(step_kernel<GT, kUnroll, kApply, true, false, Addr>, grid, block, lds, s, addr, h);
+    if (counts)
+        return launch(step_kernel<GT, kUnroll, kApply, false, true, Addr>, grid, block, lds, s, addr, h);
+    return launch(step_kernel<GT, kUnroll, kApply, false, false, Addr>, grid, block, lds, s, addr, h);
 }
 
 template <typename GT, bool kApply, class Addr>
-dlion_status launch_step_unroll(const Addr &addr, const Hyper &h, bool packed, bool counts, hipStream_t s)
+dlion_status launch_step_unroll(const Addr &addr, const Hyper &h, bool packed, bool counts, int64_t problem_tiles,
+                                hipStream_t s)
 {
-    LaunchShape shape = step_shape(h.worker_end - h.worker_begin, kSubs * kLanes * (16 + Grad<GT>::kVecBytes));
+    LaunchShape shape = step_shape(h.worker_end - h.worker_begin, kLanes * (16 + Grad<GT>::kVecBytes));
     // A problem whose waves all fit on the chip at once never reaches the steady state the cap
     // is tuned for; it is latency-bound and wants every wave resident (d = 1,000,003, N = 4:
     // 12.7 -> 10.4 us).
-    if (env_int("DLION_BLOCKS_PER_CU") < 0) {
-        if (addr.total_tiles - addr.first_tile <= kResidentWaves)
+    if (tuning().blocks_per_cu < 0) {
+        if (problem_tiles <= kResidentWaves)
             shape.blocks_per_cu = 0;
         else if (shape.blocks_per_cu > 0 && std::is_same<Addr, SegAddr>::value)
             shape.blocks_per_cu += 1;
@@ -178,97 +178,156 @@ dlion_status launch_step_unroll(const Addr &addr, const Hyper &h, bool packed, b
 
 template <bool kApply, class Addr>
 dlion_status launch_step_once(const Addr &addr, const Hyper &h, dlion_dtype g_dtype, bool packed, bool counts,
-                              hipStream_t s)
+                              int64_t problem_tiles, hipStream_t s)
 {
     if (g_dtype == DLION_BF16)
-        return launch_step_unroll<uint16_t, kApply, Addr>(addr, h, packed, counts, s);
-    return launch_step_unroll<float, kApply, Addr>(addr, h, packed, counts, s);
+        return launch_step_unroll<uint16_t, kApply, Addr>(addr, h, packed, counts, problem_tiles, s);
+    return launch_step_unroll<float, kApply, Addr>(addr, h, packed, counts, problem_tiles, s);
 }
 
-// Many workers, large d: the step runs as consecutive launches over kPassWorkers workers each.
-// One launch over all N rows keeps 2N + 1 streams (and as many pages) open across the chip at
-// once, and from N = 16 on that costs more bandwidth than the counts cost that carry the votes
-// from one launch to the next (2 B written and 2 B read per coordinate and launch, against
-// 10-12 B per coordinate and worker).  Measured, fused step with counts, bf16 gradients, one
-// launch -> launches over 8 workers: d = 350 M, N = 32: 21.3 -> 19.7 ms; d = 85.6 M, N = 16:
-// 2.38 -> 2.28 ms; d = 100 M, N = 64: 12.2 -> 10.5 ms; worker step, d = 350 M, N = 32:
-// 24.0 -> 19.7 ms.  N = 12 gains nothing, and below ~16 M coordinates the extra launches cost
-// what they save.  The worker step needs no carry at all; the fused step carries the votes in
-// the caller's counts array or, without one, in the caller's workspace (flat buffers only), and
-// stays one launch when it has neither: the library owns no memory.
+// How a step is cut into launches.
+//
+// By tiles.  Workgroups are handed to the 8 XCDs round-robin and every XCD works through its own
+// share at its own pace, so over a long launch the XCDs drift apart and the window of addresses in
+// flight widens; launches of kBlockTiles tiles bring them back together (N = 8, bf16: d = 1.3 G
+// 77.6 -> 80.2 % of peak, d = 350 M 76.9 -> 79.1 %, d = 124 M unchanged; a launch boundary costs
+// about 4.5 us, 0.5 % at this size).
+//
+// By workers.  One launch over all N rows keeps 2N + 1 streams (and as many pages) open across
+// the chip at once, and from N = 16 on that costs more bandwidth than handing the votes from one
+// launch over kPassWorkers workers to the next (fused step, bf16 gradients, d = 350 M, N = 32:
+// one launch 20.7 ms, launches over 8 workers 18.5 ms; N = 12 gains nothing, and below ~16 M
+// coordinates the extra launches cost what they save).  The worker step needs no hand-over.  The
+// fused step hands the votes on in the caller's workspace or, without one, in the caller's counts
+// array, and stays one launch per block when it has neither: the library owns no memory.  All
+// launches of one block of tiles run before the next block starts, so the hand-over is still in
+// the memory-side cache when it is read back.
+//
+// Hand-over formats (Carry): in a workspace and with at most kNibblePasses launches, every
+// launch but the last writes its own plane of 4-bit partial counts (0.5 B per coordinate written,
+// and read once by the last launch); with more launches a running uint16 count per coordinate (2 B
+// read + 2 B written per launch); in the counts array the running count, indexed by coordinate.
 constexpr int kPassWorkers = 8;
 constexpr int kPassMinN = 16;
+constexpr int kNibblePasses = 8;            // at most 7 planes of partial counts
+constexpr int kNibbleMaxWorkers = 15;       // a partial count must fit 4 bits
 constexpr int64_t kPassMinTiles = 8 * kResidentWaves;
-constexpr int64_t kPassTiles = 16 * kResidentWaves;      // 33.5 M coordinates
-constexpr int64_t kPassMinBlockTiles = 4 * kResidentWaves;   // a workspace below 16 MB is not used
+constexpr int64_t kBlockTiles = 32 * kResidentWaves;         // 67 M coordinates per launch
+constexpr int64_t kPassMinBlockTiles = 4 * kResidentWaves;   // a workspace that holds less is not used
 
-// Where the votes wait between the launches of one block of tiles.
 struct Workspace {
-    uint16_t *base = nullptr;
-    int64_t coords = 0;          // capacity in coordinates
+    void *base = nullptr;
+    int64_t bytes = 0;
 };
 
-// Points the carry (and, for the launches that only hand the votes on, the counts output) of a
-// flat problem at the workspace, which holds the block of coordinates that starts at `origin`.
-inline void carry_in_workspace(FlatAddr &a, const Workspace &ws, int64_t origin, bool hand_on)
+struct StepPlan {
+    int passes = 1;          // launches per block of tiles
+    int carry = kCarryNone;
+    int64_t block = 0;       // tiles per block
+    int64_t ws_tile = 0;     // workspace bytes per tile
+};
+
+inline int64_t ws_bytes_per_tile(int carry, int passes)
 {
-    uint16_t *shifted = reinterpret_cast<uint16_t *>(reinterpret_cast<uintptr_t>(ws.base) -
-                                                     static_cast<uintptr_t>(origin) * sizeof(uint16_t));
-    a.p.carry = shifted;
-    a.p.counts = hand_on ? shifted : nullptr;
+    if (carry == kCarryNibbles)
+        return (int64_t)(passes - 1) * kNibbleCarryPerTile * 2;
+    return carry == kCarryRunning ? kRunningCarryPerTile * 2 : 0;
 }
-inline void carry_in_workspace(SegAddr &, const Workspace &, int64_t, bool) {}   // tensor lists: counts only
-inline bool workspace_usable(const FlatAddr &, const Workspace &ws) { return ws.base && ws.coords >= kPassMinBlockTiles * kTile; }
-inline bool workspace_usable(const SegAddr &, const Workspace &) { return false; }
+
+// passes of the default split for N workers over `tiles` tiles (1: no split)
+inline int default_passes(int32_t N, int64_t tiles)
+{
+    int per = tuning().pass_workers;                      // 0 = always one launch
+    if (per < 0)
+        per = (N >= kPassMinN && tiles >= kPassMinTiles) ? kPassWorkers : 0;
+    return (per <= 0 || per >= N) ? 1 : (N + per - 1) / per;
+}
+
+inline int workspace_carry(int32_t N, int passes)
+{
+    const int most = (N + passes - 1) / passes;           // workers of the largest launch
+    return (passes <= kNibblePasses && most <= kNibbleMaxWorkers) ? kCarryNibbles : kCarryRunning;
+}
+
+inline int64_t default_block_tiles()
+{
+    const int64_t forced = tuning().block_tiles;           // 0 = all tiles in one block
+    return forced >= 0 ? forced : kBlockTiles;
+}
+
+StepPlan plan_step(int32_t N, int64_t tiles, bool apply, bool counts, const Workspace &ws)
+{
+    StepPlan pl;
+    pl.passes = default_passes(N, tiles);
+    pl.block = default_block_tiles();
+    if (pl.block <= 0 || pl.block > tiles)
+        pl.block = tiles;
+    if (pl.passes > 1 && apply) {
+        // the fused step needs somewhere to hand the votes on: the workspace, else the counts output
+        const int carry = workspace_carry(N, pl.passes);
+        const int64_t per_tile = ws_bytes_per_tile(carry, pl.passes);
+        const int64_t fit = ws.base ? ws.bytes / per_tile : 0;
+        if (fit >= pl.block || fit >= kPassMinBlockTiles) {
+            pl.carry = carry;
+            pl.ws_tile = per_tile;
+            if (fit < pl.block)
+                pl.block = fit;
+        } else if (counts) {
+            pl.carry = kCarryCounts;
+        } else {
+            pl.passes = 1;
+        }
+    }
+    return pl;
+}
+
+template <class Addr> inline void set_workspace(Addr &a, const StepPlan &pl, const Workspace &ws)
+{
+    a.ws = (pl.carry == kCarryNibbles || pl.carry == kCarryRunning) ? static_cast<uint16_t *>(ws.base) : nullptr;
+    a.ws_plane = pl.block * kNibbleCarryPerTile;
+}
 
 template <bool kApply, class Addr>
 dlion_status launch_step(const Addr &addr, const Hyper &h0, dlion_dtype g_dtype, bool packed, bool counts,
                          hipStream_t s, const Workspace &ws = Workspace())
 {
     const int N = h0.N;
-    int per = env_int("DLION_PASS_WORKERS");             // tuning: 0 = always one launch
-    if (per < 0)
-        per = (N >= kPassMinN && addr.total_tiles >= kPassMinTiles) ? kPassWorkers : 0;
-    // the fused step needs somewhere to carry the votes: the counts output, else the workspace
-    const bool in_ws = kApply && !counts && workspace_usable(addr, ws);
-    if (kApply && !counts && !in_ws)
-        per = 0;
-    if (per <= 0 || per >= N)
-        return launch_step_once<kApply, Addr>(addr, h0, g_dtype, packed, counts, s);
-    const int passes = (N + per - 1) / per;
-    // With a carry, all launches of one block of kPassTiles tiles run before the next block is
-    // started: the block's counts (64 MB) are still in the memory-side cache when the next
-    // launch reads them, so the carry costs no HBM traffic (d = 350 M, N = 32: 19.7 -> 19.0 ms).
-    int64_t block = env_int("DLION_PASS_TILES");          // tuning: 0 = all tiles in one block
-    if (block < 0)
-        block = kPassTiles;
-    if ((!counts && !in_ws) || block == 0)
-        block = addr.total_tiles;
-    if (in_ws && block > ws.coords / kTile)
-        block = ws.coords / kTile;
+    const int64_t tiles = addr.total_tiles;
+    const StepPlan pl = plan_step(N, tiles, kApply, counts, ws);
     Hyper h = h0;
     Addr a = addr;
-    for (int64_t first = 0; first < addr.total_tiles; first += block) {
+    set_workspace(a, pl, ws);
+    for (int64_t first = 0; first < tiles; first += pl.block) {
         a.first_tile = first;
-        a.total_tiles = first + block < addr.total_tiles ? first + block : addr.total_tiles;
-        for (int pass = 0; pass < passes; ++pass) {
+        a.total_tiles = first + pl.block < tiles ? first + pl.block : tiles;
+        for (int pass = 0; pass < pl.passes; ++pass) {
             // spread evenly: N = 30 runs as 8, 8, 7, 7
-            h.worker_begin = static_cast<int32_t>((int64_t)N * pass / passes);
-            h.worker_end = static_cast<int32_t>((int64_t)N * (pass + 1) / passes);
-            h.counts_in = ((counts || in_ws) && pass > 0) ? 1 : 0;
-            const bool last = pass == passes - 1;
-            // the carry is read again right away: keep it cached; the result follows the caller's hint
-            h.stream_counts = (last || block == addr.total_tiles) ? h0.stream_counts : 0;
-            if (in_ws) {
-                carry_in_workspace(a, ws, first * kTile, !last);
-                h.stream_counts = 0;
+            h.worker_begin = static_cast<int32_t>((int64_t)N * pass / pl.passes);
+            h.worker_end = static_cast<int32_t>((int64_t)N * (pass + 1) / pl.passes);
+            const bool last = pass == pl.passes - 1;
+            h.carry = pl.carry;
+            h.carry_in = h.carry_out = 0;
+            h.stream_counts = h0.stream_counts;
+            bool counts_out = counts;
+            if (pl.carry == kCarryCounts) {
+                h.carry_in = pass > 0;
+                // the running count is read again right away: keep it cached; the result follows the caller's hint
+                if (!last && pl.block < tiles)
+                    h.stream_counts = 0;
+            } else if (pl.carry == kCarryRunning) {
+                h.carry_in = pass > 0;
+                h.carry_out = !last;
+                counts_out = counts && last;
+            } else if (pl.carry == kCarryNibbles) {
+                h.carry_in = last ? pl.passes - 1 : 0;
+                h.carry_out = last ? 0 : pass + 1;
+                counts_out = counts && last;
             }
-            const bool counts_out = in_ws ? !last : counts;
             dlion_status st;
             if (kApply && last)
-                st = launch_step_once<true, Addr>(a, h, g_dtype, packed, counts_out, s);
+                st = launch_step_once<true, Addr>(a, h, g_dtype, packed, counts_out, tiles, s);
             else
-                st = launch_step_once<false, Addr>(a, h, g_dtype, packed, counts_out, s);
+                st = launch_step_once<false, Addr>(a, h, g_dtype, packed, counts_out, tiles, s);
             if (st != DLION_OK)
                 return st;
         }
@@ -279,14 +338,13 @@ dlion_status launch_step(const Addr &addr, const Hyper &h0, dlion_dtype g_dtype,
 template <class Addr>
 dlion_status launch_aggregate(const Addr &addr, const Hyper &h, bool apply, bool counts, hipStream_t s)
 {
-    const dim3 grid = grid_for(addr.total_tiles), block(kBlock);
+    const dim3 grid = grid_for(addr.total_tiles), block(kLanes);
     if (apply && counts)
-        hipLaunchKernelGGL((aggregate_kernel<true, true, Addr>), grid, block, 0, s, addr, h);
+        return launch(aggregate_kernel<true, true, Addr>, grid, block, 0, s, addr, h);
     else if (apply)
-        hipLaunchKernelGGL((aggregate_kernel<true, false, Addr>), grid, block, 0, s, addr, h);
+        return launch(aggregate_kernel<true, false, Addr>, grid, block, 0, s, addr, h);
     else
-        hipLaunchKernelGGL((aggregate_kernel<false, true, Addr>), grid, block, 0, s, addr, h);
-    return launched();
+        return launch(aggregate_kernel<false, true, Addr>, grid, block, 0, s, addr, h);
 }
 
 // Bit-sliced counting (flat buffers): planes = bits needed for a count 0..N; waves per
@@ -299,12 +357,11 @@ dlion_status launch_sliced_shape(const FlatAddr &addr, const Hyper &h, bool appl
     const dim3 grid(static_cast<uint32_t>((groups + kWaves - 1) / kWaves)), block(kLanes * kWaves);
     const size_t lds = static_cast<size_t>(kWaves) * kPlanes * kSlicedLdsPerPlane * sizeof(uint32_t);
     if (apply && counts)
-        hipLaunchKernelGGL((aggregate_sliced_kernel<kPlanes, kWaves, true, true>), grid, block, lds, s, addr, h);
+        return launch(aggregate_sliced_kernel<kPlanes, kWaves, true, true>, grid, block, lds, s, addr, h);
     else if (apply)
-        hipLaunchKernelGGL((aggregate_sliced_kernel<kPlanes, kWaves, true, false>), grid, block, lds, s, addr, h);
+        return launch(aggregate_sliced_kernel<kPlanes, kWaves, true, false>, grid, block, lds, s, addr, h);
     else
-        hipLaunchKernelGGL((aggregate_sliced_kernel<kPlanes, kWaves, false, true>), grid, block, lds, s, addr, h);
-    return launched();
+        return launch(aggregate_sliced_kernel<kPlanes, kWaves, false, true>, grid, block, lds, s, addr, h);
 }
 
 // Waves per workgroup of the bit-sliced kernels (they walk the streams in lockstep and write
@@ -329,16 +386,16 @@ inline int64_t sliced_groups(int64_t numel) { return (words_for(numel) + kSliced
 
 inline bool use_sliced(int32_t N, int64_t numel, bool apply)
 {
-    const int env_min = env_int("DLION_SLICED_MIN_WORKERS");      // tuning: per-nibble kernel below this N
-    if (env_min >= 0)
-        return N >= env_min;
+    const int forced = tuning().sliced_min_workers;       // per-nibble kernel below this N
+    if (forced >= 0)
+        return N >= forced;
     return !apply || sliced_groups(numel) >= kSlicedMinGroups;
 }
 
 template <int kPlanes, bool kAllow16>
 dlion_status launch_sliced_planes(const FlatAddr &addr, const Hyper &h, bool apply, bool counts, hipStream_t s)
 {
-    const int env_waves = env_int("DLION_SLICED_WAVES");   // tuning: 1, 8 or 16
+    const int env_waves = tuning().sliced_waves;            // forced: 1, 8 or 16
     // few groups: one-wave workgroups spread them over more compute units (d = 4 M, N = 32: 7.6 against 12.1 us)
     const bool small = sliced_groups(addr.p.numel) < kSlicedMinGroups;
     const int waves = env_waves > 0 ? env_waves : (small ? 1 : (h.N >= kSliced16MinWorkers ? 16 : kSlicedWaves));
@@ -365,8 +422,7 @@ dlion_status launch_sliced(const FlatAddr &addr, const Hyper &h, bool apply, boo
 template <class Addr> dlion_status launch_apply(const Addr &addr, const Hyper &h, hipStream_t s)
 {
     // no occupancy cap here: it only loses (d = 124 M: 88.7 % uncapped, 81 % with 16-24 waves per compute unit)
-    hipLaunchKernelGGL((apply_kernel<Addr>), grid_for(addr.total_tiles), dim3(kBlock), 0, s, addr, h);
-    return launched();
+    return launch(apply_kernel<Addr>, grid_for(addr.total_tiles), dim3(kLanes), 0, s, addr, h);
 }
 
 // Down-link message: planes needed for Delta.
@@ -387,14 +443,13 @@ dlion_status launch_encode_shape(const FlatAddr &addr, const Hyper &h, const Del
     const int64_t W = words_for(addr.p.numel);
     const int64_t groups = (W + kSlicedWords - 1) / kSlicedWords;
     const dim3 grid(static_cast<uint32_t>((groups + kWaves - 1) / kWaves)), block(kLanes * kWaves);
-    hipLaunchKernelGGL((aggregate_encode_kernel<kPlanes, kWaves>), grid, block, 0, s, addr, h, out);
-    return launched();
+    return launch(aggregate_encode_kernel<kPlanes, kWaves>, grid, block, 0, s, addr, h, out);
 }
 
 template <int kPlanes>
 dlion_status launch_encode_planes(const FlatAddr &addr, const Hyper &h, const DeltaOut &out, hipStream_t s)
 {
-    const int env_waves = env_int("DLION_SLICED_WAVES");
+    const int env_waves = tuning().sliced_waves;
     // 16 waves from N = 64 on (N = 256, d = 1 G: vote 5.15 -> 5.03 ms, average 6.00 -> 5.49 ms; N = 64:
     // 1.48 -> 1.44 and 1.69 -> 1.60 ms; at N = 32 and below 8 waves are the better size)
     const int waves = env_waves > 0 ? env_waves
@@ -426,10 +481,9 @@ dlion_status launch_global_lion_unroll(const FlatAddr &addr, const Hyper &h, uin
     const size_t lds = lds_reservation(shape.blocks_per_cu);
     const dim3 grid(static_cast<uint32_t>(addr.total_tiles)), block(kLanes);
     if (shape.unroll >= 2 && h.N >= 2)
-        hipLaunchKernelGGL((global_lion_kernel<GT, 2>), grid, block, lds, s, addr, h, sign_bits);
+        return launch(global_lion_kernel<GT, 2>, grid, block, lds, s, addr, h, sign_bits);
     else
-        hipLaunchKernelGGL((global_lion_kernel<GT, 1>), grid, block, lds, s, addr, h, sign_bits);
-    return launched();
+        return launch(global_lion_kernel<GT, 1>, grid, block, lds, s, addr, h, sign_bits);
 }
 
 // ------------------------------------------------------------------ validation
@@ -477,10 +531,11 @@ FlatAddr flat_addr(float *x, float *m, int64_t m_stride, const void *g, int64_t 
     a.p.packed = packed;
     a.p.packed_stride = packed_stride;
     a.p.counts = counts;
-    a.p.carry = counts;
     a.p.counts_end = d;
     a.total_tiles = tiles_for(d);
     a.first_tile = 0;
+    a.ws = nullptr;
+    a.ws_plane = 0;
     return a;
 }
 
@@ -537,6 +592,8 @@ SegAddr seg_addr(const dlion_seg *segs_dev, int32_t K, int64_t total_tiles, uint
     a.K = K;
     a.total_tiles = total_tiles;
     a.first_tile = 0;
+    a.ws = nullptr;
+    a.ws_plane = 0;
     a.packed = packed;
     a.packed_stride = packed_stride;
     a.counts = counts;
@@ -613,12 +670,22 @@ dlion_status dlion_aggregate_apply(float *x, const uint64_t *packed, int64_t pac
     return launch_aggregate(a, h, true, counts_or_null != nullptr, static_cast<hipStream_t>(stream));
 }
 
+int64_t dlion_step_mt_workspace_bytes(int64_t total_tiles, int32_t N)
+{
+    if (total_tiles <= 0 || total_tiles > kMaxTiles || N < 1 || N > DLION_MAX_WORKERS)
+        return 0;
+    const int passes = default_passes(N, total_tiles);
+    if (passes <= 1)
+        return 0;
+    int64_t block = default_block_tiles();
+    if (block <= 0 || block > total_tiles)
+        block = total_tiles;
+    return block * ws_bytes_per_tile(workspace_carry(N, passes), passes);
+}
+
 int64_t dlion_step_workspace_bytes(int64_t d, int32_t N)
 {
-    if (d <= 0 || N < kPassMinN || tiles_for(d) < kPassMinTiles)
-        return 0;
-    const int64_t tiles = tiles_for(d) < kPassTiles ? tiles_for(d) : kPassTiles;
-    return tiles * kTile * static_cast<int64_t>(sizeof(uint16_t));
+    return d > 0 ? dlion_step_mt_workspace_bytes(tiles_for(d), N) : 0;
 }
 
 dlion_status dlion_step(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
@@ -652,8 +719,8 @@ dlion_status dlion_step_ws(float *x, float *m, int64_t m_stride, const void *g, 
     h.xcd_quads = step_quads(rows_split_lines(m, m_stride, 4, N) || rows_split_lines(g, g_stride, grad_size(g_dtype), N));
     const FlatAddr a = flat_addr(x, m, m_stride, g, g_stride, d, packed_or_null, packed_stride, counts_or_null);
     Workspace ws;
-    ws.base = static_cast<uint16_t *>(workspace_or_null);
-    ws.coords = workspace_bytes / static_cast<int64_t>(sizeof(uint16_t));
+    ws.base = workspace_or_null;
+    ws.bytes = workspace_bytes;
     return launch_step<true>(a, h, g_dtype, packed_or_null != nullptr, counts_or_null != nullptr,
                              static_cast<hipStream_t>(stream), ws);
 }
@@ -759,9 +826,21 @@ dlion_status dlion_step_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev
                            float lambda, uint64_t *packed_or_null, int64_t packed_stride,
                            uint16_t *counts_or_null, void *stream)
 {
+    return dlion_step_mt_ws(segs_host, segs_dev, K, g_dtype, N, mode, beta1, beta2, lr, lambda, packed_or_null,
+                            packed_stride, counts_or_null, nullptr, 0, stream);
+}
+
+dlion_status dlion_step_mt_ws(const dlion_seg *segs_host, const dlion_seg *segs_dev, int32_t K,
+                              dlion_dtype g_dtype, int32_t N, dlion_mode mode, float beta1, float beta2,
+                              float lr, float lambda, uint64_t *packed_or_null, int64_t packed_stride,
+                              uint16_t *counts_or_null, void *workspace_or_null, int64_t workspace_bytes,
+                              void *stream)
+{
     if (!dtype_ok(g_dtype) || !mode_ok(mode))
         return DLION_EINVAL;
-    if (!aligned_to(counts_or_null, 2))
+    if (workspace_bytes < 0 || (workspace_or_null == nullptr && workspace_bytes != 0))
+        return DLION_EINVAL;
+    if (!aligned_to(counts_or_null, 2) || !aligned_to(workspace_or_null, 16))
         return DLION_EALIGN;
     int64_t words, tiles;
     bool split;
@@ -772,8 +851,11 @@ dlion_status dlion_step_mt(const dlion_seg *segs_host, const dlion_seg *segs_dev
     h.stream_counts = counts_or_null ? counts_exceed_cache(64 * words) : 0;
     h.xcd_quads = step_quads(split);
     const SegAddr a = seg_addr(segs_dev, K, tiles, packed_or_null, packed_stride, counts_or_null);
+    Workspace ws;
+    ws.base = workspace_or_null;
+    ws.bytes = workspace_bytes;
     return launch_step<true>(a, h, g_dtype, packed_or_null != nullptr, counts_or_null != nullptr,
-                             static_cast<hipStream_t>(stream));
+                             static_cast<hipStream_t>(stream), ws);
 }
 
 // ----------------------------------------------------------------------- wider rows
@@ -820,17 +902,16 @@ dlion_status dlion_apply_encoded(float *x, const uint64_t *delta, int64_t delta_
     // resident waves per compute unit, capped like the fused step's (a wave has 4 KB of x and a
     // line of every plane in flight): N = 256, d = 1 G, vote (2 planes) uncapped 80.4 %, 12 waves
     // 84.5 %, 16 waves 82.7 %; average (9 planes) uncapped 75.1 %, 12 waves 76.2 %, 16 waves 79.1 %
-    const int env_k = env_int("DLION_APPLY_BLOCKS");      // tuning
+    const int env_k = tuning().apply_blocks;
     const size_t lds = lds_reservation(env_k >= 0 ? env_k : (planes <= 2 ? 12 : 16));
     if (planes <= 2)
-        hipLaunchKernelGGL(apply_encoded_kernel<2>, grid, block, lds, s, a, h, in);
+        return launch(apply_encoded_kernel<2>, grid, block, lds, s, a, h, in);
     else if (planes <= 5)
-        hipLaunchKernelGGL(apply_encoded_kernel<5>, grid, block, lds, s, a, h, in);
+        return launch(apply_encoded_kernel<5>, grid, block, lds, s, a, h, in);
     else if (planes <= 9)
-        hipLaunchKernelGGL(apply_encoded_kernel<9>, grid, block, lds, s, a, h, in);
+        return launch(apply_encoded_kernel<9>, grid, block, lds, s, a, h, in);
     else
-        hipLaunchKernelGGL(apply_encoded_kernel<16>, grid, block, lds, s, a, h, in);
-    return launched();
+        return launch(apply_encoded_kernel<16>, grid, block, lds, s, a, h, in);
 }
 
 dlion_status dlion_worker_step_pw(float *m, int64_t m_stride, const void *g, int64_t g_stride,
@@ -907,6 +988,37 @@ const char *dlion_status_str(dlion_status s)
     return "unknown status";
 }
 
-int dlion_version(void) { return 101; }
+int dlion_version(void) { return 200; }
+
+void dlion_tuning_defaults(dlion_tuning *t)
+{
+    if (t) {
+        const dlion_tuning d = {-1, -1, -1, -1, -1, -1, -1, -1, -1};
+        *t = d;
+    }
+}
+
+dlion_status dlion_set_tuning(const dlion_tuning *t)
+{
+    dlion_tuning v;
+    dlion_tuning_defaults(&v);
+    if (t)
+        v = *t;
+    const bool unroll_ok = v.unroll == -1 || v.unroll == 1 || v.unroll == 2 || v.unroll == 4 || v.unroll == 8;
+    const bool waves_ok = v.sliced_waves == -1 || v.sliced_waves == 1 || v.sliced_waves == 8 || v.sliced_waves == 16;
+    if (!unroll_ok || !waves_ok || v.blocks_per_cu < -1 || v.blocks_per_cu > 64 || v.pass_workers < -1 ||
+        v.step_quads < -1 || v.step_quads > 1 || v.sliced_min_workers < -1 || v.apply_blocks < -1 ||
+        v.apply_blocks > 64 || v.block_tiles < -1 || v.block_tiles > kMaxTiles)
+        return DLION_EINVAL;
+    v.reserved = -1;
+    g_tuning = v;
+    return DLION_OK;
+}
+
+void dlion_get_tuning(dlion_tuning *t)
+{
+    if (t)
+        *t = g_tuning;
+}
 
 }  // extern "C"

@@ -29,13 +29,7 @@
 
 namespace dlion {
 
-// Launch-shape knobs (compile-time; the defaults are the measured best on MI355X).
-#ifndef DLION_SUBTILES
-#define DLION_SUBTILES 1        // 256-coordinate sub-tiles a wave handles together
-#endif
-#ifndef DLION_WAVES_PER_BLOCK
-#define DLION_WAVES_PER_BLOCK 1
-#endif
+// Compile-time switches (the defaults are the measured best on MI355X).
 #ifndef DLION_XCD_QUADS
 #define DLION_XCD_QUADS 1       // readers of packed rows: 4 consecutive tiles on one XCD
 #endif
@@ -46,19 +40,25 @@ namespace dlion {
 #define DLION_NT_STORE 1        // streaming stores of m
 #endif
 
-constexpr int kLanes = 64;
-constexpr int kVec = 4;                       // coordinates per lane per sub-tile on the vector path
-constexpr int kSubTile = kLanes * kVec;       // 256 coordinates = 4 packed words
-constexpr int kWordsPerSub = kSubTile / 64;
-constexpr int kSubs = DLION_SUBTILES;
-constexpr int kTile = kSubTile * kSubs;       // coordinates one wave owns
-constexpr int kWavesPerBlock = DLION_WAVES_PER_BLOCK;
-constexpr int kBlock = kLanes * kWavesPerBlock;
+constexpr int kLanes = 64;                    // one-wave workgroups everywhere on the worker/fused path
+constexpr int kVec = 4;                       // coordinates per lane on the vector path
+constexpr int kTile = kLanes * kVec;          // 256 coordinates = 4 packed words: what one wave owns
+constexpr int kWordsPerTile = kTile / 64;
 
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
+
+// How the votes of the workers that earlier launches handled reach the current one, when a step
+// over many workers runs as several launches over a few workers each (Hyper::carry).
+enum Carry : int32_t {
+    kCarryNone = 0,
+    kCarryCounts = 1,    // running count in the caller's counts array (uint16, indexed by coordinate)
+    kCarryRunning = 2,   // running count in the workspace, private to the lane: 4 x uint16 per lane and tile
+    kCarryNibbles = 3,   // one plane per launch in the workspace: the lane's 4 partial counts (each <= 15)
+                         // are the nibbles of one uint16; the last launch adds the planes up
+};
 
 struct Hyper {
     float beta1, omb1, beta2, omb2;  // omb = 1.0f - beta, formed on the host in fp32
@@ -68,10 +68,11 @@ struct Hyper {
     int32_t mode;     // dlion_mode
     int32_t stream_counts;   // counts array too large to stay cached: write it with streaming stores
     // The worker/fused kernels walk workers [worker_begin, worker_end) of the N: a step over many
-    // workers may be run as several launches over a few workers each.  counts_in: start from the
-    // counts the earlier launches left in the counts array instead of from zero.
+    // workers may be run as several launches over a few workers each.
     int32_t worker_begin, worker_end;
-    int32_t counts_in;
+    int32_t carry;       // Carry
+    int32_t carry_in;    // counts / running: 1 = start from the stored count; nibbles: planes to add up
+    int32_t carry_out;   // running: 1 = store the count; nibbles: 1 + plane to write; else 0
     int32_t xcd_quads;   // worker/fused kernels: 4 consecutive tiles per XCD (quad_tile_index)
     const float *beta1_pw;   // per-worker coefficients (device arrays of N floats), or null:
     const float *beta2_pw;   // then beta1/beta2 above are shared by all workers
@@ -92,10 +93,16 @@ struct Problem {
     uint64_t *packed;       // worker 0, first word of this tensor (may be null)
     int64_t packed_stride;
     uint16_t *counts;       // first count of this tensor (may be null)
-    const uint16_t *carry;  // counts_in: the votes left by the launches over the earlier workers, indexed
-                            // like counts (the counts array itself, or a workspace)
     int64_t counts_end;     // counts[0..counts_end) may be written: numel (flat buffer) or
                             // numel rounded up to a whole word (tensor list)
+};
+
+// Where a tile's votes wait between the launches of one step (kCarryRunning, kCarryNibbles): the
+// launches of one block of tiles [first_tile, total_tiles) share ws, laid out by tile within the
+// block and by lane within the tile, so that every lane reads back exactly what it wrote.
+struct CarrySlot {
+    uint16_t *tile;     // this tile's first element (null when the step has no workspace carry)
+    int64_t plane;      // kCarryNibbles: uint16 elements from one plane to the next
 };
 
 // ---------------------------------------------------------------- addressing
@@ -104,6 +111,8 @@ struct FlatAddr {
     Problem p;
     int64_t total_tiles;
     int64_t first_tile;    // worker/fused kernels: the launch covers tiles [first_tile, total_tiles)
+    uint16_t *ws;          // workspace carry of this block of tiles, or null
+    int64_t ws_plane;
     __device__ int64_t resolve(int64_t tile, Problem &out) const
     {
         out = p;
@@ -119,6 +128,8 @@ struct SegAddr {
     int32_t K;
     int64_t total_tiles;
     int64_t first_tile;
+    uint16_t *ws;
+    int64_t ws_plane;
     uint64_t *packed;
     int64_t packed_stride;
     uint16_t *counts;
@@ -142,11 +153,22 @@ struct SegAddr {
         out.packed = packed ? packed + s.word_begin : nullptr;
         out.packed_stride = packed_stride;
         out.counts = counts ? counts + 64 * s.word_begin : nullptr;
-        out.carry = out.counts;
         out.counts_end = ((s.numel + 63) >> 6) << 6;
         return tile - s.tile_begin;
     }
 };
+
+// uint16 elements of workspace one tile takes per plane (kCarryNibbles) / in all (kCarryRunning)
+constexpr int kNibbleCarryPerTile = kLanes;
+constexpr int kRunningCarryPerTile = kLanes * kVec;
+
+template <class Addr> __device__ __forceinline__ CarrySlot carry_slot(const Addr &addr, int64_t tile, const Hyper &h)
+{
+    CarrySlot c = {nullptr, addr.ws_plane};
+    if (addr.ws)
+        c.tile = addr.ws + (tile - addr.first_tile) * (h.carry == kCarryRunning ? kRunningCarryPerTile : kNibbleCarryPerTile);
+    return c;
+}
 
 // Tile numbering for kernels that READ bit-packed rows.  A tile needs only 32 bytes of each
 // packed row, a quarter of a 128-byte line, and every XCD has its own L2: with the plain
@@ -165,18 +187,14 @@ __device__ __forceinline__ int64_t quad_tile_index()
     return block;
 }
 
-template <int kWaves = kWavesPerBlock> __device__ __forceinline__ int64_t wave_tile_index()
+// Plain numbering: workgroup b owns tile b.  Workgroups are handed to the 8 XCDs round-robin
+// (workgroup b runs on XCD b % 8), so all XCDs work inside the same narrow window of addresses.
+// That is what DRAM page locality wants: renumbering so that every XCD walks its own contiguous
+// eighth of the tiles costs 15 % of the bandwidth, and grouping 4 consecutive tiles per XCD (to
+// merge the 32-byte packed writes in one L2) changes nothing.
+__device__ __forceinline__ int64_t wave_tile_index()
 {
-    // blockIdx and the wave number are uniform across the wavefront; say so, so
-    // that everything derived from the tile index stays in scalar registers.
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b % 8), so
-    // with the plain numbering all XCDs work inside the same narrow window of addresses.
-    // That is what DRAM page locality wants: renumbering so that every XCD walks its own
-    // contiguous eighth of the tiles costs 15 % of the bandwidth, and grouping 4 consecutive
-    // tiles per XCD (to merge the 32-byte packed writes in one L2) changes nothing.
-    const uint32_t block = blockIdx.x;
-    return (int64_t)block * kWaves + wave;
+    return blockIdx.x;     // uniform across the wavefront: everything derived from it stays scalar
 }
 
 // Cache policy of the small per-coordinate arrays.  x is touched once per step: streaming
@@ -389,15 +407,15 @@ __device__ __forceinline__ uint64_t row_gather_nibbles(uint32_t nibble, int lane
 // ---------------------------------------------------------------- fused / worker tile
 // kApply : read x, aggregate, write x (fused step); else worker step only.
 // kPacked: write packed words.   kCounts: write counts.
-// Vector path over kR full sub-tiles starting at sub-tile `t`: the loads of kUnroll workers
-// x kR sub-tiles are issued back to back before any arithmetic.
-template <typename GT, int kUnroll, int kR, bool kApply, bool kPacked, bool kCounts>
-__device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t, int lane, const Hyper &h,
-                                                     uint64_t *stage)
+// Vector path over one full tile: the loads of kUnroll workers are issued back to back before
+// any arithmetic.
+template <typename GT, int kUnroll, bool kApply, bool kPacked, bool kCounts>
+__device__ __forceinline__ void step_tile_vector(const Problem &p, int64_t t, int lane, const Hyper &h,
+                                                 const CarrySlot &carry, uint64_t *stage)
 {
-    const int64_t j0 = t * kSubTile + lane * kVec;
+    const int64_t j0 = t * kTile + lane * kVec;
     // packed words wait in `stage` (LDS, private to the wave) until kPackWorkers workers are done
-    constexpr int kPackWorkers = kLanes / (kR * kWordsPerSub);
+    constexpr int kPackWorkers = kLanes / kWordsPerTile;
     int staged = 0;                                        // uniform
     auto flush_packed = [&](int i_next) {                  // workers [i_next - staged, i_next)
         if (!kPacked)
@@ -407,32 +425,38 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        const int worker = lane / (kR * kWordsPerSub);     // lane -> (worker, word of the kR sub-tiles)
-        const int word = lane % (kR * kWordsPerSub);
+        const int worker = lane / kWordsPerTile;           // lane -> (worker, word of the tile)
+        const int word = lane % kWordsPerTile;
         if (worker < staged) {
             const uint64_t v = stage[lane];
-            p.packed[(int64_t)(i_next - staged + worker) * p.packed_stride + t * kWordsPerSub + word] = v;
+            p.packed[(int64_t)(i_next - staged + worker) * p.packed_stride + t * kWordsPerTile + word] = v;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         staged = 0;
     };
-    f32x4 xv[kR];
-    if (kApply) {
-#pragma unroll
-        for (int r = 0; r < kR; ++r)
-            xv[r] = x_load4(p.x + j0 + r * kSubTile);
-    }
-    uint32_t cnt[kR][4];
-#pragma unroll
-    for (int r = 0; r < kR; ++r) {
-        cnt[r][0] = cnt[r][1] = cnt[r][2] = cnt[r][3] = 0;
-        if (h.counts_in) {                              // uniform
-            const u16x4 c = counts_load4(p.carry + j0 + r * kSubTile);
-            cnt[r][0] = c.x;
-            cnt[r][1] = c.y;
-            cnt[r][2] = c.z;
-            cnt[r][3] = c.w;
+    f32x4 xv;
+    if (kApply)
+        xv = x_load4(p.x + j0);
+    // votes of the workers that earlier launches of this step handled (all branches uniform)
+    uint32_t cnt0 = 0, cnt1 = 0, cnt2 = 0, cnt3 = 0;
+    if (h.carry == kCarryCounts) {
+        if (h.carry_in) {
+            const u16x4 c = counts_load4(p.counts + j0);
+            cnt0 = c.x, cnt1 = c.y, cnt2 = c.z, cnt3 = c.w;
+        }
+    } else if (h.carry == kCarryRunning) {
+        if (h.carry_in) {
+            const u16x4 c = *reinterpret_cast<const u16x4 *>(carry.tile + lane * kVec);
+            cnt0 = c.x, cnt1 = c.y, cnt2 = c.z, cnt3 = c.w;
+        }
+    } else if (h.carry == kCarryNibbles) {
+        for (int pl = 0; pl < h.carry_in; ++pl) {
+            const uint32_t v = carry.tile[pl * carry.plane + lane];
+            cnt0 += v & 15u;
+            cnt1 += (v >> 4) & 15u;
+            cnt2 += (v >> 8) & 15u;
+            cnt3 += v >> 12;
         }
     }
     const int N = h.N, i_begin = h.worker_begin, i_end = h.worker_end;
@@ -452,7 +476,7 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
         return k;
     };
 
-    auto one_worker = [&](int i, int r, f32x4 mv, f32x4 gv) {
+    auto one_worker = [&](int i, f32x4 mv, f32x4 gv) {
         const Coef k = coef_of(i);
         float m0 = mv.x, m1 = mv.y, m2 = mv.z, m3 = mv.w;
         const bool b0 = lion_worker(m0, gv.x, k);
@@ -463,99 +487,115 @@ __device__ __forceinline__ void step_subtiles_vector(const Problem &p, int64_t t
         mv.y = m1;
         mv.z = m2;
         mv.w = m3;
-        row_store4(mv, p.m + (int64_t)i * p.m_stride + j0 + r * kSubTile);
-        cnt[r][0] += b0;
-        cnt[r][1] += b1;
-        cnt[r][2] += b2;
-        cnt[r][3] += b3;
+        row_store4(mv, p.m + (int64_t)i * p.m_stride + j0);
+        cnt0 += b0;
+        cnt1 += b1;
+        cnt2 += b2;
+        cnt3 += b3;
         if (kPacked) {
             const uint32_t nib = (b0 ? 1u : 0u) | (b1 ? 2u : 0u) | (b2 ? 4u : 0u) | (b3 ? 8u : 0u);
             const uint64_t word = row_gather_nibbles(nib, lane);
             // staged in LDS: one store instruction then writes the words of up to kPackWorkers
             // workers (a store by 4 scattered lanes per worker costs the kernel 10 % of its time)
             if ((lane & 15) == 0)
-                stage[(staged * kR + r) * kWordsPerSub + (lane >> 4)] = word;
-            if (r == kR - 1 && ++staged == kPackWorkers)
+                stage[staged * kWordsPerTile + (lane >> 4)] = word;
+            if (++staged == kPackWorkers)
                 flush_packed(i + 1);
         }
     };
 
     for (int c0 = i_begin; c0 < i_end;) {
-    // workers [c0, c1): the rest of c0's block of 64
-    const int c1 = min(i_end, (c0 | 63) + 1);
-    if (h.beta1_pw) {                                   // uniform
-        const int w = (c0 & ~63) + lane;
-        pw_beta1 = w < N ? __float_as_uint(h.beta1_pw[w]) : 0u;
-        pw_beta2 = w < N ? __float_as_uint(h.beta2_pw[w]) : 0u;
-    }
-    int i = c0;
-    for (; i + kUnroll <= c1; i += kUnroll) {
-        f32x4 mv[kUnroll][kR], gv[kUnroll][kR];
+        // workers [c0, c1): the rest of c0's block of 64
+        const int c1 = min(i_end, (c0 | 63) + 1);
+        if (h.beta1_pw) {                                   // uniform
+            const int w = (c0 & ~63) + lane;
+            pw_beta1 = w < N ? __float_as_uint(h.beta1_pw[w]) : 0u;
+            pw_beta2 = w < N ? __float_as_uint(h.beta2_pw[w]) : 0u;
+        }
+        int i = c0;
+        for (; i + kUnroll <= c1; i += kUnroll) {
+            f32x4 mv[kUnroll], gv[kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-#pragma unroll
-            for (int r = 0; r < kR; ++r) {
-                mv[u][r] = row_load4(p.m + (int64_t)(i + u) * p.m_stride + j0 + r * kSubTile);
-                gv[u][r] = Grad<GT>::load4(p.g, (int64_t)(i + u) * p.g_stride + j0 + r * kSubTile);
+            for (int u = 0; u < kUnroll; ++u) {
+                mv[u] = row_load4(p.m + (int64_t)(i + u) * p.m_stride + j0);
+                gv[u] = Grad<GT>::load4(p.g, (int64_t)(i + u) * p.g_stride + j0);
             }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+                one_worker(i + u, mv[u], gv[u]);
         }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-#pragma unroll
-            for (int r = 0; r < kR; ++r)
-                one_worker(i + u, r, mv[u][r], gv[u][r]);
+        for (; i < c1; ++i) {
+            const f32x4 mv = row_load4(p.m + (int64_t)i * p.m_stride + j0);
+            const f32x4 gv = Grad<GT>::load4(p.g, (int64_t)i * p.g_stride + j0);
+            one_worker(i, mv, gv);
         }
-    }
-    for (; i < c1; ++i) {
-        f32x4 mv[kR], gv[kR];
-#pragma unroll
-        for (int r = 0; r < kR; ++r) {
-            mv[r] = row_load4(p.m + (int64_t)i * p.m_stride + j0 + r * kSubTile);
-            gv[r] = Grad<GT>::load4(p.g, (int64_t)i * p.g_stride + j0 + r * kSubTile);
-        }
-#pragma unroll
-        for (int r = 0; r < kR; ++r)
-            one_worker(i, r, mv[r], gv[r]);
-    }
-    c0 = c1;
+        c0 = c1;
     }
     if (kPacked && staged > 0)
         flush_packed(i_end);
 
-#pragma unroll
-    for (int r = 0; r < kR; ++r) {
-        if (kApply) {
-            xv[r].x = lion_apply(xv[r].x, aggregate_votes(cnt[r][0], h), h);
-            xv[r].y = lion_apply(xv[r].y, aggregate_votes(cnt[r][1], h), h);
-            xv[r].z = lion_apply(xv[r].z, aggregate_votes(cnt[r][2], h), h);
-            xv[r].w = lion_apply(xv[r].w, aggregate_votes(cnt[r][3], h), h);
-            x_store4(xv[r], p.x + j0 + r * kSubTile);
-        }
-        if (kCounts) {
+    if (kApply) {
+        xv.x = lion_apply(xv.x, aggregate_votes(cnt0, h), h);
+        xv.y = lion_apply(xv.y, aggregate_votes(cnt1, h), h);
+        xv.z = lion_apply(xv.z, aggregate_votes(cnt2, h), h);
+        xv.w = lion_apply(xv.w, aggregate_votes(cnt3, h), h);
+        x_store4(xv, p.x + j0);
+    }
+    if (kCounts) {
+        u16x4 c;
+        c.x = static_cast<uint16_t>(cnt0);
+        c.y = static_cast<uint16_t>(cnt1);
+        c.z = static_cast<uint16_t>(cnt2);
+        c.w = static_cast<uint16_t>(cnt3);
+        COUNTS_STORE4(c, p.counts + j0);
+    }
+    // hand the votes on to the next launch of this step: read back soon, so ordinary stores
+    if (h.carry_out) {                                      // uniform
+        if (h.carry == kCarryRunning) {
             u16x4 c;
-            c.x = static_cast<uint16_t>(cnt[r][0]);
-            c.y = static_cast<uint16_t>(cnt[r][1]);
-            c.z = static_cast<uint16_t>(cnt[r][2]);
-            c.w = static_cast<uint16_t>(cnt[r][3]);
-            COUNTS_STORE4(c, p.counts + j0 + r * kSubTile);
+            c.x = static_cast<uint16_t>(cnt0);
+            c.y = static_cast<uint16_t>(cnt1);
+            c.z = static_cast<uint16_t>(cnt2);
+            c.w = static_cast<uint16_t>(cnt3);
+            *reinterpret_cast<u16x4 *>(carry.tile + lane * kVec) = c;
+        } else if (h.carry == kCarryNibbles) {
+            carry.tile[(h.carry_out - 1) * carry.plane + lane] =
+                static_cast<uint16_t>(cnt0 | (cnt1 << 4) | (cnt2 << 8) | (cnt3 << 12));
         }
     }
 }
 
-// Guarded path: lane l owns coordinates 64k+l of the tile; every access checks
-// j < numel; a 64-lane ballot is already a canonical packed word.
+// Guarded path (ragged last tile of a tensor): lane l owns coordinates 64k+l, k = 0..3, of the
+// tile; every access checks j < numel; a 64-lane ballot is already a canonical packed word.  The
+// lane's four counts travel in the 16-bit fields of one 64-bit register.
 template <typename GT, bool kApply, bool kPacked, bool kCounts>
-__device__ __forceinline__ void step_subtile_guarded(const Problem &p, int64_t t, int lane, const Hyper &h)
+__device__ __forceinline__ void step_tile_guarded(const Problem &p, int64_t t, int lane, const Hyper &h,
+                                                  const CarrySlot &carry)
 {
     const int64_t W = (p.numel + 63) >> 6;
+    uint64_t cnt = 0;                                       // field k = votes for coordinate 64k + lane
+    if (h.carry == kCarryRunning) {
+        if (h.carry_in) {
+            const u16x4 c = *reinterpret_cast<const u16x4 *>(carry.tile + lane * kVec);
+            cnt = static_cast<uint64_t>(c.x) | (static_cast<uint64_t>(c.y) << 16) |
+                  (static_cast<uint64_t>(c.z) << 32) | (static_cast<uint64_t>(c.w) << 48);
+        }
+    } else if (h.carry == kCarryNibbles) {
+        for (int pl = 0; pl < h.carry_in; ++pl) {
+            const uint64_t v = carry.tile[pl * carry.plane + lane];
+            cnt += (v & 15u) | (((v >> 4) & 15u) << 16) | (((v >> 8) & 15u) << 32) | ((v >> 12) << 48);
+        }
+    }
 #pragma unroll 1
-    for (int k = 0; k < kWordsPerSub; ++k) {
-        const int64_t w = t * kWordsPerSub + k;
+    for (int k = 0; k < kWordsPerTile; ++k) {
+        const int64_t w = t * kWordsPerTile + k;
         if (w >= W)
             break;                                   // uniform: whole wave leaves together
         const int64_t j = w * 64 + lane;
         const bool valid = j < p.numel;
-        uint32_t cnt = (h.counts_in && valid) ? p.carry[j] : 0u;
+        uint32_t c = static_cast<uint32_t>(cnt >> (16 * k)) & 0xFFFFu;
+        if (h.carry == kCarryCounts && h.carry_in && valid)
+            c = p.counts[j];
         for (int i = h.worker_begin; i < h.worker_end; ++i) {
             bool plus = false;
             if (valid) {
@@ -565,7 +605,7 @@ __device__ __forceinline__ void step_subtile_guarded(const Problem &p, int64_t t
                 plus = lion_worker(mv, gv, worker_coef(h, i));
                 *mp = mv;
             }
-            cnt += plus;
+            c += plus;
             if (kPacked) {
                 const uint64_t word = __ballot(plus);   // invalid lanes contribute 0: tail bits zero
                 if (lane == 0)
@@ -573,39 +613,42 @@ __device__ __forceinline__ void step_subtile_guarded(const Problem &p, int64_t t
             }
         }
         if (kApply && valid)
-            p.x[j] = lion_apply(p.x[j], aggregate_votes(cnt, h), h);
+            p.x[j] = lion_apply(p.x[j], aggregate_votes(c, h), h);
         if (kCounts && j < p.counts_end)
-            p.counts[j] = static_cast<uint16_t>(cnt);   // 0 past numel (tensor-list padding)
+            p.counts[j] = static_cast<uint16_t>(c);     // 0 past numel (tensor-list padding)
+        cnt = (cnt & ~(static_cast<uint64_t>(0xFFFFu) << (16 * k))) | (static_cast<uint64_t>(c) << (16 * k));
+    }
+    if (h.carry_out) {
+        if (h.carry == kCarryRunning) {
+            u16x4 c;
+            c.x = static_cast<uint16_t>(cnt);
+            c.y = static_cast<uint16_t>(cnt >> 16);
+            c.z = static_cast<uint16_t>(cnt >> 32);
+            c.w = static_cast<uint16_t>(cnt >> 48);
+            *reinterpret_cast<u16x4 *>(carry.tile + lane * kVec) = c;
+        } else if (h.carry == kCarryNibbles) {
+            carry.tile[(h.carry_out - 1) * carry.plane + lane] = static_cast<uint16_t>(
+                (cnt & 15u) | (((cnt >> 16) & 15u) << 4) | (((cnt >> 32) & 15u) << 8) | (((cnt >> 48) & 15u) << 12));
+        }
     }
 }
 
 template <typename GT, int kUnroll, bool kApply, bool kPacked, bool kCounts, class Addr>
-__global__ __launch_bounds__(kBlock) void step_kernel(Addr addr, Hyper h)
+__global__ __launch_bounds__(kLanes) void step_kernel(Addr addr, Hyper h)
 {
-    const int64_t tile = addr.first_tile + ((kWavesPerBlock == 1 && h.xcd_quads) ? quad_tile_index() : wave_tile_index());
+    const int64_t tile = addr.first_tile + (h.xcd_quads ? quad_tile_index() : wave_tile_index());
     if (tile >= addr.total_tiles)
         return;
-    const int lane = threadIdx.x & 63;
-    // dynamic LDS: reserved to cap the resident waves; its first 512 bytes per wave stage packed words
+    const int lane = threadIdx.x;
+    // dynamic LDS: reserved to cap the resident waves; its first 512 bytes stage packed words
     extern __shared__ uint64_t step_lds[];
-    uint64_t *stage = step_lds + (threadIdx.x >> 6) * kLanes;
     Problem p;
-    const int64_t t = addr.resolve(tile, p) * kSubs;      // first sub-tile of this wave
-    if ((t + kSubs) * kSubTile <= p.numel) {
-        step_subtiles_vector<GT, kUnroll, kSubs, kApply, kPacked, kCounts>(p, t, lane, h, stage);
-        return;
-    }
-    // ragged end of a tensor
-#pragma unroll 1
-    for (int r = 0; r < kSubs; ++r) {
-        const int64_t sub = t + r;
-        if (sub * kSubTile >= p.numel)
-            break;
-        if (kSubs > 1 && (sub + 1) * kSubTile <= p.numel)
-            step_subtiles_vector<GT, kUnroll, 1, kApply, kPacked, kCounts>(p, sub, lane, h, stage);
-        else
-            step_subtile_guarded<GT, kApply, kPacked, kCounts>(p, sub, lane, h);
-    }
+    const int64_t t = addr.resolve(tile, p);              // tile within its tensor
+    const CarrySlot carry = carry_slot(addr, tile, h);
+    if ((t + 1) * kTile <= p.numel)
+        step_tile_vector<GT, kUnroll, kApply, kPacked, kCounts>(p, t, lane, h, carry, step_lds);
+    else if (t * kTile < p.numel)                         // ragged end of a tensor
+        step_tile_guarded<GT, kApply, kPacked, kCounts>(p, t, lane, h, carry);
 }
 
 // A nibble's four bits, one per byte (bit 0 of each byte): 24-bit multiply, full rate.
@@ -621,7 +664,7 @@ __device__ __forceinline__ uint32_t nibble_to_bytes(uint32_t nib)
 template <bool kApply, bool kCounts>
 __device__ __forceinline__ void agg_subtile_vector(const Problem &p, int64_t t, int lane, const Hyper &h)
 {
-    const uint32_t *half = reinterpret_cast<const uint32_t *>(p.packed + t * kWordsPerSub + (lane >> 4)) +
+    const uint32_t *half = reinterpret_cast<const uint32_t *>(p.packed + t * kWordsPerTile + (lane >> 4)) +
                            ((lane >> 3) & 1);
     const int shift = (lane & 7) * 4;
     const int64_t stride32 = p.packed_stride * 2;
@@ -647,7 +690,7 @@ __device__ __forceinline__ void agg_subtile_vector(const Problem &p, int64_t t, 
         cnt2 += (acc >> 16) & 0xFFu;
         cnt3 += acc >> 24;
     }
-    const int64_t j0 = t * kSubTile + lane * kVec;
+    const int64_t j0 = t * kTile + lane * kVec;
     if (kApply) {
         f32x4 xv = x_load4(p.x + j0);
         xv.x = lion_apply(xv.x, aggregate_votes(cnt0, h), h);
@@ -672,8 +715,8 @@ __device__ __forceinline__ void agg_subtile_guarded(const Problem &p, int64_t t,
 {
     const int64_t W = (p.numel + 63) >> 6;
 #pragma unroll 1
-    for (int k = 0; k < kWordsPerSub; ++k) {
-        const int64_t w = t * kWordsPerSub + k;
+    for (int k = 0; k < kWordsPerTile; ++k) {
+        const int64_t w = t * kWordsPerTile + k;
         if (w >= W)
             break;
         const int64_t j = w * 64 + lane;
@@ -693,24 +736,18 @@ __device__ __forceinline__ void agg_subtile_guarded(const Problem &p, int64_t t,
 }
 
 template <bool kApply, bool kCounts, class Addr>
-__global__ __launch_bounds__(kBlock) void aggregate_kernel(Addr addr, Hyper h)
+__global__ __launch_bounds__(kLanes) void aggregate_kernel(Addr addr, Hyper h)
 {
-    const int64_t tile = kWavesPerBlock == 1 ? quad_tile_index() : wave_tile_index();
+    const int64_t tile = quad_tile_index();
     if (tile >= addr.total_tiles)
         return;
-    const int lane = threadIdx.x & 63;
+    const int lane = threadIdx.x;
     Problem p;
-    const int64_t t = addr.resolve(tile, p) * kSubs;
-#pragma unroll 1
-    for (int r = 0; r < kSubs; ++r) {
-        const int64_t sub = t + r;
-        if (sub * kSubTile >= p.numel)
-            break;
-        if ((sub + 1) * kSubTile <= p.numel)
-            agg_subtile_vector<kApply, kCounts>(p, sub, lane, h);
-        else
-            agg_subtile_guarded<kApply, kCounts>(p, sub, lane, h);
-    }
+    const int64_t t = addr.resolve(tile, p);
+    if ((t + 1) * kTile <= p.numel)
+        agg_subtile_vector<kApply, kCounts>(p, t, lane, h);
+    else if (t * kTile < p.numel)
+        agg_subtile_guarded<kApply, kCounts>(p, t, lane, h);
 }
 
 // ---------------------------------------------------------------- server side, bit-sliced
@@ -995,8 +1032,8 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_sliced_kernel(FlatA
     if (kApply) {
         // lane l owns coordinates 4*(l&15).. of word 4*s + (l>>4): 16 bytes of x per lane
 #pragma unroll 2
-        for (int s = 0; s < kSlicedWords / kWordsPerSub; ++s) {
-            const int wl = s * kWordsPerSub + (lane >> 4);
+        for (int s = 0; s < kSlicedWords / kWordsPerTile; ++s) {
+            const int wl = s * kWordsPerTile + (lane >> 4);
             const int64_t j0 = (w0 + wl) * 64 + (lane & 15) * kVec;
             if (j0 >= p.numel)
                 continue;
@@ -1132,7 +1169,7 @@ __device__ __forceinline__ float decode_vote(uint32_t plus, uint32_t tie)
 // (l & 31) of the line, and for sub-tile s takes the dword that holds its nibble from lane
 // 8s + (l >> 3) with a lane permute.
 constexpr int kLineSubs = 4;
-constexpr int kLineCoords = kLineSubs * kSubTile;   // 1024
+constexpr int kLineCoords = kLineSubs * kTile;   // 1024
 
 template <int kMaxPlanes>
 __global__ __launch_bounds__(kLanes) void apply_encoded_kernel(FlatAddr addr, Hyper h, DeltaOut in)
@@ -1147,13 +1184,13 @@ __global__ __launch_bounds__(kLanes) void apply_encoded_kernel(FlatAddr addr, Hy
 #pragma unroll
         for (int b = 0; b < kMaxPlanes; ++b) {
             const uint32_t *line = reinterpret_cast<const uint32_t *>(in.planes + (int64_t)b * in.stride +
-                                                                      t * (kLineSubs * kWordsPerSub));
+                                                                      t * (kLineSubs * kWordsPerTile));
             raw[b] = b < in.n_planes ? line[lane & 31] : 0u;
         }
         f32x4 xv[kLineSubs];
 #pragma unroll
         for (int s = 0; s < kLineSubs; ++s)
-            xv[s] = x_load4(p.x + t * kLineCoords + s * kSubTile + lane * kVec);
+            xv[s] = x_load4(p.x + t * kLineCoords + s * kTile + lane * kVec);
         const int shift = (lane & 7) * 4;
 #pragma unroll
         for (int s = 0; s < kLineSubs; ++s) {
@@ -1184,15 +1221,15 @@ __global__ __launch_bounds__(kLanes) void apply_encoded_kernel(FlatAddr addr, Hy
             xv[s].y = lion_apply(xv[s].y, Delta[1], h);
             xv[s].z = lion_apply(xv[s].z, Delta[2], h);
             xv[s].w = lion_apply(xv[s].w, Delta[3], h);
-            x_store4(xv[s], p.x + t * kLineCoords + s * kSubTile + lane * kVec);
+            x_store4(xv[s], p.x + t * kLineCoords + s * kTile + lane * kVec);
         }
         return;
     }
     // ragged end: lane l owns bit l of one word at a time
     const int64_t W = (p.numel + 63) >> 6;
 #pragma unroll 1
-    for (int k = 0; k < kLineSubs * kWordsPerSub; ++k) {
-        const int64_t w = t * (kLineSubs * kWordsPerSub) + k;
+    for (int k = 0; k < kLineSubs * kWordsPerTile; ++k) {
+        const int64_t w = t * (kLineSubs * kWordsPerTile) + k;
         if (w >= W)
             break;
         const int64_t j = w * 64 + lane;
@@ -1232,9 +1269,9 @@ __global__ __launch_bounds__(kLanes) void global_lion_kernel(FlatAddr addr, Hype
     const int lane = threadIdx.x;
     const int N = h.N;
     const Coef k = {h.beta1, h.omb1, h.beta2, h.omb2};
-    const bool vec = (t + 1) * kSubTile <= p.numel;
+    const bool vec = (t + 1) * kTile <= p.numel;
     if (vec) {
-        const int64_t j0 = t * kSubTile + lane * kVec;
+        const int64_t j0 = t * kTile + lane * kVec;
         f32x4 xv = x_load4(p.x + j0);
         float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
         auto one_worker = [&](int i, f32x4 mv, f32x4 gv) {
@@ -1276,14 +1313,14 @@ __global__ __launch_bounds__(kLanes) void global_lion_kernel(FlatAddr addr, Hype
             const uint32_t nib = (b0 ? 1u : 0u) | (b1 ? 2u : 0u) | (b2 ? 4u : 0u) | (b3 ? 8u : 0u);
             const uint64_t word = row_gather_nibbles(nib, lane);
             if ((lane & 15) == 0)
-                sign_bits[t * kWordsPerSub + (lane >> 4)] = word;
+                sign_bits[t * kWordsPerTile + (lane >> 4)] = word;
         }
         return;
     }
     const int64_t W = (p.numel + 63) >> 6;
 #pragma unroll 1
-    for (int kk = 0; kk < kWordsPerSub; ++kk) {
-        const int64_t w = t * kWordsPerSub + kk;
+    for (int kk = 0; kk < kWordsPerTile; ++kk) {
+        const int64_t w = t * kWordsPerTile + kk;
         if (w >= W)
             break;
         const int64_t j = w * 64 + lane;
@@ -1310,35 +1347,29 @@ __global__ __launch_bounds__(kLanes) void global_lion_kernel(FlatAddr addr, Hype
 
 // ---------------------------------------------------------------- apply from counts
 template <class Addr>
-__global__ __launch_bounds__(kBlock) void apply_kernel(Addr addr, Hyper h)
+__global__ __launch_bounds__(kLanes) void apply_kernel(Addr addr, Hyper h)
 {
     const int64_t tile = wave_tile_index();
     if (tile >= addr.total_tiles)
         return;
-    const int lane = threadIdx.x & 63;
+    const int lane = threadIdx.x;
     Problem p;
-    const int64_t t = addr.resolve(tile, p) * kSubs;
+    const int64_t t = addr.resolve(tile, p);
+    if ((t + 1) * kTile <= p.numel) {
+        const int64_t j0 = t * kTile + lane * kVec;
+        const u16x4 c = counts_load4(p.counts + j0);
+        f32x4 xv = x_load4(p.x + j0);
+        xv.x = lion_apply(xv.x, aggregate_votes(c.x, h), h);
+        xv.y = lion_apply(xv.y, aggregate_votes(c.y, h), h);
+        xv.z = lion_apply(xv.z, aggregate_votes(c.z, h), h);
+        xv.w = lion_apply(xv.w, aggregate_votes(c.w, h), h);
+        x_store4(xv, p.x + j0);
+    } else {
 #pragma unroll 1
-    for (int r = 0; r < kSubs; ++r) {
-        const int64_t sub = t + r;
-        if (sub * kSubTile >= p.numel)
-            break;
-        if ((sub + 1) * kSubTile <= p.numel) {
-            const int64_t j0 = sub * kSubTile + lane * kVec;
-            const u16x4 c = counts_load4(p.counts + j0);
-            f32x4 xv = x_load4(p.x + j0);
-            xv.x = lion_apply(xv.x, aggregate_votes(c.x, h), h);
-            xv.y = lion_apply(xv.y, aggregate_votes(c.y, h), h);
-            xv.z = lion_apply(xv.z, aggregate_votes(c.z, h), h);
-            xv.w = lion_apply(xv.w, aggregate_votes(c.w, h), h);
-            x_store4(xv, p.x + j0);
-        } else {
-#pragma unroll 1
-            for (int k = 0; k < kWordsPerSub; ++k) {
-                const int64_t j = (sub * kWordsPerSub + k) * 64 + lane;
-                if (j < p.numel)
-                    p.x[j] = lion_apply(p.x[j], aggregate_votes(p.counts[j], h), h);
-            }
+        for (int k = 0; k < kWordsPerTile; ++k) {
+            const int64_t j = (t * kWordsPerTile + k) * 64 + lane;
+            if (j < p.numel)
+                p.x[j] = lion_apply(p.x[j], aggregate_votes(p.counts[j], h), h);
         }
     }
 }

@@ -15,3 +15,17 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+@pytest.fixture
+def tune():
+    """``tune(pass_workers=3, ...)`` installs launch-shape overrides of the library for this test only."""
+    import paper_2404_00438_amd as dl
+
+    before = dl.dlion_get_tuning()
+
+    def install(**fields):
+        dl.dlion_set_tuning(dl.dlion_get_tuning(), **fields)
+
+    yield install
+    dl.dlion_set_tuning(before)

@@ -196,7 +196,152 @@ def test_workspace_entry_point_validation(lib):
     assert call(A + 8, 4096) == EALIGN        # workspace not 16-byte aligned
     assert lib.dlion_step_workspace_bytes(1000, 4) == 0
     assert lib.dlion_step_workspace_bytes(-5, 32) == 0
-    assert lib.dlion_step_workspace_bytes(350_000_000, 32) == 131072 * 256 * 2
+    # 4 launches over 8 workers: 3 planes of 128 bytes per tile, 262144 tiles at a time
+    assert lib.dlion_step_workspace_bytes(350_000_000, 32) == 262144 * 3 * 128
+    # 16 launches: a running count, 512 bytes per tile
+    assert lib.dlion_step_workspace_bytes(350_000_000, 128) == 262144 * 512
+    assert lib.dlion_step_mt_workspace_bytes(0, 32) == 0 and lib.dlion_step_mt_workspace_bytes(1 << 31, 32) == 0
+    assert lib.dlion_step_mt_workspace_bytes(78125, 16) == 78125 * 128
+
+    def call_mt(ws, nbytes):
+        return lib.dlion_step_mt_ws(None, A, 1, 0, 4, 0, 0.9, 0.99, 1e-3, 0.1, None, 0, None, ws, nbytes, None)
+
+    assert call_mt(A, -1) == EINVAL and call_mt(None, 64) == EINVAL and call_mt(A + 8, 4096) == EALIGN
+    assert call_mt(A, 4096) == EINVAL         # null table
+
+
+def test_tuning_overrides_are_validated_and_restored(lib):
+    """dlion_set_tuning: host-only state, every field -1 by default, out-of-range values refused."""
+    t = binding.Tuning()
+    lib.dlion_get_tuning(ctypes.byref(t))
+    assert [getattr(t, f) for f, _ in binding.Tuning._fields_ if f != "reserved"] == [-1] * 8
+    try:
+        binding.dlion_set_tuning(pass_workers=3, block_tiles=5, unroll=4)
+        now = binding.dlion_get_tuning()
+        assert (now.pass_workers, now.block_tiles, now.unroll, now.sliced_waves) == (3, 5, 4, -1)
+        # the size helper follows the overrides: 11 launches of 3 workers need a running count
+        assert lib.dlion_step_workspace_bytes(70_001, 33) == 5 * 512
+        with binding.tuned(pass_workers=0):
+            assert binding.dlion_get_tuning().pass_workers == 0 and binding.dlion_get_tuning().block_tiles == 5
+            assert lib.dlion_step_workspace_bytes(350_000_000, 32) == 0
+        assert binding.dlion_get_tuning().pass_workers == 3
+        for bad in (dict(unroll=3), dict(sliced_waves=4), dict(blocks_per_cu=-2), dict(step_quads=2),
+                    dict(block_tiles=-7), dict(pass_workers=-3)):
+            with pytest.raises(binding.DlionError):
+                binding.dlion_set_tuning(**bad)
+        assert binding.dlion_get_tuning().pass_workers == 3          # a refused struct changes nothing
+        with pytest.raises(TypeError):
+            binding.dlion_set_tuning(no_such_field=1)
+    finally:
+        binding.dlion_set_tuning(None)
+    assert binding.dlion_get_tuning().pass_workers == -1 and binding.dlion_get_tuning().block_tiles == -1
+
+
+class _Recorder:
+    """Stands in for the loaded library: records calls, launches nothing."""
+
+    def __init__(self, real):
+        self.real, self.calls = real, []
+
+    def __getattr__(self, name):
+        if name in ("dlion_delta_planes", "dlion_mt_layout", "dlion_status_str"):
+            return getattr(self.real, name)
+
+        def fn(*args):
+            self.calls.append(name)
+            return 0
+        return fn
+
+
+def test_binding_checks_extents_before_calling_the_library(lib, monkeypatch):
+    """The C ABI sees pointers, not tensor sizes: the binding must refuse short, strided, host or
+    mismatched tensors itself.  Host tensors stand in for device ones here (the device check is
+    switched off, and a recorder replaces the library so nothing is launched)."""
+    import torch
+
+    rec = _Recorder(lib)
+    monkeypatch.setattr(binding, "load_library", lambda path=None: rec)
+    monkeypatch.setattr(binding, "_stream", lambda s: 0)
+    N, d = 4, 1000
+    W = binding.words_for(d)
+    x = torch.zeros(d)
+    m = torch.zeros(N, d)
+    g = torch.zeros(N, d)
+    packed = torch.zeros(N, W, dtype=torch.int64)
+    counts = torch.zeros(d, dtype=torch.int16)
+
+    # host tensors are refused while the device check is on
+    for call in (lambda: binding.dlion_aggregate(packed, d, counts),
+                 lambda: binding.dlion_apply(x, counts, N, 0, 1e-3, 0.1),
+                 lambda: binding.dlion_step(x, m, g, 0, 0.9, 0.99, 1e-3, 0.1),
+                 lambda: binding.dlion_step_ws(x, m, g, 0, 0.9, 0.99, 1e-3, 0.1, torch.zeros(64, dtype=torch.uint8))):
+        with pytest.raises(ValueError):
+            call()
+    assert rec.calls == []
+
+    monkeypatch.setattr(binding, "_on_device", lambda t: True)
+    binding.dlion_worker_step(m, g, packed, 0.9, 0.99)
+    binding.dlion_aggregate(packed, d, counts)
+    binding.dlion_apply(x, counts, N, 0, 1e-3, 0.1)
+    binding.dlion_aggregate_apply(x, packed, 0, 1e-3, 0.1, counts=counts)
+    binding.dlion_step(x, m, g, 0, 0.9, 0.99, 1e-3, 0.1, packed=packed, counts=counts)
+    good = list(rec.calls)
+    assert good == ["dlion_worker_step", "dlion_aggregate", "dlion_apply", "dlion_aggregate_apply", "dlion_step"]
+
+    short_packed = torch.zeros(N, W - 1, dtype=torch.int64)
+    short_counts = torch.zeros(d - 1, dtype=torch.int16)
+    bad = [
+        lambda: binding.dlion_worker_step(m, g, short_packed, 0.9, 0.99),
+        lambda: binding.dlion_worker_step(m, g, packed, 0.9, 0.99, d=d + 1),        # d beyond the rows
+        lambda: binding.dlion_worker_step(m, g, packed[:3], 0.9, 0.99),             # N mismatch
+        lambda: binding.dlion_worker_step(m, torch.zeros(N, d + 1), packed, 0.9, 0.99),
+        lambda: binding.dlion_aggregate(short_packed, d, counts),
+        lambda: binding.dlion_aggregate(packed, d, short_counts),
+        lambda: binding.dlion_aggregate(packed, d, torch.zeros(2 * d, dtype=torch.int16)[::2]),   # strided counts
+        lambda: binding.dlion_aggregate(packed, d, torch.zeros(d, 1, dtype=torch.int16)),         # not 1-D
+        lambda: binding.dlion_apply(x, short_counts, N, 0, 1e-3, 0.1),
+        lambda: binding.dlion_aggregate_apply(x, short_packed, 0, 1e-3, 0.1),
+        lambda: binding.dlion_aggregate_apply(x, packed, 0, 1e-3, 0.1, counts=short_counts),
+        lambda: binding.dlion_step(x, m, g, 0, 0.9, 0.99, 1e-3, 0.1, packed=short_packed),
+        lambda: binding.dlion_step(x, m, g, 0, 0.9, 0.99, 1e-3, 0.1, counts=short_counts),
+        lambda: binding.dlion_step(x[:-1], m, g, 0, 0.9, 0.99, 1e-3, 0.1),
+        lambda: binding.dlion_step(x, m, g[:, ::2], 0, 0.9, 0.99, 1e-3, 0.1),       # strided rows
+        lambda: binding.dlion_step_ws(x, m, g, 0, 0.9, 0.99, 1e-3, 0.1, torch.zeros(8, 8)[:, ::2]),
+        lambda: binding.dlion_aggregate_encode(packed, d, 0, torch.zeros(2, W - 1, dtype=torch.int64)),
+        lambda: binding.dlion_aggregate_encode(packed, d, 0, torch.zeros(1, W, dtype=torch.int64)),   # N even: 2 planes
+        lambda: binding.dlion_apply_encoded(x, torch.zeros(2, W - 1, dtype=torch.int64), N, 0, 1e-3, 0.1),
+        lambda: binding.dlion_global_lion_step(x, m, g, 0.9, 0.99, 1e-3, 0.1, sign_bits=torch.zeros(W - 1, dtype=torch.int64)),
+        lambda: binding.dlion_step_pw(x, m, g, 0, torch.zeros(N - 1), torch.zeros(N), 1e-3, 0.1),
+    ]
+    for k, call in enumerate(bad):
+        with pytest.raises((ValueError, TypeError)):
+            call()
+        assert rec.calls == good, f"case {k} reached the library"
+
+    # tensor lists: packed / counts against the table's totals, N against the table's rows
+    xs = [torch.zeros(n) for n in (1000, 5, 300)]
+    ms = [torch.zeros(N, n) for n in (1000, 5, 300)]
+    gs = [torch.zeros(N, n) for n in (1000, 5, 300)]
+    table = binding.SegTable(xs, ms, gs, device="cpu")
+    Wt = table.total_words
+    assert Wt == 16 + 1 + 5
+    ok_packed = torch.zeros(N, Wt, dtype=torch.int64)
+    ok_counts = torch.zeros(64 * Wt, dtype=torch.int16)
+    binding.dlion_step_mt(table, N, 0, 0.9, 0.99, 1e-3, 0.1, packed=ok_packed, counts=ok_counts)
+    good = list(rec.calls)
+    bad = [
+        lambda: binding.dlion_step_mt(table, N + 1, 0, 0.9, 0.99, 1e-3, 0.1),
+        lambda: binding.dlion_step_mt(table, N, 0, 0.9, 0.99, 1e-3, 0.1, packed=torch.zeros(N, Wt - 1, dtype=torch.int64)),
+        lambda: binding.dlion_step_mt(table, N, 0, 0.9, 0.99, 1e-3, 0.1, counts=torch.zeros(64 * Wt - 1, dtype=torch.int16)),
+        lambda: binding.dlion_worker_step_mt(table, torch.zeros(N + 1, Wt, dtype=torch.int64), 0.9, 0.99),
+        lambda: binding.dlion_aggregate_mt(table, ok_packed, torch.zeros(1000 + 5 + 300, dtype=torch.int16)),
+        lambda: binding.dlion_apply_mt(table, ok_counts[:-64], N, 0, 1e-3, 0.1),
+        lambda: binding.dlion_aggregate_apply_mt(table, ok_packed[:, :-1], 0, 1e-3, 0.1),
+    ]
+    for k, call in enumerate(bad):
+        with pytest.raises((ValueError, TypeError)):
+            call()
+        assert rec.calls == good, f"tensor-list case {k} reached the library"
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -293,12 +293,11 @@ def test_tiny_config_full_run():
 
 
 @pytest.mark.parametrize("waves", [1, 8, 16])
-def test_many_worker_aggregate_matches_oracle(waves, monkeypatch):
+def test_many_worker_aggregate_matches_oracle(waves, tune):
     """The bit-sliced server-side kernel: counts bit-exact, apply within the bar.  At these sizes the
     library would pick one-wave workgroups (and the per-nibble kernel for the fused update), so the
     bit-sliced kernel and its workgroup size are forced."""
-    monkeypatch.setenv("DLION_SLICED_MIN_WORKERS", "1")
-    monkeypatch.setenv("DLION_SLICED_WAVES", str(waves))
+    tune(sliced_min_workers=1, sliced_waves=waves)
     rng = np.random.default_rng(2024)
     cases = [(1, 300), (2, 8192), (3, 8193), (7, 70_001), (8, 129), (15, 5000),
              (16, 4096), (17, 4097), (31, 1), (32, 63), (33, 10_000), (64, 8192 + 5), (127, 4095),
@@ -407,12 +406,11 @@ def test_arrays_with_only_their_element_alignment(g_dtype):
 
 
 @pytest.mark.parametrize("per,tiles", [(1, 0), (3, 3), (8, 5)])
-def test_step_split_into_launches_over_few_workers(per, tiles, monkeypatch):
+def test_step_split_into_launches_over_few_workers(per, tiles, tune):
     """Many workers at large d run as several launches over a few workers each, the votes carried in
     the counts array, block of tiles by block of tiles; forced here at small sizes (`per` workers per
     launch, `tiles` tiles per block, 0 = one block).  Same bits and state as one launch."""
-    monkeypatch.setenv("DLION_PASS_WORKERS", str(per))
-    monkeypatch.setenv("DLION_PASS_TILES", str(tiles))
+    tune(pass_workers=per, block_tiles=tiles)
     rng = np.random.default_rng(4242 + per)
     for (d, N), mode, g_dtype in itertools.product(((1000, 4), (4099, 9), (257, 17), (70_001, 33), (700, 70)),
                                                    (dl.VOTE, dl.AVG), (torch.float32, torch.bfloat16)):
@@ -464,10 +462,10 @@ def test_step_split_into_launches_over_few_workers(per, tiles, monkeypatch):
             assert_f32_equal(to_np(ms[k]), mn[k], f"m[{k}]")
 
 
-def test_per_nibble_server_kernel_on_flat_buffers(monkeypatch):
+def test_per_nibble_server_kernel_on_flat_buffers(tune):
     """Flat buffers take the bit-sliced server kernel at every N; the per-nibble one (which tensor
     lists use for the fused aggregate + update) is forced here so that its flat form stays checked."""
-    monkeypatch.setenv("DLION_SLICED_MIN_WORKERS", "100000")
+    tune(sliced_min_workers=100000)
     rng = np.random.default_rng(515)
     for N, d in ((1, 1), (2, 63), (3, 257), (8, 4096 + 3), (9, 70_001), (33, 1000), (300, 5000)):
         W = dl.words_for(d)
@@ -492,15 +490,16 @@ def test_per_nibble_server_kernel_on_flat_buffers(monkeypatch):
             assert_f32_equal(to_np(x), xn, f"N={N} d={d} mode={mode}: x")
 
 
-@pytest.mark.parametrize("per,tiles", [(3, 3), (8, 0)])
-def test_step_with_votes_carried_in_a_workspace(per, tiles, monkeypatch):
-    """dlion_step_ws without a counts array: the launches over a few workers hand the votes on
-    through the caller's workspace, block of tiles by block of tiles (forced at small sizes)."""
-    monkeypatch.setenv("DLION_PASS_WORKERS", str(per))
-    monkeypatch.setenv("DLION_PASS_TILES", str(tiles))
+@pytest.mark.parametrize("per,tiles", [(3, 3), (8, 0), (15, 2), (20, 0)])
+def test_step_with_votes_carried_in_a_workspace(per, tiles, tune):
+    """dlion_step_ws / dlion_step_mt_ws: the launches over a few workers hand the votes on through the
+    caller's workspace, block of tiles by block of tiles (forced at small sizes).  Up to 8 launches of at
+    most 15 workers use planes of 4-bit partial counts, anything beyond a running uint16 count: the
+    cases cover both, with and without a counts output."""
+    tune(pass_workers=per, block_tiles=tiles)
     rng = np.random.default_rng(99 + per)
-    workspace = torch.full((16 << 20,), 0x5A, dtype=torch.uint8, device=DEV)       # the smallest size that is used
-    small = torch.zeros(1 << 20, dtype=torch.uint8, device=DEV)                    # too small: one launch
+    workspace = torch.full((4 << 20,), 0x5A, dtype=torch.uint8, device=DEV)
+    small = torch.zeros(64, dtype=torch.uint8, device=DEV)                         # holds no block: not used
     for (d, N), mode, g_dtype in itertools.product(((1000, 4), (4099, 9), (70_001, 33), (700, 70)),
                                                    (dl.VOTE, dl.AVG), (torch.float32, torch.bfloat16)):
         announce("workspace carry", per, tiles, g_dtype, "d", d, "N", N, "mode", mode)
@@ -512,14 +511,43 @@ def test_step_with_votes_carried_in_a_workspace(per, tiles, monkeypatch):
                                                                (workspace, True, True), (small, False, False),
                                                                (None, True, False))):
             xn, mn, pn, cn = oracle_step(x, m, g, mode, HYP)
+            workspace.fill_(0x5A if step % 2 else 0xFF)             # scratch: whatever it held must not matter
             dl.dlion_step_ws(x, m, g, mode, HYP["beta1"], HYP["beta2"], HYP["lr"], HYP["lam"], ws,
                              packed=packed if want_packed else None, counts=counts if want_counts else None)
             torch.cuda.synchronize()
             compare_all(f"d={d} N={N} step={step}", x, m, packed if want_packed else None,
                         counts if want_counts else None, xn, mn, pn, cn)
+    # tensor list, ragged tensors included
+    numels = [1000, 5, 64, 256, 257, 1, 2304 * 8, 63]
+    for N, mode in ((5, dl.VOTE), (18, dl.AVG), (70, dl.VOTE)):
+        announce("workspace carry: tensor list N", N)
+        xs, ms, gs = make_list(rng, numels, N, torch.bfloat16)
+        table = dl.SegTable(xs, ms, gs)
+        Wt = table.total_words
+        packed = torch.full((N, Wt), -1, dtype=torch.int64, device=DEV)
+        counts = torch.full((64 * Wt,), -1, dtype=torch.int16, device=DEV)
+        xn = [to_np(t) for t in xs]
+        mn = [to_np(t) for t in ms]
+        for step, (want_packed, want_counts) in enumerate(((False, False), (True, True))):
+            pn, cn = oracle.step_mt(xn, mn, [to_np(t) for t in gs], mode, 0.9, 0.99, 1e-4, 10.0)
+            dl.dlion_step_mt(table, N, mode, 0.9, 0.99, 1e-4, 10.0, packed=packed if want_packed else None,
+                             counts=counts if want_counts else None, workspace=workspace)
+            torch.cuda.synchronize()
+            if want_packed:
+                assert np.array_equal(to_np(packed), pn) and np.array_equal(unpad_counts(counts, table), cn)
+            for k in range(len(numels)):
+                assert_f32_equal(to_np(xs[k]), xn[k], f"x[{k}] step {step}")
+                assert_f32_equal(to_np(ms[k]), mn[k], f"m[{k}] step {step}")
+
+
+def test_workspace_sizes():
     assert dl.dlion_step_workspace_bytes(1000, 4) == 0 and dl.dlion_step_workspace_bytes(350_000_000, 8) == 0
-    assert dl.dlion_step_workspace_bytes(350_000_000, 32) == 131072 * 256 * 2
-    assert dl.dlion_step_workspace_bytes(20_000_000, 16) == 78125 * 256 * 2
+    # 4 launches over 8 workers: 3 planes of one uint16 per lane and tile, 262144 tiles at a time
+    assert dl.dlion_step_workspace_bytes(350_000_000, 32) == 262144 * 3 * 128
+    assert dl.dlion_step_workspace_bytes(20_000_000, 16) == 78125 * 1 * 128
+    # 16 launches: a running count, four uint16 per lane
+    assert dl.dlion_step_workspace_bytes(350_000_000, 128) == 262144 * 512
+    assert dl.dlion_step_mt_workspace_bytes(78125, 16) == dl.dlion_step_workspace_bytes(20_000_000, 16)
 
 
 def test_randomized_shapes_strides_and_flags():
@@ -579,10 +607,10 @@ def test_calls_follow_the_given_stream():
     compare_all("side stream", x, m, packed, counts, xn, mn, pn, cn)
 
 
-def test_step_can_be_captured_in_a_graph(monkeypatch):
+def test_step_can_be_captured_in_a_graph(tune):
     """The calls allocate nothing and never synchronise, so a step (here split into several launches)
     can be captured once and replayed; every replay is checked, with eager work in between."""
-    monkeypatch.setenv("DLION_PASS_WORKERS", "3")
+    tune(pass_workers=3)
     rng = np.random.default_rng(31)
     N, d = 7, 70_001
     x, m, g = draw_state(rng, N, d, torch.bfloat16, d + 3, d + 5)
