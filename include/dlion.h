@@ -313,6 +313,20 @@ dlion_status dlion_global_lion_step(float *x, float *m, int64_t m_stride, const 
                                     float beta1, float beta2, float lr, float lambda,
                                     uint64_t *sign_bits_or_null, void *stream);
 
+/*
+ * Memory-rate probe for benchmarks (no passage of the paper: it computes nothing of the
+ * method).  One-wave workgroups as in the real kernels: wave t reads the t-th 1 KB piece
+ * of each of `rows` rows of src (row r at src + r*src_row_stride_bytes), folds them with
+ * XOR, and, if write != 0, writes one 1 KB piece to dst; with write == 0 nothing is
+ * written (dst must still be valid).  rows = 1, write = 1 is a plain copy; rows = k gives
+ * a k : 1 read : write byte mix.  bytes_per_row must be a multiple of 1024, pointers and
+ * stride multiples of 16 (DLION_EINVAL / DLION_EALIGN otherwise); waves_per_cu caps the
+ * resident waves per compute unit (0 = no cap).  It moves rows*bytes_per_row bytes in and
+ * (write ? bytes_per_row : 0) bytes out.
+ */
+dlion_status dlion_membench(const void *src, int64_t src_row_stride_bytes, int32_t rows, void *dst,
+                            int64_t bytes_per_row, int32_t write, int32_t waves_per_cu, void *stream);
+
 /* Text for a status code (static storage, never NULL). */
 const char *dlion_status_str(dlion_status s);
 
@@ -332,7 +346,7 @@ typedef struct dlion_tuning {
     int32_t sliced_waves;       /* bit-sliced server kernels: waves per workgroup (1, 8, 16)                          */
     int32_t sliced_min_workers; /* server side: the per-nibble kernel below this N, the bit-sliced one from it on     */
     int32_t apply_blocks;       /* dlion_apply_encoded: resident workgroups per compute unit, 0 = no cap              */
-    int32_t reserved;           /* ignored                                                                           */
+    int32_t blocks_per_cu_pass; /* as blocks_per_cu, for the launches of a step that only hand their votes on        */
     int64_t block_tiles;        /* worker/fused kernels: tiles (256 coordinates) per launch, 0 = all in one launch    */
 } dlion_tuning;
 

@@ -27,6 +27,7 @@ from .binding import (  # noqa: F401
     dlion_step_mt,
     dlion_step_mt_workspace_bytes,
     dlion_get_tuning,
+    dlion_membench,
     dlion_set_tuning,
     tuned,
     Tuning,

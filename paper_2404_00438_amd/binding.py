@@ -30,7 +30,7 @@ EXPORTS = (
     "dlion_delta_planes", "dlion_aggregate_encode", "dlion_apply_encoded", "dlion_worker_step_pw",
     "dlion_step_pw", "dlion_global_lion_step", "dlion_step_ws", "dlion_step_workspace_bytes",
     "dlion_step_mt_ws", "dlion_step_mt_workspace_bytes", "dlion_tuning_defaults", "dlion_set_tuning",
-    "dlion_get_tuning",
+    "dlion_get_tuning", "dlion_membench",
 )
 
 
@@ -54,7 +54,7 @@ class Tuning(ctypes.Structure):
     _fields_ = [
         ("unroll", ctypes.c_int32), ("blocks_per_cu", ctypes.c_int32), ("pass_workers", ctypes.c_int32),
         ("step_quads", ctypes.c_int32), ("sliced_waves", ctypes.c_int32), ("sliced_min_workers", ctypes.c_int32),
-        ("apply_blocks", ctypes.c_int32), ("reserved", ctypes.c_int32), ("block_tiles", ctypes.c_int64),
+        ("apply_blocks", ctypes.c_int32), ("blocks_per_cu_pass", ctypes.c_int32), ("block_tiles", ctypes.c_int64),
     ]
 
 
@@ -87,6 +87,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "dlion_step_mt": [segp, vp, i32, ci, i32, ci, f32, f32, f32, f32, vp, i64, vp, vp],
         "dlion_step_mt_ws": [segp, vp, i32, ci, i32, ci, f32, f32, f32, f32, vp, i64, vp, vp, i64, vp],
         "dlion_set_tuning": [ctypes.POINTER(Tuning)],
+        "dlion_membench": [vp, i64, i32, vp, i64, i32, i32, vp],
         "dlion_delta_planes": [i32, ci],
         "dlion_aggregate_encode": [vp, i64, i64, i32, ci, vp, i64, vp],
         "dlion_apply_encoded": [vp, vp, i64, i64, i32, ci, f32, f32, vp],
@@ -287,7 +288,7 @@ def dlion_set_tuning(t: Optional[Tuning] = None, **fields) -> None:
         t = Tuning()
         load_library().dlion_tuning_defaults(ctypes.byref(t))
     for k, v in fields.items():
-        if k not in dict(Tuning._fields_) or k == "reserved":
+        if k not in dict(Tuning._fields_):
             raise TypeError(f"dlion_tuning has no field {k}")
         setattr(t, k, int(v))
     _check(load_library().dlion_set_tuning(ctypes.byref(t) if t is not None else None), "dlion_set_tuning")
@@ -472,3 +473,18 @@ def dlion_global_lion_step(x, m, g, beta1, beta2, lr, lam, sign_bits=None, strea
         sp = sign_bits.data_ptr()
     _check(load_library().dlion_global_lion_step(xp, mp, ms, gp, gs, gt, d, N, beta1, beta2, lr, lam,
                                                  sp, _stream(stream)), "dlion_global_lion_step")
+
+
+def dlion_membench(src, dst, rows=1, write=True, waves_per_cu=0, stream=None):
+    """Memory-rate probe: ``src`` is ``[rows, n]`` (contiguous rows, any row stride), ``dst`` ``[n]`` of the
+    same dtype; bytes per row must be a multiple of 1024.  Returns (bytes read, bytes written)."""
+    if src.dim() == 1:
+        src = src.unsqueeze(0)
+    sp, ss, R, n = _rows(src, "src")
+    if R != rows or dst.dim() != 1 or dst.numel() != n or dst.dtype != src.dtype or not _on_device(dst) or \
+            (n > 1 and dst.stride(0) != 1):
+        raise ValueError("src must be [rows, n] and dst [n] of the same dtype, on the device")
+    e = src.element_size()
+    _check(load_library().dlion_membench(sp, ss * e, rows, dst.data_ptr(), n * e, 1 if write else 0, waves_per_cu,
+                                         _stream(stream)), "dlion_membench")
+    return rows * n * e, (n * e if write else 0)

@@ -82,21 +82,23 @@ dlion_status launch(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds, hip
 
 // ------------------------------------------------------------------ launch shape
 // HBM delivers the most when the chip keeps only a modest, compact window of addresses in
-// flight: roughly 28 KB of outstanding loads per compute unit (a little less with many
-// workers in one launch): bf16 gradients, 3 KB per wave, 8 / 9 / 10 waves per compute unit give
-// 79.5 / 80.3 / 80.0 % of peak at N = 8; fp32 gradients, 4 KB per wave, 6 / 7 / 8 waves give
-// 79.4 / 79.9 / 78.2 %; 5 waves lose a quarter.  A tensor list takes one wave more: its waves
-// start with a table lookup during which they have nothing in flight (148 tensors, fp32,
-// N = 16: 7 waves 78.8 %, 8 waves 79.4 %).  A wave of the fused kernel has `unroll` workers' loads outstanding at once, so
-// the number of resident waves per compute unit is capped accordingly.  The cap is applied by
-// reserving (unused) dynamic LDS per workgroup: a compute unit has 160 KB, so a reservation
-// of 160 KB / k admits k workgroups.
+// flight.  A wave of the worker/fused kernels has one worker's loads outstanding at a time
+// (1 KB of m and 0.5 or 1 KB of g), and the number of resident waves per compute unit is capped:
+// bf16 gradients, 12 / 13 / 14 / 16 waves give 78.5 / 80.1 / 78.5 / 77.3 % of peak at N = 8,
+// d = 124 M, and 79.3 / 80.3 / 79.9 / 79.4 % at d = 1.3 G; the launches of a split step that only
+// hand their votes on want one more (N = 32, d = 350 M: 13 / 14 / 16 waves 77.9 / 79.4 / 78.8 %);
+// fp32 gradients 12 (tensor list, N = 16: 12 / 13 / 14 waves 79.1 / 79.1 / 77.2 %).  Issuing two
+// workers' loads back to back with 9 waves comes within 0.5 % at N = 8 but loses 2 % in the split
+// step; uncapped the kernel reaches 68 %.  A tensor list takes one wave more: its waves start
+// with a table lookup during which they have nothing in flight.  The cap is applied by reserving
+// (unused) dynamic LDS per workgroup: a compute unit has 160 KB, so a reservation of 160 KB / k
+// admits k workgroups.
 //
 // What was tried and dropped for many workers in one launch: 16-wave workgroups walking over
 // the workers in lockstep cut the per-CU translation-cache misses 15x at N = 32 (5.5 M against
 // 84 M per launch) but were 1-3 % slower on the same allocation; the large run-to-run spread
-// of one launch at N = 32 (65-76 % of peak) follows the row stride (a multiple of 4 KB is the
-// slow case), not the launch shape.  What works is fewer workers per launch (launch_step below).
+// of one launch at N = 32 (65-76 % of peak) follows the row stride, not the launch shape.  What
+// works is fewer workers per launch (launch_step below).
 struct LaunchShape {
     int unroll;          // workers whose loads are issued back to back (8, 4, 2 or 1)
     int blocks_per_cu;   // resident workgroups per compute unit (0: no cap)
@@ -104,7 +106,6 @@ struct LaunchShape {
 
 constexpr size_t kLdsPerCu = 160 * 1024;
 constexpr size_t kMaxDynamicLds = 160 * 1024;
-constexpr int kManyWorkers = 24;
 constexpr int64_t kResidentWaves = 256 * 32;   // one-wave workgroups the 256 compute units hold at once
 
 inline size_t lds_reservation(int blocks_per_cu)
@@ -115,22 +116,29 @@ inline size_t lds_reservation(int blocks_per_cu)
     return bytes > kMaxDynamicLds ? kMaxDynamicLds : bytes;
 }
 
-LaunchShape step_shape(int32_t N, size_t bytes_per_worker_per_wave)
+// What a launch of the worker/fused kernels is within its step.
+enum StepRole {
+    kWholeStep,   // all workers of the step in this launch
+    kHandOn,      // some of the workers; the votes are handed on to a later launch (no x)
+    kLastPass,    // the last workers: adds up what was handed on, then aggregates and updates x
+};
+
+// wide_g: fp32 gradients (a wave then has 2 KB per worker in flight, 1.5 KB with bf16 ones).
+LaunchShape step_shape(int32_t N, bool wide_g, StepRole role)
 {
     const dlion_tuning &tn = tuning();
     LaunchShape s;
-    s.unroll = tn.unroll > 0 ? tn.unroll : 2;
+    s.unroll = tn.unroll > 0 ? tn.unroll : 1;
     while (s.unroll > N)
         s.unroll >>= 1;
     if (s.unroll < 1)
         s.unroll = 1;
-    if (tn.blocks_per_cu >= 0) {
-        s.blocks_per_cu = tn.blocks_per_cu;
+    const int forced = (role == kHandOn && tn.blocks_per_cu_pass >= 0) ? tn.blocks_per_cu_pass : tn.blocks_per_cu;
+    if (forced >= 0) {
+        s.blocks_per_cu = forced;
     } else {
-        const size_t target = (N >= kManyWorkers ? 18 : 28) * 1024;
-        const size_t in_flight = bytes_per_worker_per_wave * static_cast<size_t>(s.unroll);
-        int k = static_cast<int>((target + in_flight / 2) / in_flight);
-        s.blocks_per_cu = k < 3 ? 3 : (k > 32 ? 0 : k);
+        const int waves = wide_g ? (role == kLastPass ? 13 : 12) : (role == kWholeStep ? 13 : (role == kHandOn ? 14 : 17));
+        s.blocks_per_cu = s.unroll == 1 ? waves : (waves * 3 / 2 / s.unroll < 3 ? 3 : waves * 3 / 2 / s.unroll);
     }
     return s;
 }
@@ -157,14 +165,15 @@ template <typename GT, bool kApply, class Addr>
 dlion_status launch_step_unroll(const Addr &addr, const Hyper &h, bool packed, bool counts, int64_t problem_tiles,
                                 hipStream_t s)
 {
-    LaunchShape shape = step_shape(h.worker_end - h.worker_begin, kLanes * (16 + Grad<GT>::kVecBytes));
+    const StepRole role = h.carry_out != 0 ? kHandOn : ((h.carry != kCarryNone && h.carry_in) ? kLastPass : kWholeStep);
+    LaunchShape shape = step_shape(h.worker_end - h.worker_begin, Grad<GT>::kVecBytes == 16, role);
     // A problem whose waves all fit on the chip at once never reaches the steady state the cap
     // is tuned for; it is latency-bound and wants every wave resident (d = 1,000,003, N = 4:
     // 12.7 -> 10.4 us).
     if (tuning().blocks_per_cu < 0) {
         if (problem_tiles <= kResidentWaves)
             shape.blocks_per_cu = 0;
-        else if (shape.blocks_per_cu > 0 && std::is_same<Addr, SegAddr>::value)
+        else if (role == kWholeStep && shape.blocks_per_cu > 0 && std::is_same<Addr, SegAddr>::value)
             shape.blocks_per_cu += 1;
     }
     const size_t lds = lds_reservation(shape.blocks_per_cu);
@@ -212,7 +221,8 @@ constexpr int kPassMinN = 16;
 constexpr int kNibblePasses = 8;            // at most 7 planes of partial counts
 constexpr int kNibbleMaxWorkers = 15;       // a partial count must fit 4 bits
 constexpr int64_t kPassMinTiles = 8 * kResidentWaves;
-constexpr int64_t kBlockTiles = 32 * kResidentWaves;         // 67 M coordinates per launch
+constexpr int64_t kBlockTiles = 64 * kResidentWaves;         // 134 M coordinates per launch
+constexpr int64_t kPassBlockTiles = 32 * kResidentWaves;     // 67 M when the block is cut into launches over few workers
 constexpr int64_t kPassMinBlockTiles = 4 * kResidentWaves;   // a workspace that holds less is not used
 
 struct Workspace {
@@ -249,17 +259,17 @@ inline int workspace_carry(int32_t N, int passes)
     return (passes <= kNibblePasses && most <= kNibbleMaxWorkers) ? kCarryNibbles : kCarryRunning;
 }
 
-inline int64_t default_block_tiles()
+inline int64_t default_block_tiles(int passes)
 {
     const int64_t forced = tuning().block_tiles;           // 0 = all tiles in one block
-    return forced >= 0 ? forced : kBlockTiles;
+    return forced >= 0 ? forced : (passes > 1 ? kPassBlockTiles : kBlockTiles);
 }
 
 StepPlan plan_step(int32_t N, int64_t tiles, bool apply, bool counts, const Workspace &ws)
 {
     StepPlan pl;
     pl.passes = default_passes(N, tiles);
-    pl.block = default_block_tiles();
+    pl.block = default_block_tiles(pl.passes);
     if (pl.block <= 0 || pl.block > tiles)
         pl.block = tiles;
     if (pl.passes > 1 && apply) {
@@ -477,7 +487,7 @@ dlion_status launch_encode(const FlatAddr &addr, const Hyper &h, const DeltaOut 
 template <typename GT>
 dlion_status launch_global_lion_unroll(const FlatAddr &addr, const Hyper &h, uint64_t *sign_bits, hipStream_t s)
 {
-    const LaunchShape shape = step_shape(h.N, kLanes * (16 + Grad<GT>::kVecBytes));
+    const LaunchShape shape = step_shape(h.N, Grad<GT>::kVecBytes == 16, kWholeStep);
     const size_t lds = lds_reservation(shape.blocks_per_cu);
     const dim3 grid(static_cast<uint32_t>(addr.total_tiles)), block(kLanes);
     if (shape.unroll >= 2 && h.N >= 2)
@@ -677,7 +687,7 @@ int64_t dlion_step_mt_workspace_bytes(int64_t total_tiles, int32_t N)
     const int passes = default_passes(N, total_tiles);
     if (passes <= 1)
         return 0;
-    int64_t block = default_block_tiles();
+    int64_t block = default_block_tiles(passes);
     if (block <= 0 || block > total_tiles)
         block = total_tiles;
     return block * ws_bytes_per_tile(workspace_carry(N, passes), passes);
@@ -976,6 +986,31 @@ dlion_status dlion_global_lion_step(float *x, float *m, int64_t m_stride, const 
     return launch_global_lion_unroll<float>(a, h, sign_bits_or_null, static_cast<hipStream_t>(stream));
 }
 
+dlion_status dlion_membench(const void *src, int64_t src_row_stride_bytes, int32_t rows, void *dst,
+                            int64_t bytes_per_row, int32_t write, int32_t waves_per_cu, void *stream)
+{
+    if (!src || !dst || rows < 1 || bytes_per_row <= 0 || bytes_per_row % 1024 != 0 || waves_per_cu < 0 ||
+        waves_per_cu > 64 || (rows > 1 && src_row_stride_bytes < bytes_per_row))
+        return DLION_EINVAL;
+    if (!aligned_to(src, 16) || !aligned_to(dst, 16) || src_row_stride_bytes % 16 != 0)
+        return DLION_EALIGN;
+    const int64_t pieces = bytes_per_row / 1024;
+    if (pieces > kMaxTiles)
+        return DLION_EUNSUPPORTED;
+    const size_t lds = lds_reservation(waves_per_cu);
+    const u32x4 *s4 = static_cast<const u32x4 *>(src);
+    u32x4 *d4 = static_cast<u32x4 *>(dst);
+    const int64_t block = default_block_tiles(1) > 0 ? default_block_tiles(1) : pieces;
+    for (int64_t first = 0; first < pieces; first += block) {
+        const dim3 grid = grid_for(first + block < pieces ? block : pieces - first), threads(kLanes);
+        DLION_TRY(write ? launch(membench_kernel<true>, grid, threads, lds, static_cast<hipStream_t>(stream), s4,
+                                 src_row_stride_bytes / 16, rows, d4, first)
+                        : launch(membench_kernel<false>, grid, threads, lds, static_cast<hipStream_t>(stream), s4,
+                                 src_row_stride_bytes / 16, rows, d4, first));
+    }
+    return DLION_OK;
+}
+
 const char *dlion_status_str(dlion_status s)
 {
     switch (s) {
@@ -1006,12 +1041,11 @@ dlion_status dlion_set_tuning(const dlion_tuning *t)
         v = *t;
     const bool unroll_ok = v.unroll == -1 || v.unroll == 1 || v.unroll == 2 || v.unroll == 4 || v.unroll == 8;
     const bool waves_ok = v.sliced_waves == -1 || v.sliced_waves == 1 || v.sliced_waves == 8 || v.sliced_waves == 16;
-    if (!unroll_ok || !waves_ok || v.blocks_per_cu < -1 || v.blocks_per_cu > 64 || v.pass_workers < -1 ||
+    if (!unroll_ok || !waves_ok || v.blocks_per_cu < -1 || v.blocks_per_cu > 64 || v.blocks_per_cu_pass < -1 || v.blocks_per_cu_pass > 64 || v.pass_workers < -1 ||
         v.step_quads < -1 || v.step_quads > 1 || v.sliced_min_workers < -1 || v.apply_blocks < -1 ||
         v.apply_blocks > 64 || v.block_tiles < -1 || v.block_tiles > kMaxTiles)
         return DLION_EINVAL;
-    v.reserved = -1;
-    g_tuning = v;
+        g_tuning = v;
     return DLION_OK;
 }
 

@@ -1374,4 +1374,34 @@ __global__ __launch_bounds__(kLanes) void apply_kernel(Addr addr, Hyper h)
     }
 }
 
+// ---------------------------------------------------------------- memory-rate probe
+// None of the method's arithmetic: wave t reads the t-th 1 KB piece of each of `rows` rows (128
+// bits per lane, up to 16 rows in flight), folds them with XOR so that no load can be dropped, and
+// writes one 1 KB piece (kWrite) or nothing.  rows = 1 with kWrite is a plain copy; rows = 16 has
+// the 16 : 1 read : write byte mix of counting 256 packed streams into uint16 counts.  Same launch
+// style as the real kernels: one-wave workgroups, streaming accesses, plain tile numbering.
+template <bool kWrite>
+__global__ __launch_bounds__(kLanes) void membench_kernel(const u32x4 *src, int64_t row_stride, int32_t rows,
+                                                          u32x4 *dst, int64_t first_piece)
+{
+    const int64_t at = (first_piece + blockIdx.x) * kLanes + threadIdx.x;      // in 16-byte units
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    int r = 0;
+    for (; r + 16 <= rows; r += 16) {
+        u32x4 v[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+            v[k] = __builtin_nontemporal_load(src + (int64_t)(r + k) * row_stride + at);
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+            acc ^= v[k];
+    }
+    for (; r < rows; ++r)
+        acc ^= __builtin_nontemporal_load(src + (int64_t)r * row_stride + at);
+    if (kWrite)
+        __builtin_nontemporal_store(acc, dst + at);
+    else if (acc.x == 0x9E3779B9u && acc.y == 0x7F4A7C15u && acc.z == acc.x && acc.w == acc.y)
+        dst[0] = acc;                                        // practically never: keeps the loads alive
+}
+
 }  // namespace dlion

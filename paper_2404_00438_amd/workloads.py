@@ -136,6 +136,12 @@ def init_x(w: Workload, device, numel: Optional[int] = None, tensor: int = 0) ->
     return torch.randn(n, generator=_gen(device, w.seed - 1 - tensor), device=device, dtype=torch.float32) * 0.02
 
 
+def padded_stride(numel: int) -> int:
+    """Row stride (elements) that starts every worker's row of a flat buffer on a 1 KB boundary of the
+    fp32 momentum (512 B of bf16 gradients): the layout the library's header names as its fastest."""
+    return (numel + 255) // 256 * 256
+
+
 def init_m(w: Workload, device, numel: Optional[int] = None, row_stride: Optional[int] = None) -> torch.Tensor:
     """Momentum starts at zero (Algorithm 1, initialisation); ``[N, numel]`` view of padded rows."""
     n = w.d if numel is None else numel
@@ -145,11 +151,12 @@ def init_m(w: Workload, device, numel: Optional[int] = None, row_stride: Optiona
 
 
 def make_grads(w: Workload, step: int, device, numel: Optional[int] = None, tensor: int = 0,
-               out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """Per-worker gradients of one step, ``[N, numel]`` of ``w.g_dtype`` (cast round-to-nearest-even)."""
+               out: Optional[torch.Tensor] = None, row_stride: Optional[int] = None) -> torch.Tensor:
+    """Per-worker gradients of one step, ``[N, numel]`` of ``w.g_dtype`` (cast round-to-nearest-even);
+    ``row_stride`` pads the rows (the values do not depend on it)."""
     n = w.numels()[tensor] if numel is None else numel
     if out is None:
-        out = torch.empty((w.N, n), device=device, dtype=w.g_dtype)
+        out = torch.empty((w.N, n if row_stride is None else row_stride), device=device, dtype=w.g_dtype)[:, :n]
     for i in range(w.N):
         gen = _gen(device, w.seed + 1000 * step + i + 100_000 * tensor)
         out[i].copy_(draw(w.g_dist, w.g_scale, n, gen, device))

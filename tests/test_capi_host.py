@@ -214,7 +214,7 @@ def test_tuning_overrides_are_validated_and_restored(lib):
     """dlion_set_tuning: host-only state, every field -1 by default, out-of-range values refused."""
     t = binding.Tuning()
     lib.dlion_get_tuning(ctypes.byref(t))
-    assert [getattr(t, f) for f, _ in binding.Tuning._fields_ if f != "reserved"] == [-1] * 8
+    assert [getattr(t, f) for f, _ in binding.Tuning._fields_] == [-1] * 9
     try:
         binding.dlion_set_tuning(pass_workers=3, block_tiles=5, unroll=4)
         now = binding.dlion_get_tuning()
