@@ -162,6 +162,35 @@ dlion_status dlion_step_ws(float *x, float *m, int64_t m_stride, const void *g, 
 
 int64_t dlion_step_workspace_bytes(int64_t d, int32_t N);
 
+/*
+ * dlion_step for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and the same results
+ * bit for bit as dlion_step_ws; the workspace in which launches over 8 workers each hand
+ * their votes on is a static array of DLION_NOALLOC_SCRATCH_BYTES (64 MiB) of device memory
+ * inside the library, which every GPU the library runs on holds until the process ends.
+ * The call allocates and frees nothing (no hipMalloc / hipFree, no library routine that
+ * allocates); its device address is looked up once per device, on the first call made with
+ * that device current or by dlion_noalloc_init (call it outside a graph capture; the device
+ * that is current must be the stream's).
+ *   Limits.  Every (d, N) that dlion_step accepts: the step runs in blocks of coordinates
+ *            sized to the scratch (44 M coordinates at 32 workers).  Should a launch plan
+ *            ever need more than the scratch holds for its smallest block, the call
+ *            returns DLION_EUNSUPPORTED before anything is launched.
+ *   Sharing. All calls on one GPU share that GPU's scratch, and nothing in it has to be
+ *            cleared between calls (every launch writes what a later one reads).  Calls
+ *            that overlap on one GPU (different streams, concurrent graph launches) race:
+ *            order them.
+ *   Errors.  As dlion_step; DLION_ELAUNCH also when the runtime cannot name the current
+ *            device or the scratch's address.
+ */
+#define DLION_NOALLOC_SCRATCH_BYTES (64u << 20)
+dlion_status dlion_noalloc_init(void);
+dlion_status dlion_step_noalloc(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
+                                dlion_dtype g_dtype, int64_t d, int32_t N, dlion_mode mode,
+                                float beta1, float beta2, float lr, float lambda,
+                                uint64_t *packed_or_null, int64_t packed_stride,
+                                uint16_t *counts_or_null, void *stream);
+
 /* ------------------------------------------------------------------------- *
  * Multi-tensor form: the model is a list of K tensors instead of one flat
  * buffer.  Every tensor is an independent flat problem whose packed bits start

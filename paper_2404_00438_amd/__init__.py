@@ -28,6 +28,8 @@ from .binding import (  # noqa: F401
     dlion_step_mt_workspace_bytes,
     dlion_get_tuning,
     dlion_membench,
+    dlion_noalloc_init,
+    dlion_step_noalloc,
     dlion_set_tuning,
     tuned,
     Tuning,

@@ -30,7 +30,7 @@ EXPORTS = (
     "dlion_delta_planes", "dlion_aggregate_encode", "dlion_apply_encoded", "dlion_worker_step_pw",
     "dlion_step_pw", "dlion_global_lion_step", "dlion_step_ws", "dlion_step_workspace_bytes",
     "dlion_step_mt_ws", "dlion_step_mt_workspace_bytes", "dlion_tuning_defaults", "dlion_set_tuning",
-    "dlion_get_tuning", "dlion_membench",
+    "dlion_get_tuning", "dlion_membench", "dlion_noalloc_init", "dlion_step_noalloc",
 )
 
 
@@ -79,6 +79,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "dlion_aggregate_apply": [vp, vp, i64, i64, i32, ci, f32, f32, vp, vp],
         "dlion_step": [vp, vp, i64, vp, i64, ci, i64, i32, ci, f32, f32, f32, f32, vp, i64, vp, vp],
         "dlion_step_ws": [vp, vp, i64, vp, i64, ci, i64, i32, ci, f32, f32, f32, f32, vp, i64, vp, vp, i64, vp],
+        "dlion_step_noalloc": [vp, vp, i64, vp, i64, ci, i64, i32, ci, f32, f32, f32, f32, vp, i64, vp, vp],
+        "dlion_noalloc_init": [],
         "dlion_mt_layout": [segp, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)],
         "dlion_worker_step_mt": [segp, vp, i32, ci, vp, i64, i32, f32, f32, vp],
         "dlion_aggregate_mt": [segp, vp, i32, vp, i64, i32, vp, vp],
@@ -264,6 +266,17 @@ def dlion_step_ws(x, m, g, mode, beta1, beta2, lr, lam, workspace, packed=None, 
     wp, wb = _workspace(workspace)
     _check(load_library().dlion_step_ws(xp, mp, ms, gp, gs, gt, d, N, mode, beta1, beta2, lr, lam,
                                         pp, ps, cp, wp, wb, _stream(stream)), "dlion_step_ws")
+
+
+def dlion_step_noalloc(x, m, g, mode, beta1, beta2, lr, lam, packed=None, counts=None, stream=None):
+    """``dlion_step`` whose hand-over workspace is the library's static device array: allocates nothing."""
+    xp, mp, ms, gp, gs, gt, d, N, pp, ps, cp = _step_args(x, m, g, packed, counts)
+    _check(load_library().dlion_step_noalloc(xp, mp, ms, gp, gs, gt, d, N, mode, beta1, beta2, lr, lam,
+                                             pp, ps, cp, _stream(stream)), "dlion_step_noalloc")
+
+
+def dlion_noalloc_init() -> None:
+    _check(load_library().dlion_noalloc_init(), "dlion_noalloc_init")
 
 
 def dlion_step_workspace_bytes(d: int, N: int) -> int:

@@ -24,6 +24,33 @@ inline bool power_of_two(int32_t n) { return n > 0 && (n & (n - 1)) == 0; }
 dlion_tuning g_tuning = {-1, -1, -1, -1, -1, -1, -1, -1, -1};
 inline const dlion_tuning &tuning() { return g_tuning; }
 
+// Scratch of dlion_step_noalloc: device memory inside the library's code object, so that the entry
+// point needs no allocation by anybody.  Every GPU the library runs on holds its own copy at its
+// own address; in host code the array's name is only a handle for hipGetSymbolAddress, never a
+// pointer to pass on.
+static __device__ __align__(256) unsigned char dlion_static_scratch[DLION_NOALLOC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of the scratch on the current device, looked up once per device.
+dlion_status static_scratch(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return DLION_ELAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(dlion_static_scratch)) != hipSuccess || !p)
+            return DLION_ELAUNCH;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return DLION_OK;
+}
+
 Hyper make_hyper(int32_t N, int mode, float beta1, float beta2, float lr, float lambda)
 {
     Hyper h;
@@ -733,6 +760,36 @@ dlion_status dlion_step_ws(float *x, float *m, int64_t m_stride, const void *g, 
     ws.bytes = workspace_bytes;
     return launch_step<true>(a, h, g_dtype, packed_or_null != nullptr, counts_or_null != nullptr,
                              static_cast<hipStream_t>(stream), ws);
+}
+
+dlion_status dlion_noalloc_init(void)
+{
+    void *p;
+    return static_scratch(&p);
+}
+
+dlion_status dlion_step_noalloc(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
+                                dlion_dtype g_dtype, int64_t d, int32_t N, dlion_mode mode, float beta1,
+                                float beta2, float lr, float lambda, uint64_t *packed_or_null,
+                                int64_t packed_stride, uint16_t *counts_or_null, void *stream)
+{
+    DLION_TRY(check_common(d, N));
+    // what the hand-over of this step needs for its smallest block must fit the static scratch
+    const int passes = default_passes(N, tiles_for(d));
+    if (passes > 1) {
+        const int64_t per_tile = ws_bytes_per_tile(workspace_carry(N, passes), passes);
+        int64_t least = default_block_tiles(passes);
+        if (least <= 0 || least > tiles_for(d))
+            least = tiles_for(d);
+        if (least > kPassMinBlockTiles)
+            least = kPassMinBlockTiles;
+        if (least * per_tile > (int64_t)DLION_NOALLOC_SCRATCH_BYTES)
+            return DLION_EUNSUPPORTED;
+    }
+    void *scratch = nullptr;
+    DLION_TRY(static_scratch(&scratch));
+    return dlion_step_ws(x, m, m_stride, g, g_stride, g_dtype, d, N, mode, beta1, beta2, lr, lambda, packed_or_null,
+                         packed_stride, counts_or_null, scratch, (int64_t)DLION_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 // ----------------------------------------------------------------------- tensor lists
