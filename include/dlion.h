@@ -68,16 +68,22 @@
 extern "C" {
 #endif
 
-typedef enum dlion_status {
+/* Status, aggregation mode and gradient type travel as plain 32-bit integers, so that a value
+ * outside the lists below is an error the library can report (DLION_EINVAL), not undefined
+ * behaviour in the caller's or the library's language. */
+typedef int32_t dlion_status;
+enum {
     DLION_OK = 0,
     DLION_EINVAL = 1,       /* a size, stride, count or enum is out of range, or a pointer is NULL */
     DLION_EALIGN = 2,       /* a pointer is not aligned to its element type */
     DLION_ELAUNCH = 3,      /* the HIP runtime refused a launch (hipLaunchKernel != hipSuccess) */
     DLION_EUNSUPPORTED = 4  /* valid request outside what this build implements */
-} dlion_status;
+};
 
-typedef enum dlion_mode { DLION_VOTE = 0, DLION_AVG = 1 } dlion_mode;   /* Section 3.2, aggregate() */
-typedef enum dlion_dtype { DLION_F32 = 0, DLION_BF16 = 1 } dlion_dtype; /* gradient storage type */
+typedef int32_t dlion_mode;  /* Section 3.2, aggregate() */
+enum { DLION_VOTE = 0, DLION_AVG = 1 };
+typedef int32_t dlion_dtype; /* gradient storage type */
+enum { DLION_F32 = 0, DLION_BF16 = 1 };
 
 #define DLION_MAX_WORKERS 65535 /* counts are uint16 */
 

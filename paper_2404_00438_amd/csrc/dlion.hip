@@ -637,6 +637,23 @@ SegAddr seg_addr(const dlion_seg *segs_dev, int32_t K, int64_t total_tiles, uint
     return a;
 }
 
+// Arguments that every form of the flat fused step shares.
+dlion_status check_step(const float *x, const float *m, int64_t m_stride, const void *g, int64_t g_stride,
+                        dlion_dtype g_dtype, int64_t d, int32_t N, dlion_mode mode, const uint64_t *packed_or_null,
+                        int64_t packed_stride, const uint16_t *counts_or_null)
+{
+    DLION_TRY(check_common(d, N));
+    if (!dtype_ok(g_dtype) || !mode_ok(mode) || !x)
+        return DLION_EINVAL;
+    if (!aligned_to(x, 4) || !aligned_to(counts_or_null, 2))
+        return DLION_EALIGN;
+    DLION_TRY(check_rows(m, m_stride, d, N, 4));
+    DLION_TRY(check_rows(g, g_stride, d, N, grad_size(g_dtype)));
+    if (packed_or_null)
+        DLION_TRY(check_rows(packed_or_null, packed_stride, words_for(d), N, 8));
+    return DLION_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -740,17 +757,12 @@ dlion_status dlion_step_ws(float *x, float *m, int64_t m_stride, const void *g, 
                            uint16_t *counts_or_null, void *workspace_or_null, int64_t workspace_bytes,
                            void *stream)
 {
-    DLION_TRY(check_common(d, N));
-    if (!dtype_ok(g_dtype) || !mode_ok(mode) || !x)
-        return DLION_EINVAL;
+    DLION_TRY(check_step(x, m, m_stride, g, g_stride, g_dtype, d, N, mode, packed_or_null, packed_stride,
+                         counts_or_null));
     if (workspace_bytes < 0 || (workspace_or_null == nullptr && workspace_bytes != 0))
         return DLION_EINVAL;
-    if (!aligned_to(x, 4) || !aligned_to(counts_or_null, 2) || !aligned_to(workspace_or_null, 16))
+    if (!aligned_to(workspace_or_null, 16))
         return DLION_EALIGN;
-    DLION_TRY(check_rows(m, m_stride, d, N, 4));
-    DLION_TRY(check_rows(g, g_stride, d, N, grad_size(g_dtype)));
-    if (packed_or_null)
-        DLION_TRY(check_rows(packed_or_null, packed_stride, words_for(d), N, 8));
     Hyper h = make_hyper(N, mode, beta1, beta2, lr, lambda);
     h.stream_counts = counts_or_null ? counts_exceed_cache(d) : 0;
     h.xcd_quads = step_quads(rows_split_lines(m, m_stride, 4, N) || rows_split_lines(g, g_stride, grad_size(g_dtype), N));
@@ -773,7 +785,8 @@ dlion_status dlion_step_noalloc(float *x, float *m, int64_t m_stride, const void
                                 float beta2, float lr, float lambda, uint64_t *packed_or_null,
                                 int64_t packed_stride, uint16_t *counts_or_null, void *stream)
 {
-    DLION_TRY(check_common(d, N));
+    DLION_TRY(check_step(x, m, m_stride, g, g_stride, g_dtype, d, N, mode, packed_or_null, packed_stride,
+                         counts_or_null));
     // what the hand-over of this step needs for its smallest block must fit the static scratch
     const int passes = default_passes(N, tiles_for(d));
     if (passes > 1) {
