@@ -218,7 +218,7 @@ class Oracle:
                                          lr, lam, _ptr(bits))
         return bits
 
-    def step_mt(self, xs, ms, gs, mode, beta1, beta2, lr, lam):
+    def step_mt(self, xs, ms, gs, mode, beta1, beta2, lr, lam, threads: int = 1):
         """Multi-tensor iteration: tensor ``k`` is ``xs[k]`` flat ``[n_k]``, ``ms[k]``/``gs[k]`` ``[N, n_k]``.
 
         Every tensor is an independent flat problem whose bits start on a fresh
@@ -227,7 +227,7 @@ class Oracle:
         """
         packed_all, counts_all = [], []
         for xk, mk, gk in zip(xs, ms, gs):
-            pk, ck = self.step(xk, mk, gk, mode, beta1, beta2, lr, lam)
+            pk, ck = self.step(xk, mk, gk, mode, beta1, beta2, lr, lam, threads=threads)
             packed_all.append(pk)
             counts_all.append(ck)
         return np.concatenate(packed_all, axis=1), np.concatenate(counts_all)

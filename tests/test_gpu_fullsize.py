@@ -7,6 +7,8 @@ of the full problem -- always including the first words and the ragged end --
 fed with the very same initial state and gradients the GPU sees, step after
 step.  Whole-array properties that hold at any size complete the check.
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -25,18 +27,44 @@ def announce(*what):
     print("[case]", *what, flush=True)
 
 
-def sample_chunks(d: int, n_chunks: int, seed: int):
-    """Word-aligned [start, stop) ranges: the first chunk, random ones, and the one ending at d."""
+BLOCK_COORDS = (262144 * 256, 524288 * 256)   # coordinates per launch: split steps, whole steps
+
+
+def sample_chunks(d: int, n_chunks: int, seed: int, edges=()):
+    """Word-aligned, disjoint [start, stop) ranges in increasing order: the first chunk, random ones, a
+    chunk centred on every coordinate in ``edges`` (launch boundaries, 2^32-byte crossings, ...), the
+    last tiles, and the one ending at d (the only one that may be ragged)."""
     rng = np.random.default_rng(seed)
     W = (d + 63) // 64
     words_per_chunk = CHUNK // 64
     starts = {0}
     while len(starts) < n_chunks - 1:
         starts.add(int(rng.integers(0, max(1, W - words_per_chunk))) * 64)
-    ranges = sorted((s, min(s + CHUNK, d)) for s in starts)
+    for e in edges:
+        if 0 < e < d:
+            starts.add(max(0, (e - CHUNK // 2) // 64 * 64))
     last_start = max(0, (W - words_per_chunk)) * 64
-    ranges = [r for r in ranges if r[1] <= last_start] + [(last_start, d)]   # ragged end goes last
-    return ranges
+    starts.add(max(0, last_start - 32 * 256))          # the last 32 tiles before the final chunk
+    ranges = []
+    for s_ in sorted(starts):
+        if s_ >= last_start:
+            continue
+        stop = min(s_ + CHUNK, last_start)
+        if ranges and s_ < ranges[-1][1]:              # overlap: extend the previous range
+            ranges[-1] = (ranges[-1][0], max(ranges[-1][1], stop))
+        else:
+            ranges.append((s_, stop))
+    return ranges + [(last_start, d)]                  # ragged end goes last
+
+
+def launch_edges(d: int):
+    """Coordinates where one launch of a step ends and the next begins, the first tiles of the last
+    (partial) block, and where a row crosses 2^32 bytes (fp32: 2^30 elements, bf16: 2^31)."""
+    edges = [1 << 30, 1 << 31]
+    for block in BLOCK_COORDS:
+        edges += list(range(block, d, block))
+        edges.append(d // block * block + CHUNK // 2)
+    return edges
 
 
 def gather(t: torch.Tensor, ranges) -> torch.Tensor:
@@ -66,41 +94,79 @@ def popcount64_total(t: torch.Tensor) -> int:
     return total
 
 
-def run_flat_workload(w: wl.Workload, n_chunks: int = 24, steps=None):
+def same_bits(a: torch.Tensor, b: torch.Tensor) -> bool:
+    """Whole-array, bit-for-bit comparison on the device (fp32 compared as integers: NaNs included)."""
+    if a.dtype == torch.float32:
+        return all(torch.equal(a[i].view(torch.int32), b[i].view(torch.int32)) for i in range(a.shape[0])) \
+            if a.dim() == 2 else torch.equal(a.view(torch.int32), b.view(torch.int32))
+    return torch.equal(a, b)
+
+
+def run_flat_workload(w: wl.Workload, n_chunks: int = 24, steps=None, padded=True, full_oracle_step=False):
+    """All steps of a flat workload exactly as bench.py launches it (padded rows, the workspace form when
+    the library would use one), the oracle following on sampled chunks; on the last step the instrumented
+    variant (packed words and counts) and, on copies of the state, the unfused pipeline, whose x, m, packed
+    words and counts must equal the fused step's over the WHOLE arrays; optionally one step of the oracle
+    over the whole arrays on all host threads."""
     steps = w.steps if steps is None else steps
     d, N = w.d, w.N
     announce(w.name, "d", d, "N", N, "mode", w.mode, "steps", steps)
-    ranges = sample_chunks(d, n_chunks, seed=d % 9973)
+    ranges = sample_chunks(d, n_chunks, seed=d % 9973, edges=launch_edges(d))
+    stride = wl.padded_stride(d) if padded else d
     x = wl.init_x(w, DEV)
-    m = wl.init_m(w, DEV)
-    g = torch.empty((N, d), dtype=w.g_dtype, device=DEV)
+    m = wl.init_m(w, DEV, row_stride=stride)
+    g = torch.empty((N, stride), dtype=w.g_dtype, device=DEV)[:, :d]
     xh, mh = to_np(gather(x, ranges)), to_np(gather(m, ranges))
     W = dl.words_for(d)
     exact = True
     ws_bytes = dl.dlion_step_workspace_bytes(d, N)
     workspace = torch.full((ws_bytes,), 0xA5, dtype=torch.uint8, device=DEV) if ws_bytes else None
+    hyp = (w.mode, w.beta1, w.beta2, w.lr, w.lam)
     for t in range(steps):
         wl.make_grads(w, t, DEV, out=g)
         gh = to_np(gather(g, ranges))
-        ph, ch = oracle.step(xh, mh, gh, w.mode, w.beta1, w.beta2, w.lr, w.lam)
+        ph, ch = oracle.step(xh, mh, gh, *hyp)
         last = t == steps - 1
         if last:
+            # copies for the unfused pipeline and (optionally) the oracle over the whole arrays
+            x_u, m_u = x.clone(), m.clone()
+            if full_oracle_step:
+                x_full, m_full, g_full = to_np(x), to_np(m), to_np(g)
             # the instrumented variant on the last step: packed words and counts at full size
             packed = torch.empty((N, W), dtype=torch.int64, device=DEV)
             counts = torch.empty(d, dtype=torch.int16, device=DEV)
-            dl.dlion_step(x, m, g, w.mode, w.beta1, w.beta2, w.lr, w.lam, packed=packed, counts=counts)
-        elif workspace is not None:
-            # exactly what bench.py launches for many workers: the votes carried in a workspace
-            dl.dlion_step_ws(x, m, g, w.mode, w.beta1, w.beta2, w.lr, w.lam, workspace)
+            dl.dlion_step_ws(x, m, g, *hyp, workspace, packed=packed, counts=counts)
         else:
-            # exactly what bench.py launches
-            dl.dlion_step(x, m, g, w.mode, w.beta1, w.beta2, w.lr, w.lam)
+            # exactly what bench.py launches (a null workspace is dlion_step)
+            dl.dlion_step_ws(x, m, g, *hyp, workspace)
         torch.cuda.synchronize()
         exact &= assert_f32_equal(to_np(gather(m, ranges)), mh, f"{w.name} step {t}: m")
         exact &= assert_f32_equal(to_np(gather(x, ranges)), xh, f"{w.name} step {t}: x")
         print(f"  step {t} ok", flush=True)
     assert np.array_equal(to_np(gather_words(packed, ranges)), ph), f"{w.name}: packed words differ"
     assert np.array_equal(to_np(gather(counts, ranges)), ch), f"{w.name}: counts differ"
+    # the unfused pipeline (three other kernels) on the copies: whole arrays, bit for bit
+    packed_u = torch.empty((N, W), dtype=torch.int64, device=DEV)
+    counts_u = torch.empty(d, dtype=torch.int16, device=DEV)
+    dl.dlion_worker_step(m_u, g, packed_u, w.beta1, w.beta2)
+    dl.dlion_aggregate(packed_u, d, counts_u)
+    dl.dlion_apply(x_u, counts_u, N, w.mode, w.lr, w.lam)
+    torch.cuda.synchronize()
+    assert same_bits(packed_u, packed), f"{w.name}: fused and unfused packed words differ somewhere"
+    assert same_bits(counts_u, counts), f"{w.name}: fused and unfused counts differ somewhere"
+    assert same_bits(m_u, m), f"{w.name}: fused and unfused momentum differ somewhere"
+    assert same_bits(x_u, x), f"{w.name}: fused and unfused weights differ somewhere"
+    del packed_u, counts_u, m_u, x_u
+    print("  fused step == worker_step + aggregate + apply over the whole arrays", flush=True)
+    if full_oracle_step:
+        threads = min(len(os.sched_getaffinity(0)), 16)
+        p_full, c_full = oracle.step(x_full, m_full, g_full, *hyp, threads=threads)
+        assert np.array_equal(to_np(packed), p_full), f"{w.name}: packed words differ from the whole-array oracle"
+        assert np.array_equal(to_np(counts), c_full), f"{w.name}: counts differ from the whole-array oracle"
+        exact &= assert_f32_equal(to_np(m), m_full, f"{w.name}: m, whole arrays")
+        exact &= assert_f32_equal(to_np(x), x_full, f"{w.name}: x, whole arrays")
+        del p_full, c_full, x_full, m_full, g_full
+        print(f"  last step equals the oracle over all {d} x {N} updates", flush=True)
     # properties of the whole arrays
     c32 = counts.to(torch.int32) & 0xFFFF
     assert int(c32.max().item()) <= N and int(c32.min().item()) >= 0
@@ -109,15 +175,16 @@ def run_flat_workload(w: wl.Workload, n_chunks: int = 24, steps=None):
     if tail < 64:
         assert int(((packed[:, W - 1] >> tail) != 0).sum().item()) == 0, "bits past d must be zero"
     assert bool(torch.isfinite(x).all()) and bool(torch.isfinite(m).all())
-    print(f"{w.name}: sampled {sum(b - a for a, b in ranges)} coordinates per step, "
+    print(f"{w.name}: sampled {sum(b - a for a, b in ranges)} coordinates per step in {len(ranges)} ranges, "
           f"fp32 state bit-identical: {exact}", flush=True)
     del packed, counts, g, m, x
     torch.cuda.empty_cache()
 
 
 def test_gpt2_small_avg8_full_size():
-    """Benchmark workload: d = 124 M flat, N = 8, averaging, bf16 Student-t gradients, 20 steps."""
-    run_flat_workload(wl.CONFIGS["gpt2s_avg8"])
+    """d = 124 M flat, N = 8, averaging, bf16 Student-t gradients, 20 steps; the last step also against
+    the oracle over the whole arrays."""
+    run_flat_workload(wl.CONFIGS["gpt2s_avg8"], full_oracle_step=True)
 
 
 def test_gpt350m_32_workers_vote_then_avg_full_size():
@@ -128,11 +195,14 @@ def test_gpt350m_32_workers_vote_then_avg_full_size():
 
 def test_stress_1p3b_full_size():
     """d = 1.3 B, N = 8: offsets beyond 2^32 bytes within one stream and 2^33 elements overall."""
-    run_flat_workload(wl.CONFIGS["stress1p3b_vote8"], steps=3)
+    run_flat_workload(wl.CONFIGS["stress1p3b_vote8"])
 
 
 def test_vit_b16_tensor_list_full_size():
-    """ViT-B/16-shaped list of 148 tensors, N = 16, majority vote, fp32 gradients, 10 steps."""
+    """ViT-B/16-shaped list of 148 tensors, N = 16, majority vote, fp32 gradients, 10 steps, launched as
+    bench.py launches it (workspace form).  The oracle follows on every small tensor in full, on sampled
+    chunks of the large ones and on the chunks around every launch boundary; the last step is also
+    compared with the oracle over ALL tensors in full and with the unfused calls over the whole arrays."""
     w = wl.CONFIGS["vitb16_vote16"]
     numels = w.numels()
     N = w.N
@@ -142,6 +212,9 @@ def test_vit_b16_tensor_list_full_size():
     gs = [torch.empty((N, n), dtype=w.g_dtype, device=DEV) for n in numels]
     table = dl.SegTable(xs, ms, gs)
     Wt = table.total_words
+    ws_bytes = dl.dlion_step_mt_workspace_bytes(table.total_tiles, N)
+    assert ws_bytes > 0
+    workspace = torch.full((ws_bytes,), 0xA5, dtype=torch.uint8, device=DEV)
     # every small tensor in full, and sampled chunks of the big ones
     rng = np.random.default_rng(3)
     picks = []
@@ -152,21 +225,33 @@ def test_vit_b16_tensor_list_full_size():
             s = int(rng.integers(0, (n - CHUNK) // 64)) * 64
             picks.append((k, s, s + CHUNK))
             picks.append((k, n - CHUNK, n))
+    # the tiles on both sides of every launch boundary (tile numbers run through the whole list)
+    tile_begin = [table.host[k].tile_begin for k in range(len(numels))]
+    for block in (262144, 524288):
+        for edge in range(block, table.total_tiles, block):
+            k = max(i for i in range(len(numels)) if tile_begin[i] <= edge)
+            at = (edge - tile_begin[k]) * 256
+            lo, hi = max(0, at - CHUNK // 2), min(numels[k], at + CHUNK // 2)
+            if hi > lo:
+                picks.append((k, lo, hi))
     xh = [to_np(xs[k][a:b]) for k, a, b in picks]
     mh = [to_np(ms[k][:, a:b]) for k, a, b in picks]
     exact = True
+    hyp = (w.mode, w.beta1, w.beta2, w.lr, w.lam)
     for t in range(w.steps):
         for k in range(len(numels)):
             wl.make_grads(w, t, DEV, tensor=k, out=gs[k])
         gh = [to_np(gs[k][:, a:b]) for k, a, b in picks]
-        ph, ch = oracle.step_mt(xh, mh, gh, w.mode, w.beta1, w.beta2, w.lr, w.lam)
+        ph, ch = oracle.step_mt(xh, mh, gh, *hyp)
         last = t == w.steps - 1
         if last:
+            x_full, m_full, g_full = [to_np(t_) for t_ in xs], [to_np(t_) for t_ in ms], [to_np(t_) for t_ in gs]
+            xs_u, ms_u = [t_.clone() for t_ in xs], [t_.clone() for t_ in ms]
             packed = torch.empty((N, Wt), dtype=torch.int64, device=DEV)
             counts = torch.empty(64 * Wt, dtype=torch.int16, device=DEV)
-            dl.dlion_step_mt(table, N, w.mode, w.beta1, w.beta2, w.lr, w.lam, packed=packed, counts=counts)
+            dl.dlion_step_mt(table, N, *hyp, packed=packed, counts=counts, workspace=workspace)
         else:
-            dl.dlion_step_mt(table, N, w.mode, w.beta1, w.beta2, w.lr, w.lam)
+            dl.dlion_step_mt(table, N, *hyp, workspace=workspace)
         torch.cuda.synchronize()
         for i, (k, a, b) in enumerate(picks):
             exact &= assert_f32_equal(to_np(ms[k][:, a:b]), mh[i], f"step {t} tensor {k}: m")
@@ -180,7 +265,35 @@ def test_vit_b16_tensor_list_full_size():
     c32 = counts.to(torch.int32) & 0xFFFF
     assert int(c32.max().item()) <= N
     assert popcount64_total(packed) == int(c32.sum(dtype=torch.int64).item())
-    print(f"{w.name}: {len(picks)} sampled ranges, fp32 state bit-identical: {exact}", flush=True)
+    # the last step through the unfused calls on copies: whole arrays, bit for bit
+    table_u = dl.SegTable(xs_u, ms_u, gs)
+    packed_u = torch.empty((N, Wt), dtype=torch.int64, device=DEV)
+    counts_u = torch.empty(64 * Wt, dtype=torch.int16, device=DEV)
+    dl.dlion_worker_step_mt(table_u, packed_u, w.beta1, w.beta2)
+    dl.dlion_aggregate_mt(table_u, packed_u, counts_u)
+    dl.dlion_apply_mt(table_u, counts_u, N, w.mode, w.lr, w.lam)
+    torch.cuda.synchronize()
+    assert torch.equal(packed_u, packed) and torch.equal(counts_u, counts)
+    for k in range(len(numels)):
+        assert same_bits(ms_u[k], ms[k]) and same_bits(xs_u[k], xs[k]), f"tensor {k}: fused and unfused state differ"
+    print("  fused step == worker_step + aggregate + apply over all tensors", flush=True)
+    # ... and against the oracle over all 148 tensors in full
+    threads = min(len(os.sched_getaffinity(0)), 16)
+    p_full, c_full = oracle.step_mt(x_full, m_full, g_full, *hyp, threads=threads)
+    assert np.array_equal(to_np(packed), p_full)
+    assert np.array_equal(unpad(counts, table), c_full)
+    for k in range(len(numels)):
+        exact &= assert_f32_equal(to_np(ms[k]), m_full[k], f"tensor {k}: m in full")
+        exact &= assert_f32_equal(to_np(xs[k]), x_full[k], f"tensor {k}: x in full")
+    print(f"{w.name}: {len(picks)} sampled ranges per step, last step against the oracle on all {w.d} x {N} updates; "
+          f"fp32 state bit-identical: {exact}", flush=True)
+
+
+def unpad(counts, table):
+    """counts of a tensor list without the padding entries between a tensor's end and its next word"""
+    c = to_np(counts)
+    return np.concatenate([c[64 * table.word_begin[k]: 64 * table.word_begin[k] + table.numels[k]]
+                           for k in range(table.K)])
 
 
 def test_vote_only_256_streams_full_size():
@@ -193,7 +306,8 @@ def test_vote_only_256_streams_full_size():
     counts = torch.empty(d, dtype=torch.int16, device=DEV)
     dl.dlion_aggregate(packed, d, counts)
     torch.cuda.synchronize()
-    ranges = sample_chunks(d, 16, seed=11)
+    # the bit-sliced kernel's workgroups own 8192 coordinates per wave, 16 waves each
+    ranges = sample_chunks(d, 16, seed=11, edges=[8192 * 16 * k for k in (1, 2, 1000, 7629)] + [1 << 30])
     ph = to_np(gather_words(packed, ranges))
     want = oracle.aggregate_packed(ph, ph.shape[1] * 64)
     assert np.array_equal(to_np(gather(counts, ranges)), want)
@@ -220,7 +334,7 @@ def test_unfused_and_wider_rows_full_size():
     d, N = w.d, w.N
     W = dl.words_for(d)
     announce("unfused + wider rows", "d", d, "N", N)
-    ranges = sample_chunks(d, 16, seed=5)
+    ranges = sample_chunks(d, 16, seed=5, edges=launch_edges(d))
     x = wl.init_x(w, DEV)
     m = wl.init_m(w, DEV)
     m.normal_(0, 1e-3)
