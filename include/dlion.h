@@ -351,16 +351,18 @@ dlion_status dlion_global_lion_step(float *x, float *m, int64_t m_stride, const 
 /*
  * Memory-rate probe for benchmarks (no passage of the paper: it computes nothing of the
  * method).  One-wave workgroups as in the real kernels: wave t reads the t-th 1 KB piece
- * of each of `rows` rows of src (row r at src + r*src_row_stride_bytes), folds them with
- * XOR, and, if write != 0, writes one 1 KB piece to dst; with write == 0 nothing is
- * written (dst must still be valid).  rows = 1, write = 1 is a plain copy; rows = k gives
- * a k : 1 read : write byte mix.  bytes_per_row must be a multiple of 1024, pointers and
- * stride multiples of 16 (DLION_EINVAL / DLION_EALIGN otherwise); waves_per_cu caps the
- * resident waves per compute unit (0 = no cap).  It moves rows*bytes_per_row bytes in and
+ * of each of `rows` rows of src (row r at src + r*src_row_stride_bytes), loads_in_flight
+ * (1, 2, 4, 8 or 16) rows at a time, folds them with XOR, and, if write != 0, writes one
+ * 1 KB piece to dst; with write == 0 nothing is written (dst must still be valid).
+ * rows = 1, write = 1 is a plain copy; rows = k gives a k : 1 read : write byte mix.
+ * bytes_per_row must be a multiple of 1024, pointers and stride multiples of 16
+ * (DLION_EINVAL / DLION_EALIGN otherwise); waves_per_cu caps the resident waves per
+ * compute unit (0 = no cap).  It moves rows*bytes_per_row bytes in and
  * (write ? bytes_per_row : 0) bytes out.
  */
 dlion_status dlion_membench(const void *src, int64_t src_row_stride_bytes, int32_t rows, void *dst,
-                            int64_t bytes_per_row, int32_t write, int32_t waves_per_cu, void *stream);
+                            int64_t bytes_per_row, int32_t write, int32_t loads_in_flight,
+                            int32_t waves_per_cu, void *stream);
 
 /* Text for a status code (static storage, never NULL). */
 const char *dlion_status_str(dlion_status s);

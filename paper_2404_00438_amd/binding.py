@@ -89,7 +89,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "dlion_step_mt": [segp, vp, i32, ci, i32, ci, f32, f32, f32, f32, vp, i64, vp, vp],
         "dlion_step_mt_ws": [segp, vp, i32, ci, i32, ci, f32, f32, f32, f32, vp, i64, vp, vp, i64, vp],
         "dlion_set_tuning": [ctypes.POINTER(Tuning)],
-        "dlion_membench": [vp, i64, i32, vp, i64, i32, i32, vp],
+        "dlion_membench": [vp, i64, i32, vp, i64, i32, i32, i32, vp],
         "dlion_delta_planes": [i32, ci],
         "dlion_aggregate_encode": [vp, i64, i64, i32, ci, vp, i64, vp],
         "dlion_apply_encoded": [vp, vp, i64, i64, i32, ci, f32, f32, vp],
@@ -488,7 +488,7 @@ def dlion_global_lion_step(x, m, g, beta1, beta2, lr, lam, sign_bits=None, strea
                                                  sp, _stream(stream)), "dlion_global_lion_step")
 
 
-def dlion_membench(src, dst, rows=1, write=True, waves_per_cu=0, stream=None):
+def dlion_membench(src, dst, rows=1, write=True, loads_in_flight=16, waves_per_cu=0, stream=None):
     """Memory-rate probe: ``src`` is ``[rows, n]`` (contiguous rows, any row stride), ``dst`` ``[n]`` of the
     same dtype; bytes per row must be a multiple of 1024.  Returns (bytes read, bytes written)."""
     if src.dim() == 1:
@@ -498,6 +498,6 @@ def dlion_membench(src, dst, rows=1, write=True, waves_per_cu=0, stream=None):
             (n > 1 and dst.stride(0) != 1):
         raise ValueError("src must be [rows, n] and dst [n] of the same dtype, on the device")
     e = src.element_size()
-    _check(load_library().dlion_membench(sp, ss * e, rows, dst.data_ptr(), n * e, 1 if write else 0, waves_per_cu,
+    _check(load_library().dlion_membench(sp, ss * e, rows, dst.data_ptr(), n * e, 1 if write else 0, loads_in_flight, waves_per_cu,
                                          _stream(stream)), "dlion_membench")
     return rows * n * e, (n * e if write else 0)

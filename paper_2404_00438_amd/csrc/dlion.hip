@@ -637,6 +637,19 @@ SegAddr seg_addr(const dlion_seg *segs_dev, int32_t K, int64_t total_tiles, uint
     return a;
 }
 
+template <int kBatch>
+dlion_status launch_membench(const u32x4 *src, int64_t row_stride, int32_t rows, u32x4 *dst, int64_t pieces,
+                             bool write, size_t lds, hipStream_t s)
+{
+    const int64_t block = default_block_tiles(1) > 0 ? default_block_tiles(1) : pieces;
+    for (int64_t first = 0; first < pieces; first += block) {
+        const dim3 grid = grid_for(first + block < pieces ? block : pieces - first), threads(kLanes);
+        DLION_TRY(write ? launch(membench_kernel<true, kBatch>, grid, threads, lds, s, src, row_stride, rows, dst, first)
+                        : launch(membench_kernel<false, kBatch>, grid, threads, lds, s, src, row_stride, rows, dst, first));
+    }
+    return DLION_OK;
+}
+
 // Arguments that every form of the flat fused step shares.
 dlion_status check_step(const float *x, const float *m, int64_t m_stride, const void *g, int64_t g_stride,
                         dlion_dtype g_dtype, int64_t d, int32_t N, dlion_mode mode, const uint64_t *packed_or_null,
@@ -1057,10 +1070,14 @@ dlion_status dlion_global_lion_step(float *x, float *m, int64_t m_stride, const 
 }
 
 dlion_status dlion_membench(const void *src, int64_t src_row_stride_bytes, int32_t rows, void *dst,
-                            int64_t bytes_per_row, int32_t write, int32_t waves_per_cu, void *stream)
+                            int64_t bytes_per_row, int32_t write, int32_t loads_in_flight, int32_t waves_per_cu,
+                            void *stream)
 {
     if (!src || !dst || rows < 1 || bytes_per_row <= 0 || bytes_per_row % 1024 != 0 || waves_per_cu < 0 ||
         waves_per_cu > 64 || (rows > 1 && src_row_stride_bytes < bytes_per_row))
+        return DLION_EINVAL;
+    if (loads_in_flight != 1 && loads_in_flight != 2 && loads_in_flight != 4 && loads_in_flight != 8 &&
+        loads_in_flight != 16)
         return DLION_EINVAL;
     if (!aligned_to(src, 16) || !aligned_to(dst, 16) || src_row_stride_bytes % 16 != 0)
         return DLION_EALIGN;
@@ -1070,15 +1087,15 @@ dlion_status dlion_membench(const void *src, int64_t src_row_stride_bytes, int32
     const size_t lds = lds_reservation(waves_per_cu);
     const u32x4 *s4 = static_cast<const u32x4 *>(src);
     u32x4 *d4 = static_cast<u32x4 *>(dst);
-    const int64_t block = default_block_tiles(1) > 0 ? default_block_tiles(1) : pieces;
-    for (int64_t first = 0; first < pieces; first += block) {
-        const dim3 grid = grid_for(first + block < pieces ? block : pieces - first), threads(kLanes);
-        DLION_TRY(write ? launch(membench_kernel<true>, grid, threads, lds, static_cast<hipStream_t>(stream), s4,
-                                 src_row_stride_bytes / 16, rows, d4, first)
-                        : launch(membench_kernel<false>, grid, threads, lds, static_cast<hipStream_t>(stream), s4,
-                                 src_row_stride_bytes / 16, rows, d4, first));
+    const int64_t stride = src_row_stride_bytes / 16;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (loads_in_flight) {
+    case 1: return launch_membench<1>(s4, stride, rows, d4, pieces, write != 0, lds, s);
+    case 2: return launch_membench<2>(s4, stride, rows, d4, pieces, write != 0, lds, s);
+    case 4: return launch_membench<4>(s4, stride, rows, d4, pieces, write != 0, lds, s);
+    case 8: return launch_membench<8>(s4, stride, rows, d4, pieces, write != 0, lds, s);
+    default: return launch_membench<16>(s4, stride, rows, d4, pieces, write != 0, lds, s);
     }
-    return DLION_OK;
 }
 
 const char *dlion_status_str(dlion_status s)

@@ -766,6 +766,11 @@ constexpr int kWpl = DLION_SLICED_WORDS_PER_LANE;
 constexpr int kSlices = 2 * kWpl;                      // 32-bit slices a lane carries
 constexpr int kSlicedWords = kLanes * kWpl;            // words per wave
 constexpr int kSlicedCoords = kSlicedWords * 64;
+#ifndef DLION_SLICED_IN_FLIGHT
+#define DLION_SLICED_IN_FLIGHT 4           // rows whose loads a wave has outstanding at once (2, 4, 8 or 16)
+#endif
+constexpr int kSlicedInFlight = DLION_SLICED_IN_FLIGHT;
+static_assert(kSlicedInFlight == 2 || kSlicedInFlight == 4 || kSlicedInFlight == 8 || kSlicedInFlight == 16, "rows in flight");
 
 typedef u32x4 words2_e __attribute__((aligned(8)));
 
@@ -815,23 +820,15 @@ __device__ __forceinline__ void sliced_count(const Problem &p, int N, int64_t w0
             hi[b][q] = 0;
     }
 
-    // adds one batch of 16 words per slice (carry-save tree, then a ripple into the upper planes)
-    auto add_batch = [&](const uint32_t (&v)[16][kSlices]) {
+    // Tree over the weight-2 carries of 8 pairs of words, then a ripple into the upper planes.
+    auto add_pairs = [&](uint32_t (&t)[8][kSlices]) {
 #pragma unroll
         for (int q = 0; q < kSlices; ++q) {
-            uint32_t t0, t1, t2, t3, t4, t5, t6, t7, f0, f1, f2, f3, e0, e1, s16;
-            csa(t0, ones[q], ones[q], v[0][q], v[1][q]);
-            csa(t1, ones[q], ones[q], v[2][q], v[3][q]);
-            csa(t2, ones[q], ones[q], v[4][q], v[5][q]);
-            csa(t3, ones[q], ones[q], v[6][q], v[7][q]);
-            csa(t4, ones[q], ones[q], v[8][q], v[9][q]);
-            csa(t5, ones[q], ones[q], v[10][q], v[11][q]);
-            csa(t6, ones[q], ones[q], v[12][q], v[13][q]);
-            csa(t7, ones[q], ones[q], v[14][q], v[15][q]);
-            csa(f0, twos[q], twos[q], t0, t1);
-            csa(f1, twos[q], twos[q], t2, t3);
-            csa(f2, twos[q], twos[q], t4, t5);
-            csa(f3, twos[q], twos[q], t6, t7);
+            uint32_t f0, f1, f2, f3, e0, e1, s16;
+            csa(f0, twos[q], twos[q], t[0][q], t[1][q]);
+            csa(f1, twos[q], twos[q], t[2][q], t[3][q]);
+            csa(f2, twos[q], twos[q], t[4][q], t[5][q]);
+            csa(f3, twos[q], twos[q], t[6][q], t[7][q]);
             csa(e0, fours[q], fours[q], f0, f1);
             csa(e1, fours[q], fours[q], f2, f3);
             csa(s16, eights[q], eights[q], e0, e1);
@@ -844,44 +841,71 @@ __device__ __forceinline__ void sliced_count(const Problem &p, int N, int64_t w0
             }
         }
     };
-    // one batch of 16 rows starting at row i, full-width loads; guard_rows: rows past N count as zeros
-    auto load_rows = [&](int i, uint32_t (&v)[16][kSlices], auto guard_rows) {
-        // the row base is uniform; each lane adds a small unsigned byte offset
-        const uint32_t lane_bytes = static_cast<uint32_t>(lane) * (8u * kWpl);
+    // adds one batch of 16 words per slice
+    auto add_batch = [&](const uint32_t (&v)[16][kSlices]) {
+        uint32_t t[8][kSlices];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
+        for (int k = 0; k < 8; ++k)
 #pragma unroll
             for (int q = 0; q < kSlices; ++q)
-                v[k][q] = 0;
-            if (!decltype(guard_rows)::value || i + k < N) {        // uniform
-                const char *row = reinterpret_cast<const char *>(p.packed + (int64_t)(i + k) * p.packed_stride + w0);
-                if (kWpl == 2) {
-                    const u32x4 r = packed_load2(reinterpret_cast<const uint64_t *>(row + lane_bytes));
-                    v[k][0] = r.x;
-                    v[k][1] = r.y;
-                    v[k][kSlices - 2] = r.z;
-                    v[k][kSlices - 1] = r.w;
-                } else {
-                    const u32x2 r = stream_load(reinterpret_cast<const u32x2 *>(row + lane_bytes));
-                    v[k][0] = r.x;
-                    v[k][1] = r.y;
+                csa(t[k][q], ones[q], ones[q], v[2 * k][q], v[2 * k + 1][q]);
+        add_pairs(t);
+    };
+    // One batch of 16 rows starting at row i, full-width loads, kSlicedInFlight rows at a time:
+    // the memory system gives the most with 24-32 KB of loads outstanding per compute unit, which
+    // 16 waves reach with two 1 KB loads each (all 16 rows of a batch at once: 256 KB, and 6 % less
+    // bandwidth).  The running sums pass through an empty asm statement after every group, so
+    // that the compiler can neither issue the next group's loads early nor postpone the adds.
+    // guard_rows: rows past N count as zeros.
+    auto count_rows = [&](int i, auto guard_rows) {
+        // the row base is uniform; each lane adds a small unsigned byte offset
+        const uint32_t lane_bytes = static_cast<uint32_t>(lane) * (8u * kWpl);
+        uint32_t t[8][kSlices];
+#pragma unroll
+        for (int k0 = 0; k0 < 16; k0 += kSlicedInFlight) {
+            uint32_t v[kSlicedInFlight][kSlices];
+#pragma unroll
+            for (int k = 0; k < kSlicedInFlight; ++k) {
+#pragma unroll
+                for (int q = 0; q < kSlices; ++q)
+                    v[k][q] = 0;
+                if (!decltype(guard_rows)::value || i + k0 + k < N) {        // uniform
+                    const char *row = reinterpret_cast<const char *>(p.packed + (int64_t)(i + k0 + k) * p.packed_stride + w0);
+                    if (kWpl == 2) {
+                        const u32x4 r = packed_load2(reinterpret_cast<const uint64_t *>(row + lane_bytes));
+                        v[k][0] = r.x;
+                        v[k][1] = r.y;
+                        v[k][kSlices - 2] = r.z;
+                        v[k][kSlices - 1] = r.w;
+                    } else {
+                        const u32x2 r = stream_load(reinterpret_cast<const u32x2 *>(row + lane_bytes));
+                        v[k][0] = r.x;
+                        v[k][1] = r.y;
+                    }
                 }
             }
+#pragma unroll
+            for (int k = 0; k < kSlicedInFlight; k += 2)
+#pragma unroll
+                for (int q = 0; q < kSlices; ++q)
+                    csa(t[(k0 + k) / 2][q], ones[q], ones[q], v[k][q], v[k + 1][q]);
+            if (kSlicedInFlight < 16) {
+#pragma unroll
+                for (int q = 0; q < kSlices; ++q)
+                    asm volatile("" : "+v"(ones[q]) : : "memory");
+            }
         }
+        add_pairs(t);
     };
     if (fast) {
         int i = 0;
         for (; i + 16 <= N; i += 16) {
-            uint32_t v[16][kSlices];
-            load_rows(i, v, std::false_type());
-            add_batch(v);
+            count_rows(i, std::false_type());
             if (kWaves > 1)
                 __builtin_amdgcn_s_barrier();
         }
         if (i < N) {
-            uint32_t v[16][kSlices];
-            load_rows(i, v, std::true_type());
-            add_batch(v);
+            count_rows(i, std::true_type());
             if (kWaves > 1)
                 __builtin_amdgcn_s_barrier();
         }
@@ -915,6 +939,37 @@ __device__ __forceinline__ void sliced_count(const Problem &p, int N, int64_t w0
         for (int b = 0; b < kPlanes - 4; ++b)
             out.v[4 + b][q] = hi[b][q];
     }
+}
+
+// Majority vote in the bit-sliced domain: compares the count of every coordinate with
+// K = floor(N/2) on all bit positions at once, from the top plane down.  plus = count > K, i.e.
+// S > 0; tie = count == K for even N, i.e. S == 0.
+template <int kPlanes>
+__device__ __forceinline__ void sliced_vote(const Planes<kPlanes> &pl, int N, uint32_t (&plus)[kSlices],
+                                            uint32_t (&tie)[kSlices])
+{
+    const uint32_t K = static_cast<uint32_t>(N) >> 1;
+    const uint32_t even = (N & 1) ? 0u : 0xFFFFFFFFu;
+#pragma unroll
+    for (int q = 0; q < kSlices; ++q) {
+        uint32_t gt = 0, eq = 0xFFFFFFFFu;
+#pragma unroll
+        for (int b = kPlanes - 1; b >= 0; --b) {
+            if ((K >> b) & 1u) {
+                eq &= pl.v[b][q];
+            } else {
+                gt |= eq & pl.v[b][q];
+                eq &= ~pl.v[b][q];
+            }
+        }
+        plus[q] = gt;
+        tie[q] = eq & even;
+    }
+}
+
+__device__ __forceinline__ float decode_vote(uint32_t plus, uint32_t tie)
+{
+    return plus ? 1.0f : (tie ? 0.0f : -1.0f);
 }
 
 // kWaves waves per workgroup, each with its own word group and its own LDS region.  With more
@@ -1031,26 +1086,59 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_sliced_kernel(FlatA
     }
     if (kApply) {
         // lane l owns coordinates 4*(l&15).. of word 4*s + (l>>4): 16 bytes of x per lane
-#pragma unroll 2
-        for (int s = 0; s < kSlicedWords / kWordsPerTile; ++s) {
-            const int wl = s * kWordsPerTile + (lane >> 4);
-            const int64_t j0 = (w0 + wl) * 64 + (lane & 15) * kVec;
-            if (j0 >= p.numel)
-                continue;
+        constexpr int kSteps = kSlicedWords / kWordsPerTile;        // 32 steps of 256 coordinates
+        auto step_coord = [&](int s) { return (w0 + s * kWordsPerTile + (lane >> 4)) * 64 + (lane & 15) * kVec; };
+        auto step_delta = [&](int s, float (&Delta)[4]) {
             uint32_t cnt[4];
-            unpack4(2 * wl + ((lane >> 3) & 1), (lane & 7) * 4, cnt);
-            if (j0 + kVec <= p.numel) {
-                f32x4 xv = x_load4(p.x + j0);
-                xv.x = lion_apply(xv.x, aggregate_votes(cnt[0], h), h);
-                xv.y = lion_apply(xv.y, aggregate_votes(cnt[1], h), h);
-                xv.z = lion_apply(xv.z, aggregate_votes(cnt[2], h), h);
-                xv.w = lion_apply(xv.w, aggregate_votes(cnt[3], h), h);
-                x_store4(xv, p.x + j0);
-            } else {
+            unpack4(2 * (s * kWordsPerTile + (lane >> 4)) + ((lane >> 3) & 1), (lane & 7) * 4, cnt);
 #pragma unroll
-                for (int k = 0; k < kVec; ++k)
-                    if (j0 + k < p.numel)
-                        p.x[j0 + k] = lion_apply(p.x[j0 + k], aggregate_votes(cnt[k], h), h);
+            for (int k = 0; k < 4; ++k)
+                Delta[k] = aggregate_votes(cnt[k], h);
+        };
+        if ((w0 + kSlicedWords) * 64 <= p.numel) {                  // uniform: the whole group is inside
+            // kXBatch loads of x in flight per wave.  What this phase costs is its stores: at N = 256,
+            // d = 1 G the pass takes 4.60 ms without the x phase, 5.24 ms with its loads only, 5.90 ms
+            // with its stores only and 6.89 ms with both (batches of 2 to 16 loads, ordinary instead of
+            // streaming accesses or a cheaper decoding of the vote change nothing or lose)
+            constexpr int kXBatch = 4;
+#pragma unroll 1
+            for (int s0 = 0; s0 < kSteps; s0 += kXBatch) {
+                f32x4 xv[kXBatch];
+#pragma unroll
+                for (int u = 0; u < kXBatch; ++u)
+                    xv[u] = x_load4(p.x + step_coord(s0 + u));
+#pragma unroll
+                for (int u = 0; u < kXBatch; ++u) {
+                    float Delta[4];
+                    step_delta(s0 + u, Delta);
+                    xv[u].x = lion_apply(xv[u].x, Delta[0], h);
+                    xv[u].y = lion_apply(xv[u].y, Delta[1], h);
+                    xv[u].z = lion_apply(xv[u].z, Delta[2], h);
+                    xv[u].w = lion_apply(xv[u].w, Delta[3], h);
+                    x_store4(xv[u], p.x + step_coord(s0 + u));
+                }
+            }
+        } else {
+#pragma unroll 1
+            for (int s = 0; s < kSteps; ++s) {
+                const int64_t j0 = step_coord(s);
+                if (j0 >= p.numel)
+                    continue;
+                float Delta[4];
+                step_delta(s, Delta);
+                if (j0 + kVec <= p.numel) {
+                    f32x4 xv = x_load4(p.x + j0);
+                    xv.x = lion_apply(xv.x, Delta[0], h);
+                    xv.y = lion_apply(xv.y, Delta[1], h);
+                    xv.z = lion_apply(xv.z, Delta[2], h);
+                    xv.w = lion_apply(xv.w, Delta[3], h);
+                    x_store4(xv, p.x + j0);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < kVec; ++k)
+                        if (j0 + k < p.numel)
+                            p.x[j0 + k] = lion_apply(p.x[j0 + k], Delta[k], h);
+                }
             }
         }
     }
@@ -1085,27 +1173,9 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_encode_kernel(FlatA
     if (kWaves > 1)
         __builtin_amdgcn_s_barrier();        // start the write burst together
 
-    uint32_t res[2][kSlices];                // vote: plus, tie
-    if (h.mode == DLION_VOTE) {
-        // bit-sliced compare of the count with K = floor(N/2), from the top plane down:
-        // gt = count > K, eq = count == K on every bit position at once
-        const uint32_t K = static_cast<uint32_t>(h.N) >> 1;
-#pragma unroll
-        for (int q = 0; q < kSlices; ++q) {
-            uint32_t gt = 0, eq = 0xFFFFFFFFu;
-#pragma unroll
-            for (int b = kPlanes - 1; b >= 0; --b) {
-                if ((K >> b) & 1u) {
-                    eq &= pl.v[b][q];
-                } else {
-                    gt |= eq & pl.v[b][q];
-                    eq &= ~pl.v[b][q];
-                }
-            }
-            res[0][q] = gt;                  // S > 0
-            res[1][q] = eq;                  // S == 0 (written only when N is even)
-        }
-    }
+    uint32_t res[2][kSlices];                // vote: plus (S > 0), tie (S == 0; written only when N is even)
+    if (h.mode == DLION_VOTE)
+        sliced_vote<kPlanes>(pl, h.N, res[0], res[1]);
     const int64_t wl0 = w0 + (int64_t)lane * kWpl;
     const bool whole = w0 + kSlicedWords <= W;              // uniform: every lane's words exist
 #pragma unroll 1
@@ -1159,11 +1229,6 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_encode_kernel(FlatA
 // Worker side of the down-link: decode the planes and take the step.  Same tiling as the
 // per-nibble server kernel: lane l owns coordinates 4l..4l+3 of a 256-coordinate tile, i.e.
 // nibble (l & 15) of word (l >> 4); the guarded path gives lane l bit l of one word.
-__device__ __forceinline__ float decode_vote(uint32_t plus, uint32_t tie)
-{
-    return plus ? 1.0f : (tie ? 0.0f : -1.0f);
-}
-
 // One wave owns kLineSubs = 4 consecutive sub-tiles = 16 words = one 128-byte line of every
 // plane, so that each line is read by exactly one wave (and one L2): lane l loads dword
 // (l & 31) of the line, and for sub-tile s takes the dword that holds its nibble from lane
@@ -1376,24 +1441,24 @@ __global__ __launch_bounds__(kLanes) void apply_kernel(Addr addr, Hyper h)
 
 // ---------------------------------------------------------------- memory-rate probe
 // None of the method's arithmetic: wave t reads the t-th 1 KB piece of each of `rows` rows (128
-// bits per lane, up to 16 rows in flight), folds them with XOR so that no load can be dropped, and
+// bits per lane, kBatch rows in flight), folds them with XOR so that no load can be dropped, and
 // writes one 1 KB piece (kWrite) or nothing.  rows = 1 with kWrite is a plain copy; rows = 16 has
 // the 16 : 1 read : write byte mix of counting 256 packed streams into uint16 counts.  Same launch
 // style as the real kernels: one-wave workgroups, streaming accesses, plain tile numbering.
-template <bool kWrite>
+template <bool kWrite, int kBatch>
 __global__ __launch_bounds__(kLanes) void membench_kernel(const u32x4 *src, int64_t row_stride, int32_t rows,
                                                           u32x4 *dst, int64_t first_piece)
 {
     const int64_t at = (first_piece + blockIdx.x) * kLanes + threadIdx.x;      // in 16-byte units
     u32x4 acc = {0u, 0u, 0u, 0u};
     int r = 0;
-    for (; r + 16 <= rows; r += 16) {
-        u32x4 v[16];
+    for (; r + kBatch <= rows; r += kBatch) {
+        u32x4 v[kBatch];
 #pragma unroll
-        for (int k = 0; k < 16; ++k)
+        for (int k = 0; k < kBatch; ++k)
             v[k] = __builtin_nontemporal_load(src + (int64_t)(r + k) * row_stride + at);
 #pragma unroll
-        for (int k = 0; k < 16; ++k)
+        for (int k = 0; k < kBatch; ++k)
             acc ^= v[k];
     }
     for (; r < rows; ++r)

@@ -52,8 +52,8 @@ int main()
     EXPECT(dlion_worker_step_pw(fA, 128, A, 128, DLION_F32, pA, 2, 128, 4, nullptr, fA, nullptr), DLION_EINVAL);
     EXPECT(dlion_step_pw(fA, fA, 128, A, 128, DLION_F32, 128, 4, DLION_VOTE, nullptr, fA, 1e-4f, 0.1f, nullptr, 0, nullptr, nullptr), DLION_EINVAL);
     EXPECT(dlion_global_lion_step(fA, fA, 100, A, 128, DLION_F32, 128, 4, 0.9f, 0.99f, 1e-4f, 0.1f, nullptr, nullptr), DLION_EINVAL);
-        EXPECT(dlion_membench(A, 4096, 2, A, 1000, 1, 0, nullptr), DLION_EINVAL);
-    EXPECT(dlion_membench(A + 4, 4096, 1, A, 1024, 1, 0, nullptr), DLION_EALIGN);
+        EXPECT(dlion_membench(A, 4096, 2, A, 1000, 1, 16, 0, nullptr), DLION_EINVAL);
+    EXPECT(dlion_membench(A + 4, 4096, 1, A, 1024, 1, 16, 0, nullptr), DLION_EALIGN);
 
     // host-only helpers
     EXPECT(dlion_delta_planes(3, DLION_VOTE), 1);
@@ -122,7 +122,8 @@ int main()
             EXPECT(dlion_aggregate_apply(fA, pA, 1100, 70001, N, DLION_AVG, 1e-4f, 0.1f, cA, nullptr), DLION_ELAUNCH);
             EXPECT(dlion_aggregate_encode(pA, 1100, 70001, N, DLION_AVG, pA, 1100, nullptr), DLION_ELAUNCH);
             EXPECT(dlion_apply_encoded(fA, pA, 1100, 70001, N, DLION_VOTE, 1e-4f, 0.1f, nullptr), DLION_ELAUNCH);
-            EXPECT(dlion_membench(A, 4096, N, A, 4096, 1, 0, nullptr), DLION_ELAUNCH);
+            EXPECT(dlion_membench(A, 4096, N, A, 4096, 1, 4, 0, nullptr), DLION_ELAUNCH);
+            EXPECT(dlion_membench(A, 4096, N, A, 4096, 1, 3, 0, nullptr), DLION_EINVAL);
         }
         EXPECT(dlion_step_mt_ws(segs.data(), dev, 5, DLION_F32, 20, DLION_VOTE, 0.9f, 0.99f, 1e-4f, 0.1f, nullptr, 0, nullptr, A, 1 << 20, nullptr), DLION_ELAUNCH);
     }
