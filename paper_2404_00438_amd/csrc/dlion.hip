@@ -20,6 +20,13 @@ inline int64_t words_for(int64_t numel) { return (numel + 63) / 64; }
 
 inline bool power_of_two(int32_t n) { return n > 0 && (n & (n - 1)) == 0; }
 
+#define DLION_TRY(expr)                 \
+    do {                                \
+        const dlion_status st_ = (expr); \
+        if (st_ != DLION_OK)            \
+            return st_;                 \
+    } while (0)
+
 // Launch-shape overrides (dlion_set_tuning); every field -1 = the library decides.
 dlion_tuning g_tuning = {-1, -1, -1, -1, -1, -1, -1, -1, -1};
 inline const dlion_tuning &tuning() { return g_tuning; }
@@ -226,23 +233,29 @@ dlion_status launch_step_once(const Addr &addr, const Hyper &h, dlion_dtype g_dt
 // By tiles.  Workgroups are handed to the 8 XCDs round-robin and every XCD works through its own
 // share at its own pace, so over a long launch the XCDs drift apart and the window of addresses in
 // flight widens; launches of kBlockTiles tiles bring them back together (N = 8, bf16: d = 1.3 G
-// 77.6 -> 80.2 % of peak, d = 350 M 76.9 -> 79.1 %, d = 124 M unchanged; a launch boundary costs
-// about 4.5 us, 0.5 % at this size).
+// 77.6 -> 80.2 % of peak with 67 M coordinates per launch, 81.2 % with 134 M; d = 350 M 76.9 ->
+// 79.1 %; d = 124 M unchanged).  A launch boundary costs about 4.5 us when launches are short
+// (16384 tiles) and nothing measurable from 131072 tiles on.
 //
 // By workers.  One launch over all N rows keeps 2N + 1 streams (and as many pages) open across
 // the chip at once, and from N = 16 on that costs more bandwidth than handing the votes from one
 // launch over kPassWorkers workers to the next (fused step, bf16 gradients, d = 350 M, N = 32:
-// one launch 20.7 ms, launches over 8 workers 18.5 ms; N = 12 gains nothing, and below ~16 M
-// coordinates the extra launches cost what they save).  The worker step needs no hand-over.  The
-// fused step hands the votes on in the caller's workspace or, without one, in the caller's counts
-// array, and stays one launch per block when it has neither: the library owns no memory.  All
-// launches of one block of tiles run before the next block starts, so the hand-over is still in
-// the memory-side cache when it is read back.
+// one launch 20.6 ms, launches over 8 workers 18.0 ms; 6 / 7 / 9 / 10 / 11 workers per launch are
+// all 0.1-1.5 % slower than 8, 16 lose 5 %; N = 12 gains nothing, and below ~16 M coordinates the
+// extra launches cost what they save).  The worker step needs no hand-over.  The fused step hands
+// the votes on in the caller's workspace or, without one, in the caller's counts array, and stays
+// one launch per block when it has neither: the library owns no memory.  All launches of one
+// block of tiles run before the next block starts, so the hand-over is still in the memory-side
+// cache when it is read back (a running uint16 count handed on over the whole of d = 350 M
+// instead: 19.2 against 18.5 ms).
 //
 // Hand-over formats (Carry): in a workspace and with at most kNibblePasses launches, every
 // launch but the last writes its own plane of 4-bit partial counts (0.5 B per coordinate written,
-// and read once by the last launch); with more launches a running uint16 count per coordinate (2 B
-// read + 2 B written per launch); in the counts array the running count, indexed by coordinate.
+// and read once by the last launch: 3 B per coordinate at N = 32, 0.9 % on top of the step's
+// algorithmic bytes, which is most of what separates it from the single-launch rate at N = 8);
+// with more launches a running uint16 count per coordinate (2 B read + 2 B written per launch);
+// in the counts array the running count, indexed by coordinate.  Block sizes between 131072 and
+// 524288 tiles are within 0.15 % of each other at N = 32.
 constexpr int kPassWorkers = 8;
 constexpr int kPassMinN = 16;
 constexpr int kNibblePasses = 8;            // at most 7 planes of partial counts
@@ -372,16 +385,51 @@ dlion_status launch_step(const Addr &addr, const Hyper &h0, dlion_dtype g_dtype,
     return DLION_OK;
 }
 
+// Launches of the server-side and update kernels are cut like the step's (XCDs drift apart over a
+// long launch: d = 1.3 G, dlion_apply in one launch 78.7 % of peak against 91.9 % at d = 124 M), by
+// bytes moved rather than by tiles, since their bytes per coordinate span 3 to 40: about 6 GB per
+// launch, which is what a launch of the step over 8 workers moves.  A grid unit of the kernel covers
+// tiles_per_unit tiles and moves about bytes_per_coord bytes per coordinate.
+constexpr int64_t kBlockBytes = (int64_t)6 << 30;
+// The bit-sliced kernels, whose workgroups read for a long time and then write in one burst, want
+// much shorter launches: with one round of workgroups per launch (131072 tiles: 256 workgroups of
+// 16 waves) the whole chip reads together and then writes together (N = 256, d = 1 G, fused
+// update: one launch 6.88 ms, 131072 / 262144 / 524288 / 1048576 tiles per launch 6.04 / 6.02 /
+// 6.12 / 6.30 ms; counts only 5.09 against 5.05 ms), as long as a launch still moves about 1 GB.
+constexpr int64_t kSlicedBlockTiles = 16 * kResidentWaves;
+constexpr int64_t kSlicedBlockBytes = (int64_t)1 << 30;
+
+template <class Addr, class Launch>
+dlion_status launch_in_blocks(const Addr &addr, int64_t units, int64_t tiles_per_unit, int64_t bytes_per_coord,
+                              bool sliced, Launch launch_one)
+{
+    const int64_t forced = tuning().block_tiles;           // 0 = all in one launch
+    int64_t tiles = (sliced ? kSlicedBlockBytes : kBlockBytes) / (kTile * bytes_per_coord);
+    if (sliced && tiles < kSlicedBlockTiles)
+        tiles = kSlicedBlockTiles;
+    int64_t block = forced > 0 ? forced / tiles_per_unit : (forced == 0 ? units : tiles / tiles_per_unit);
+    if (block < 1)
+        block = 1;
+    Addr a = addr;
+    for (int64_t first = 0; first < units; first += block) {
+        a.first_tile = first;
+        DLION_TRY(launch_one(a, first + block < units ? block : units - first));
+    }
+    return DLION_OK;
+}
+
 template <class Addr>
 dlion_status launch_aggregate(const Addr &addr, const Hyper &h, bool apply, bool counts, hipStream_t s)
 {
-    const dim3 grid = grid_for(addr.total_tiles), block(kLanes);
-    if (apply && counts)
-        return launch(aggregate_kernel<true, true, Addr>, grid, block, 0, s, addr, h);
-    else if (apply)
-        return launch(aggregate_kernel<true, false, Addr>, grid, block, 0, s, addr, h);
-    else
-        return launch(aggregate_kernel<false, true, Addr>, grid, block, 0, s, addr, h);
+    const int64_t bytes = h.N / 8 + 1 + (apply ? 8 : 0) + (counts ? 2 : 0);
+    return launch_in_blocks(addr, addr.total_tiles, 1, bytes, false, [&](const Addr &a, int64_t n) {
+        const dim3 grid = grid_for(n), block(kLanes);
+        if (apply && counts)
+            return launch(aggregate_kernel<true, true, Addr>, grid, block, 0, s, a, h);
+        if (apply)
+            return launch(aggregate_kernel<true, false, Addr>, grid, block, 0, s, a, h);
+        return launch(aggregate_kernel<false, true, Addr>, grid, block, 0, s, a, h);
+    });
 }
 
 // Bit-sliced counting (flat buffers): planes = bits needed for a count 0..N; waves per
@@ -391,14 +439,19 @@ dlion_status launch_sliced_shape(const FlatAddr &addr, const Hyper &h, bool appl
 {
     const int64_t W = words_for(addr.p.numel);
     const int64_t groups = (W + kSlicedWords - 1) / kSlicedWords;
-    const dim3 grid(static_cast<uint32_t>((groups + kWaves - 1) / kWaves)), block(kLanes * kWaves);
     const size_t lds = static_cast<size_t>(kWaves) * kPlanes * kSlicedLdsPerPlane * sizeof(uint32_t);
-    if (apply && counts)
-        return launch(aggregate_sliced_kernel<kPlanes, kWaves, true, true>, grid, block, lds, s, addr, h);
-    else if (apply)
-        return launch(aggregate_sliced_kernel<kPlanes, kWaves, true, false>, grid, block, lds, s, addr, h);
-    else
-        return launch(aggregate_sliced_kernel<kPlanes, kWaves, false, true>, grid, block, lds, s, addr, h);
+    // a word group of kSlicedWords words is kSlicedWords / kWordsPerTile tiles; a workgroup takes kWaves groups
+    const int64_t bytes = h.N / 8 + 1 + (apply ? 8 : 0) + (counts ? 2 : 0);
+    return launch_in_blocks(addr, (groups + kWaves - 1) / kWaves, kWaves * (kSlicedWords / kWordsPerTile), bytes,
+                            kWaves > 1, [&](FlatAddr a, int64_t n) {
+        a.first_tile *= kWaves;                          // the kernel counts in word groups
+        const dim3 grid = grid_for(n), block(kLanes * kWaves);
+        if (apply && counts)
+            return launch(aggregate_sliced_kernel<kPlanes, kWaves, true, true>, grid, block, lds, s, a, h);
+        if (apply)
+            return launch(aggregate_sliced_kernel<kPlanes, kWaves, true, false>, grid, block, lds, s, a, h);
+        return launch(aggregate_sliced_kernel<kPlanes, kWaves, false, true>, grid, block, lds, s, a, h);
+    });
 }
 
 // Waves per workgroup of the bit-sliced kernels (they walk the streams in lockstep and write
@@ -459,7 +512,9 @@ dlion_status launch_sliced(const FlatAddr &addr, const Hyper &h, bool apply, boo
 template <class Addr> dlion_status launch_apply(const Addr &addr, const Hyper &h, hipStream_t s)
 {
     // no occupancy cap here: it only loses (d = 124 M: 88.7 % uncapped, 81 % with 16-24 waves per compute unit)
-    return launch(apply_kernel<Addr>, grid_for(addr.total_tiles), dim3(kLanes), 0, s, addr, h);
+    return launch_in_blocks(addr, addr.total_tiles, 1, 10, false, [&](const Addr &a, int64_t n) {
+        return launch(apply_kernel<Addr>, grid_for(n), dim3(kLanes), 0, s, a, h);
+    });
 }
 
 // Down-link message: planes needed for Delta.
@@ -479,8 +534,11 @@ dlion_status launch_encode_shape(const FlatAddr &addr, const Hyper &h, const Del
 {
     const int64_t W = words_for(addr.p.numel);
     const int64_t groups = (W + kSlicedWords - 1) / kSlicedWords;
-    const dim3 grid(static_cast<uint32_t>((groups + kWaves - 1) / kWaves)), block(kLanes * kWaves);
-    return launch(aggregate_encode_kernel<kPlanes, kWaves>, grid, block, 0, s, addr, h, out);
+    return launch_in_blocks(addr, (groups + kWaves - 1) / kWaves, kWaves * (kSlicedWords / kWordsPerTile),
+                            h.N / 8 + 1 + out.n_planes / 8, kWaves > 1, [&](FlatAddr a, int64_t n) {
+        a.first_tile *= kWaves;
+        return launch(aggregate_encode_kernel<kPlanes, kWaves>, grid_for(n), dim3(kLanes * kWaves), 0, s, a, h, out);
+    });
 }
 
 template <int kPlanes>
@@ -547,13 +605,6 @@ dlion_status check_rows(const void *p, int64_t stride, int64_t extent, int32_t N
 inline uintptr_t grad_size(dlion_dtype t) { return t == DLION_BF16 ? 2 : 4; }
 inline bool dtype_ok(dlion_dtype t) { return t == DLION_F32 || t == DLION_BF16; }
 inline bool mode_ok(dlion_mode m) { return m == DLION_VOTE || m == DLION_AVG; }
-
-#define DLION_TRY(expr)                 \
-    do {                                \
-        const dlion_status st_ = (expr); \
-        if (st_ != DLION_OK)            \
-            return st_;                 \
-    } while (0)
 
 FlatAddr flat_addr(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride, int64_t d,
                    uint64_t *packed, int64_t packed_stride, uint16_t *counts)
@@ -990,21 +1041,23 @@ dlion_status dlion_apply_encoded(float *x, const uint64_t *delta, int64_t delta_
     const Hyper h = make_hyper(N, mode, 0.0f, 0.0f, lr, lambda);
     const FlatAddr a = flat_addr(x, nullptr, 0, nullptr, 0, d, nullptr, 0, nullptr);
     const DeltaOut in = {const_cast<uint64_t *>(delta), delta_stride, planes};
-    const dim3 grid(static_cast<uint32_t>((d + kLineCoords - 1) / kLineCoords)), block(kLanes);
     hipStream_t s = static_cast<hipStream_t>(stream);
     // resident waves per compute unit, capped like the fused step's (a wave has 4 KB of x and a
     // line of every plane in flight): N = 256, d = 1 G, vote (2 planes) uncapped 80.4 %, 12 waves
     // 84.5 %, 16 waves 82.7 %; average (9 planes) uncapped 75.1 %, 12 waves 76.2 %, 16 waves 79.1 %
     const int env_k = tuning().apply_blocks;
     const size_t lds = lds_reservation(env_k >= 0 ? env_k : (planes <= 2 ? 12 : 16));
-    if (planes <= 2)
-        return launch(apply_encoded_kernel<2>, grid, block, lds, s, a, h, in);
-    else if (planes <= 5)
-        return launch(apply_encoded_kernel<5>, grid, block, lds, s, a, h, in);
-    else if (planes <= 9)
-        return launch(apply_encoded_kernel<9>, grid, block, lds, s, a, h, in);
-    else
-        return launch(apply_encoded_kernel<16>, grid, block, lds, s, a, h, in);
+    return launch_in_blocks(a, (d + kLineCoords - 1) / kLineCoords, kLineSubs, 8 + planes / 8 + 1, false,
+                            [&](const FlatAddr &b, int64_t n) {
+        const dim3 grid = grid_for(n), block(kLanes);
+        if (planes <= 2)
+            return launch(apply_encoded_kernel<2>, grid, block, lds, s, b, h, in);
+        if (planes <= 5)
+            return launch(apply_encoded_kernel<5>, grid, block, lds, s, b, h, in);
+        if (planes <= 9)
+            return launch(apply_encoded_kernel<9>, grid, block, lds, s, b, h, in);
+        return launch(apply_encoded_kernel<16>, grid, block, lds, s, b, h, in);
+    });
 }
 
 dlion_status dlion_worker_step_pw(float *m, int64_t m_stride, const void *g, int64_t g_stride,

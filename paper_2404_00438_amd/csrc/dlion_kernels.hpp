@@ -738,7 +738,7 @@ __device__ __forceinline__ void agg_subtile_guarded(const Problem &p, int64_t t,
 template <bool kApply, bool kCounts, class Addr>
 __global__ __launch_bounds__(kLanes) void aggregate_kernel(Addr addr, Hyper h)
 {
-    const int64_t tile = quad_tile_index();
+    const int64_t tile = addr.first_tile + quad_tile_index();
     if (tile >= addr.total_tiles)
         return;
     const int lane = threadIdx.x;
@@ -990,7 +990,8 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_sliced_kernel(FlatA
     uint32_t(*lds)[kSlicedLdsPerPlane] =
         reinterpret_cast<uint32_t(*)[kSlicedLdsPerPlane]>(sliced_lds + wave * kPlanes * kSlicedLdsPerPlane);
     const int64_t W = (p.numel + 63) >> 6;
-    const int64_t w0 = ((int64_t)blockIdx.x * kWaves + wave) * kSlicedWords;   // first word of the wave
+    // first word of the wave (addr.first_tile: the first word group of this launch)
+    const int64_t w0 = (addr.first_tile + (int64_t)blockIdx.x * kWaves + wave) * kSlicedWords;
     if (w0 >= W)
         return;
     Planes<kPlanes> pl;
@@ -1165,7 +1166,7 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_encode_kernel(FlatA
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t W = (p.numel + 63) >> 6;
-    const int64_t w0 = ((int64_t)blockIdx.x * kWaves + wave) * kSlicedWords;
+    const int64_t w0 = (addr.first_tile + (int64_t)blockIdx.x * kWaves + wave) * kSlicedWords;
     if (w0 >= W)
         return;
     Planes<kPlanes> pl;
@@ -1240,7 +1241,7 @@ template <int kMaxPlanes>
 __global__ __launch_bounds__(kLanes) void apply_encoded_kernel(FlatAddr addr, Hyper h, DeltaOut in)
 {
     const Problem &p = addr.p;
-    const int64_t t = blockIdx.x;                               // line index
+    const int64_t t = addr.first_tile + blockIdx.x;             // line index (first_tile: first line of this launch)
     const int lane = threadIdx.x;
     const bool full = (t + 1) * kLineCoords <= p.numel;
     if (full) {
@@ -1414,7 +1415,7 @@ __global__ __launch_bounds__(kLanes) void global_lion_kernel(FlatAddr addr, Hype
 template <class Addr>
 __global__ __launch_bounds__(kLanes) void apply_kernel(Addr addr, Hyper h)
 {
-    const int64_t tile = wave_tile_index();
+    const int64_t tile = addr.first_tile + wave_tile_index();
     if (tile >= addr.total_tiles)
         return;
     const int lane = threadIdx.x;

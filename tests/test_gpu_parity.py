@@ -550,6 +550,44 @@ def test_workspace_sizes():
     assert dl.dlion_step_mt_workspace_bytes(78125, 16) == dl.dlion_step_workspace_bytes(20_000_000, 16)
 
 
+@pytest.mark.parametrize("sliced", [True, False], ids=["bit-sliced", "per-nibble"])
+def test_server_side_calls_cut_into_several_launches(sliced, tune):
+    """Large problems run the server-side and update kernels as several launches over blocks of
+    coordinates; forced here at small sizes (8 tiles per launch; a bit-sliced workgroup is at least 32)."""
+    tune(block_tiles=8, sliced_min_workers=1 if sliced else 100000, sliced_waves=8 if sliced else -1)
+    rng = np.random.default_rng(616)
+    for N, d in ((3, 5000), (8, 70_001), (33, 20_000), (300, 9000)):
+        W = dl.words_for(d)
+        bits = rng.random((N, W * 64)) < 0.55
+        bits[:, d:] = False
+        words = np.packbits(bits, axis=1, bitorder="little").view("<u8")
+        want = oracle.aggregate_packed(np.ascontiguousarray(words), d)
+        packed = strided_rows(N, W, W + 1, torch.int64, DEV)
+        packed.copy_(torch.from_numpy(words.view(np.int64)))
+        counts = torch.full((d,), -1, dtype=torch.int16, device=DEV)
+        dl.dlion_aggregate(packed, d, counts)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(counts), want), f"N={N} d={d}: counts"
+        for mode in (dl.VOTE, dl.AVG):
+            announce("several launches", "sliced" if sliced else "per-nibble", "N", N, "d", d, "mode", mode)
+            xv = rng.normal(0, 0.02, d).astype(np.float32)
+            xn = xv.copy()
+            oracle.apply(xn, want, N, mode, 0.25, 0.5)
+            x1, x2, x3 = (torch.from_numpy(xv).to(DEV) for _ in range(3))
+            counts2 = torch.full((d,), -1, dtype=torch.int16, device=DEV)
+            dl.dlion_apply(x1, counts, N, mode, 0.25, 0.5)
+            dl.dlion_aggregate_apply(x2, packed, mode, 0.25, 0.5, counts=counts2)
+            P = dl.dlion_delta_planes(N, mode)
+            delta = torch.full((P, W), -1, dtype=torch.int64, device=DEV)
+            dl.dlion_aggregate_encode(packed, d, mode, delta)
+            dl.dlion_apply_encoded(x3, delta, N, mode, 0.25, 0.5)
+            torch.cuda.synchronize()
+            assert np.array_equal(to_np(counts2), want)
+            assert np.array_equal(to_np(delta), oracle.encode_delta(want, N, mode))
+            for tag, x in (("apply", x1), ("aggregate_apply", x2), ("apply_encoded", x3)):
+                assert_f32_equal(to_np(x), xn, f"{tag} N={N} d={d} mode={mode}: x")
+
+
 def test_randomized_shapes_strides_and_flags():
     """Seeded random sweep over d, N, row strides (aligned or not), gradient dtype, aggregation and
     optional outputs, two steps each, fused and unfused, against the oracle."""
