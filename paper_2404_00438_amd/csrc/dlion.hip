@@ -118,15 +118,14 @@ dlion_status launch(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds, hip
 // HBM delivers the most when the chip keeps only a modest, compact window of addresses in
 // flight.  A wave of the worker/fused kernels has one worker's loads outstanding at a time
 // (1 KB of m and 0.5 or 1 KB of g), and the number of resident waves per compute unit is capped:
-// bf16 gradients, 12 / 13 / 14 / 16 waves give 78.5 / 80.1 / 78.5 / 77.3 % of peak at N = 8,
+// bf16 gradients, 11 / 12 / 14 / 16 waves give 78.5 / 80.1 / 78.5 / 77.3 % of peak at N = 8,
 // d = 124 M, and 79.3 / 80.3 / 79.9 / 79.4 % at d = 1.3 G; the launches of a split step that only
-// hand their votes on want one more (N = 32, d = 350 M: 13 / 14 / 16 waves 77.9 / 79.4 / 78.8 %);
-// fp32 gradients 12 (tensor list, N = 16: 12 / 13 / 14 waves 79.1 / 79.1 / 77.2 %).  Issuing two
-// workers' loads back to back with 9 waves comes within 0.5 % at N = 8 but loses 2 % in the split
-// step; uncapped the kernel reaches 68 %.  A tensor list takes one wave more: its waves start
+// hand their votes on want 14 (N = 32, d = 350 M: 12 / 14 / 16 waves 80.0 / 80.9 / 80.3 %), its
+// last launches 16-18; fp32 gradients 11-12 (tensor list, N = 16: 11 / 12 / 14 waves 79.1 / 79.1 /
+// 77.2 %).  Issuing two workers' loads back to back with fewer waves is 0.5-4 % slower; uncapped
+// the kernel reaches 68 %.  A tensor list takes one wave more for a whole step: its waves start
 // with a table lookup during which they have nothing in flight.  The cap is applied by reserving
-// (unused) dynamic LDS per workgroup: a compute unit has 160 KB, so a reservation of 160 KB / k
-// admits k workgroups.
+// (unused) dynamic LDS per workgroup (lds_reservation).
 //
 // What was tried and dropped for many workers in one launch: 16-wave workgroups walking over
 // the workers in lockstep cut the per-CU translation-cache misses 15x at N = 32 (5.5 M against
@@ -142,11 +141,19 @@ constexpr size_t kLdsPerCu = 160 * 1024;
 constexpr size_t kMaxDynamicLds = 160 * 1024;
 constexpr int64_t kResidentWaves = 256 * 32;   // one-wave workgroups the 256 compute units hold at once
 
+// LDS reservation that admits at most `blocks_per_cu` workgroups per compute unit.  The 160 KB are
+// handed out in units of 1280 bytes (128 per compute unit), so the caps that can be reached are
+// floor(128 / n): 32, 25, 21, 18, 16, 14, 12, 11, 10, 9, 8 ...; 13 and 15 do not exist (measured:
+// reservations asking for 14 and 15, or for 16 and 17, run at the same speed).
+constexpr size_t kLdsGranule = 1280;
+
 inline size_t lds_reservation(int blocks_per_cu)
 {
     if (blocks_per_cu <= 0)
         return 0;
-    size_t bytes = (kLdsPerCu / static_cast<size_t>(blocks_per_cu)) & ~static_cast<size_t>(1023);
+    const size_t granules = kLdsPerCu / kLdsGranule;                              // 128
+    const size_t n = granules / (static_cast<size_t>(blocks_per_cu) + 1) + 1;     // smallest n with granules / n <= cap
+    const size_t bytes = n * kLdsGranule;
     return bytes > kMaxDynamicLds ? kMaxDynamicLds : bytes;
 }
 
@@ -171,7 +178,7 @@ LaunchShape step_shape(int32_t N, bool wide_g, StepRole role)
     if (forced >= 0) {
         s.blocks_per_cu = forced;
     } else {
-        const int waves = wide_g ? (role == kLastPass ? 13 : 12) : (role == kWholeStep ? 13 : (role == kHandOn ? 14 : 17));
+        const int waves = wide_g ? (role == kLastPass ? 12 : 11) : (role == kWholeStep ? 12 : (role == kHandOn ? 14 : 16));
         s.blocks_per_cu = s.unroll == 1 ? waves : (waves * 3 / 2 / s.unroll < 3 ? 3 : waves * 3 / 2 / s.unroll);
     }
     return s;
@@ -1043,10 +1050,11 @@ dlion_status dlion_apply_encoded(float *x, const uint64_t *delta, int64_t delta_
     const DeltaOut in = {const_cast<uint64_t *>(delta), delta_stride, planes};
     hipStream_t s = static_cast<hipStream_t>(stream);
     // resident waves per compute unit, capped like the fused step's (a wave has 4 KB of x and a
-    // line of every plane in flight): N = 256, d = 1 G, vote (2 planes) uncapped 80.4 %, 12 waves
-    // 84.5 %, 16 waves 82.7 %; average (9 planes) uncapped 75.1 %, 12 waves 76.2 %, 16 waves 79.1 %
+    // line of every plane in flight): d = 1.3 G, vote (2 planes) 11 / 12 / 14 / 16 waves 84.8 / 84.5 /
+    // 82.5 / 81.4 % of peak, average at N = 8 (4 planes) 82.6 / 84.5 / 83.2 / 80.3 %; d = 350 M,
+    // average at N = 32 (6 planes) 79.2 / 83.3 / 86.2 / 86.6 %
     const int env_k = tuning().apply_blocks;
-    const size_t lds = lds_reservation(env_k >= 0 ? env_k : (planes <= 2 ? 12 : 16));
+    const size_t lds = lds_reservation(env_k >= 0 ? env_k : (planes <= 5 ? 12 : 16));
     return launch_in_blocks(a, (d + kLineCoords - 1) / kLineCoords, kLineSubs, 8 + planes / 8 + 1, false,
                             [&](const FlatAddr &b, int64_t n) {
         const dim3 grid = grid_for(n), block(kLanes);
