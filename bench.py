@@ -178,7 +178,7 @@ def run_workload(name, steps, warmup, dev, with_cpu_baseline=False):
     if w.g_dist == "packed_bernoulli":
         # vote-only pass: N pre-packed sign streams in, counts out
         W = dl.words_for(w.d)
-        packed = wl.random_packed(w.N, W, dev, seed=w.seed)
+        packed = wl.random_packed(w.N, W, dev, seed=w.seed, row_stride=wl.padded_words(W))
         counts = torch.empty(w.d, dtype=torch.int16, device=dev)
         kernel = "dlion_aggregate (packed words in, uint16 counts out)"
         metric = "votes/s (d*N per vote-only pass)"

@@ -385,6 +385,8 @@ typedef struct dlion_tuning {
     int32_t apply_blocks;       /* dlion_apply_encoded: resident workgroups per compute unit, 0 = no cap              */
     int32_t blocks_per_cu_pass; /* as blocks_per_cu, for the launches of a step that only hand their votes on        */
     int64_t block_tiles;        /* worker/fused kernels: tiles (256 coordinates) per launch, 0 = all in one launch    */
+    int32_t group_blocks;       /* server side, few-worker kernel: resident 8-wave workgroups per compute unit, 0 = no cap */
+    int32_t group_max_workers;  /* server side: the few-worker kernel for every call with N up to this (0 = never, at most 120) */
 } dlion_tuning;
 
 /* Fills *t with -1 everywhere. */

@@ -55,6 +55,7 @@ class Tuning(ctypes.Structure):
         ("unroll", ctypes.c_int32), ("blocks_per_cu", ctypes.c_int32), ("pass_workers", ctypes.c_int32),
         ("step_quads", ctypes.c_int32), ("sliced_waves", ctypes.c_int32), ("sliced_min_workers", ctypes.c_int32),
         ("apply_blocks", ctypes.c_int32), ("blocks_per_cu_pass", ctypes.c_int32), ("block_tiles", ctypes.c_int64),
+        ("group_blocks", ctypes.c_int32), ("group_max_workers", ctypes.c_int32),
     ]
 
 

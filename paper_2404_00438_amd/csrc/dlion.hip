@@ -28,7 +28,7 @@ inline bool power_of_two(int32_t n) { return n > 0 && (n & (n - 1)) == 0; }
     } while (0)
 
 // Launch-shape overrides (dlion_set_tuning); every field -1 = the library decides.
-dlion_tuning g_tuning = {-1, -1, -1, -1, -1, -1, -1, -1, -1};
+dlion_tuning g_tuning = {-1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1};
 inline const dlion_tuning &tuning() { return g_tuning; }
 
 // Scratch of dlion_step_noalloc: device memory inside the library's code object, so that the entry
@@ -469,14 +469,11 @@ dlion_status launch_sliced_shape(const FlatAddr &addr, const Hyper &h, bool appl
 constexpr int kSlicedWaves = 8;
 constexpr int kSliced16MinWorkers = 128;
 
-// Flat buffers take the bit-sliced kernel: with 128-bit streaming count stores it beats the
-// per-nibble kernel at every N (d = 350 M, counts only, N = 2 / 8 / 16: 0.150 / 0.188 / 0.245 ms
-// against 0.391 / 0.313 / 0.433 ms; with the weight update fused 0.471 / 0.520 / 0.592 against
-// 0.540 / 0.580 / 0.697 ms).  The exception is the fused update at small d: a bit-sliced wave owns
-// 8192 coordinates and walks their x in 32 dependent steps, which few waves cannot hide (d = 4 M,
-// N = 8: 21 us against 8 us; d = 16 M: 33 against 27 us; d = 64 M, N = 4: 95 against 120 us).  The
-// per-nibble kernel also serves the tensor lists' fused aggregate + update, whose x lives in
-// separate tensors.
+// Flat buffers with more workers than the few-worker kernel takes (aggregate_group_kernel, below) go
+// to the bit-sliced kernel: with 128-bit streaming count stores it beats the per-nibble kernel at
+// every N.  The exception is the fused update at small d: a bit-sliced wave owns 8192 coordinates
+// and walks their x in 32 dependent steps, which few waves cannot hide.  The per-nibble kernel also
+// serves the tensor lists' fused aggregate + update, whose x lives in separate tensors.
 constexpr int64_t kSlicedMinGroups = 4096;     // groups of 128 words: 33.5 M coordinates
 
 inline int64_t sliced_groups(int64_t numel) { return (words_for(numel) + kSlicedWords - 1) / kSlicedWords; }
@@ -574,6 +571,91 @@ dlion_status launch_encode(const FlatAddr &addr, const Hyper &h, const DeltaOut 
     if (h.N < 4096)
         return launch_encode_planes<12>(addr, h, out, s);
     return launch_encode_planes<16>(addr, h, out, s);
+}
+
+// Few workers on flat buffers (aggregate_group_kernel): eight waves share 8192 coordinates.  enc = the
+// down-link planes to write instead of counts / x, or null.
+//
+// Measured with packed rows that start on 1 KB boundaries, d = 350 M, % of the HBM peak, bit-sliced
+// kernel -> this one:
+//   counts only      N = 4 / 16 / 32 / 64 / 100: 67.1 / 70.7 / 70.7 / 73.0 / 72.8 -> 74.5 / 81.5 / 81.4 / 77.8 / 75.6
+//   fused update     N = 4 / 16 / 32 / 64 / 120: 69.4 / 72.2 / 69.8 / 72.4 / 73.6 -> 80.6 / 78.8 / 79.9 / 79.6 / 78.2
+//   message, vote    N = 12 / 16 / 32 / 64:      71.8 / 72.6 / 70.5 / 71.1        -> 72.9 / 79.6 / 77.1 / 73.9
+//   message, average N = 12 / 16 / 32 / 64:      74.5 / 71.7 / 70.4 / 72.1        -> 82.9 / 82.5 / 77.0 / 71.5
+// The shape that wins depends on what is written.  The fused update (4 KB of x read and written per
+// wave) wants one row in flight per wave and three workgroups per compute unit (two: 72-74 %, four:
+// 73-75 %); counts and messages want two rows in flight and, as N grows, fewer workgroups.  Below
+// N = 12 the message is so short (30-50 us) that the bit-sliced kernel, which has no exchange through
+// LDS on its way out, is faster (N = 4: 71 against 44 %).  Rows that do not start on a 128-byte line
+// cost either kernel 3-8 % (a wave's 1 KB piece of a row then shares lines with its neighbours').
+constexpr int kGroupMaxWorkers = 120;          // counts up to 127 fit the kernel's byte lanes
+constexpr int kGroupApplyMaxWorkers = 120;     // fused update: ahead of the bit-sliced kernel up to the limit
+constexpr int kGroupCountsMaxWorkers = 100;    // counts only: level with it at N = 120
+constexpr int kGroupEncodeMaxWorkers = 64;
+constexpr int kGroupEncodeMinWorkers = 12;
+
+// resident workgroups (of 8 waves) per compute unit; 0 = as many as fit (4)
+inline int group_blocks(const Hyper &h, bool apply, bool encode)
+{
+    const int forced = tuning().group_blocks;
+    if (forced >= 0)
+        return forced;
+    if (apply)
+        return 3;
+    if (encode)
+        return h.N < 32 || (h.N == 32 && h.mode == DLION_VOTE) ? 0 : 3;
+    return h.N < 32 ? 4 : (h.N < 64 ? 3 : 2);
+}
+
+template <int kAcc>
+dlion_status launch_group_planes(const FlatAddr &addr, const Hyper &h, bool apply, bool counts, const DeltaOut *enc,
+                                 hipStream_t s)
+{
+    const int64_t spans = (words_for(addr.p.numel) + kGroupWords - 1) / kGroupWords;
+    const DeltaOut out = enc ? *enc : DeltaOut{nullptr, 0, 0};
+    const int64_t bytes = h.N / 8 + 1 + (apply ? 8 : 0) + (counts ? 2 : 0) + out.n_planes / 8;
+    // the waves' partial planes, and (down-link message) the planes on their way out
+    const size_t need = (static_cast<size_t>(kGroupWaves) * kAcc + (enc ? kAcc + 3 : 0)) * 256 * sizeof(uint32_t);
+    const size_t cap = lds_reservation(group_blocks(h, apply, enc != nullptr));
+    const size_t lds = cap > need ? cap : need;
+    return launch_in_blocks(addr, spans, kGroupCoords / kTile, bytes, false, [&](const FlatAddr &a, int64_t n) {
+        const dim3 grid = grid_for(n), block(kLanes * kGroupWaves);
+        if (enc)
+            return launch(aggregate_group_kernel<kAcc, 2, false, false, true>, grid, block, lds, s, a, h, out);
+        if (apply && counts)
+            return launch(aggregate_group_kernel<kAcc, 1, true, true, false>, grid, block, lds, s, a, h, out);
+        if (apply)
+            return launch(aggregate_group_kernel<kAcc, 1, true, false, false>, grid, block, lds, s, a, h, out);
+        return launch(aggregate_group_kernel<kAcc, 2, false, true, false>, grid, block, lds, s, a, h, out);
+    });
+}
+
+dlion_status launch_group(const FlatAddr &addr, const Hyper &h, bool apply, bool counts, const DeltaOut *enc, hipStream_t s)
+{
+    // planes a wave needs for its own rows: ceil(N / 8) < 2^kAcc
+    if (h.N <= 8)
+        return launch_group_planes<1>(addr, h, apply, counts, enc, s);
+    if (h.N <= 24)
+        return launch_group_planes<2>(addr, h, apply, counts, enc, s);
+    if (h.N <= 56)
+        return launch_group_planes<3>(addr, h, apply, counts, enc, s);
+    return launch_group_planes<4>(addr, h, apply, counts, enc, s);
+}
+
+// The kernel serves N up to group_max_workers (never beyond kGroupMaxWorkers); a forced value also
+// sends the short messages of very few workers through it.
+enum GroupUse { kGroupCounts, kGroupApply, kGroupEncode };
+
+inline bool use_group(int32_t N, GroupUse use)
+{
+    const int forced = tuning().group_max_workers;
+    if (forced >= 0)
+        return N <= forced;
+    if (use == kGroupApply)
+        return N <= kGroupApplyMaxWorkers;
+    if (use == kGroupEncode)
+        return N >= kGroupEncodeMinWorkers && N <= kGroupEncodeMaxWorkers;
+    return N <= kGroupCountsMaxWorkers;
 }
 
 template <typename GT>
@@ -758,6 +840,8 @@ dlion_status dlion_aggregate(const uint64_t *packed, int64_t packed_stride, int6
     h.stream_counts = counts_exceed_cache(d);
     const FlatAddr a = flat_addr(nullptr, nullptr, 0, nullptr, 0, d, const_cast<uint64_t *>(packed),
                                  packed_stride, counts);
+    if (use_group(N, kGroupCounts))
+        return launch_group(a, h, false, true, nullptr, static_cast<hipStream_t>(stream));
     if (use_sliced(N, d, false))
         return launch_sliced(a, h, false, true, static_cast<hipStream_t>(stream));
     return launch_aggregate(a, h, false, true, static_cast<hipStream_t>(stream));
@@ -790,6 +874,8 @@ dlion_status dlion_aggregate_apply(float *x, const uint64_t *packed, int64_t pac
     h.stream_counts = counts_or_null ? counts_exceed_cache(d) : 0;
     const FlatAddr a = flat_addr(x, nullptr, 0, nullptr, 0, d, const_cast<uint64_t *>(packed), packed_stride,
                                  counts_or_null);
+    if (use_group(N, kGroupApply))
+        return launch_group(a, h, true, counts_or_null != nullptr, nullptr, static_cast<hipStream_t>(stream));
     if (use_sliced(N, d, true))
         return launch_sliced(a, h, true, counts_or_null != nullptr, static_cast<hipStream_t>(stream));
     return launch_aggregate(a, h, true, counts_or_null != nullptr, static_cast<hipStream_t>(stream));
@@ -928,11 +1014,13 @@ dlion_status dlion_aggregate_mt(const dlion_seg *segs_host, const dlion_seg *seg
         return DLION_EALIGN;
     Hyper h = make_hyper(N, DLION_VOTE, 0.0f, 0.0f, 0.0f, 0.0f);
     h.stream_counts = counts_exceed_cache(64 * words);
-    if (use_sliced(N, 64 * words, false)) {
+    if (use_group(N, kGroupCounts) || use_sliced(N, 64 * words, false)) {
         // packed words and counts of a tensor list are laid out by word, the padding bits of every
         // tensor's last word are zero: counting is the flat problem over 64 * words coordinates
         const FlatAddr f = flat_addr(nullptr, nullptr, 0, nullptr, 0, 64 * words, const_cast<uint64_t *>(packed),
                                      packed_stride, counts);
+        if (use_group(N, kGroupCounts))
+            return launch_group(f, h, false, true, nullptr, static_cast<hipStream_t>(stream));
         return launch_sliced(f, h, false, true, static_cast<hipStream_t>(stream));
     }
     const SegAddr a = seg_addr(segs_dev, K, tiles, const_cast<uint64_t *>(packed), packed_stride, counts);
@@ -1032,6 +1120,8 @@ dlion_status dlion_aggregate_encode(const uint64_t *packed, int64_t packed_strid
     const FlatAddr a = flat_addr(nullptr, nullptr, 0, nullptr, 0, d, const_cast<uint64_t *>(packed),
                                  packed_stride, nullptr);
     const DeltaOut out = {delta, delta_stride, planes};
+    if (use_group(N, kGroupEncode))
+        return launch_group(a, h, false, false, &out, static_cast<hipStream_t>(stream));
     return launch_encode(a, h, out, static_cast<hipStream_t>(stream));
 }
 
@@ -1171,12 +1261,12 @@ const char *dlion_status_str(dlion_status s)
     return "unknown status";
 }
 
-int dlion_version(void) { return 200; }
+int dlion_version(void) { return 210; }
 
 void dlion_tuning_defaults(dlion_tuning *t)
 {
     if (t) {
-        const dlion_tuning d = {-1, -1, -1, -1, -1, -1, -1, -1, -1};
+        const dlion_tuning d = {-1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1};
         *t = d;
     }
 }
@@ -1191,9 +1281,10 @@ dlion_status dlion_set_tuning(const dlion_tuning *t)
     const bool waves_ok = v.sliced_waves == -1 || v.sliced_waves == 1 || v.sliced_waves == 8 || v.sliced_waves == 16;
     if (!unroll_ok || !waves_ok || v.blocks_per_cu < -1 || v.blocks_per_cu > 64 || v.blocks_per_cu_pass < -1 || v.blocks_per_cu_pass > 64 || v.pass_workers < -1 ||
         v.step_quads < -1 || v.step_quads > 1 || v.sliced_min_workers < -1 || v.apply_blocks < -1 ||
-        v.apply_blocks > 64 || v.block_tiles < -1 || v.block_tiles > kMaxTiles)
+        v.apply_blocks > 64 || v.block_tiles < -1 || v.block_tiles > kMaxTiles || v.group_blocks < -1 ||
+        v.group_blocks > 64 || v.group_max_workers < -1 || v.group_max_workers > kGroupMaxWorkers)
         return DLION_EINVAL;
-        g_tuning = v;
+    g_tuning = v;
     return DLION_OK;
 }
 

@@ -1304,6 +1304,276 @@ __global__ __launch_bounds__(kLanes) void apply_encoded_kernel(FlatAddr addr, Hy
     }
 }
 
+// ---------------------------------------------------------------- server side, few workers
+// Server side for few workers (N <= 120), flat buffers.  With few rows a coordinate's x (8 bytes)
+// or counts (2 bytes) weigh as much as its votes (N/8 bytes), and a wave of the bit-sliced kernel
+// above, which owns 8192 coordinates alone, walks through some 16 dependent round trips to memory
+// (N/4 for the rows, 8 for x).  Here the eight waves of a workgroup share those 8192 coordinates
+// (128 words): wave w reads rows w, w + 8, ... over the whole span (1 KB per row and load: shorter
+// pieces of a row, e.g. one 128-byte line per wave, reach half the bandwidth however they are
+// loaded) and adds them up bit-sliced; the partial planes meet in LDS; then wave w owns
+// coordinates 1024w .. 1024w + 1023 of the span, one 128-byte line of every plane, as in
+// apply_encoded_kernel: lanes 0..31 add the partial planes of waves 0..3 for one dword of the line
+// each, lanes 32..63 those of waves 4..7, and one exchange across the halves completes the
+// count.  Every wave then has three or four round trips, and a workgroup's loads are in flight
+// together.  Ragged ends are handled by guards (words past the end read as zero, outputs past the
+// end are not written), so that every wave of a workgroup reaches the one barrier.
+constexpr int kGroupWaves = 8;
+constexpr int kGroupWords = 128;                        // words per workgroup
+constexpr int kGroupCoords = kGroupWords * 64;          // 8192
+constexpr int kLineWords = kLineSubs * kWordsPerTile;   // 16 words = 1024 coordinates per wave
+
+__device__ __forceinline__ void stream_store_b32(uint32_t v, void *p)
+{
+    asm volatile("global_store_dword %0, %1, off " DLION_STREAM_STORE_POLICY : : "v"(p), "v"(v) : "memory");
+}
+
+// bit-sliced a + b on kIn planes -> kIn + 1 planes
+template <int kIn>
+__device__ __forceinline__ void add_planes(const uint32_t (&a)[kIn], const uint32_t (&b)[kIn], uint32_t (&sum)[kIn + 1])
+{
+    uint32_t carry = 0;
+#pragma unroll
+    for (int k = 0; k < kIn; ++k)
+        csa(carry, sum[k], a[k], b[k], carry);
+    sum[kIn] = carry;
+}
+
+// counts of four coordinates, one per byte: nibble `shift / 4` of the dword that lane `from / 4` holds
+template <int kPlanes> __device__ __forceinline__ uint32_t line_counts4(const uint32_t (&pl)[kPlanes], int from, int shift)
+{
+    uint32_t bytes = 0;
+#pragma unroll
+    for (int b = 0; b < kPlanes; ++b) {
+        const uint32_t dw = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(from, pl[b]));
+        bytes += nibble_to_bytes((dw >> shift) & 0xFu) << b;
+    }
+    return bytes;
+}
+
+// kAcc = planes a wave needs for its own rows, ceil(N / 8) < 2^kAcc; the count has kAcc + 3 planes.
+// kInFlight = rows whose loads a wave has outstanding at once (1 KB each).
+template <int kAcc, int kInFlight, bool kApply, bool kCounts, bool kEncode>
+__global__ __launch_bounds__(kLanes * kGroupWaves) void aggregate_group_kernel(FlatAddr addr, Hyper h, DeltaOut out)
+{
+    static_assert(kAcc >= 1 && kAcc <= 4, "planes");           // counts up to 127 fit a byte
+    constexpr int kPlanes = kAcc + 3;
+    extern __shared__ uint32_t group_lds[];                     // [kGroupWaves][kAcc][256 dwords of the span]
+    const Problem &p = addr.p;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int N = h.N;
+    const int64_t W = (p.numel + 63) >> 6;
+    const int64_t span = addr.first_tile + blockIdx.x;
+    const int64_t w0 = span * kGroupWords;
+
+    // ---- this wave's rows over the whole span: lane l holds words 2l, 2l + 1 as four 32-bit slices
+    uint32_t acc[kAcc][4];
+#pragma unroll
+    for (int b = 0; b < kAcc; ++b)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            acc[b][q] = 0;
+    {
+        const bool whole = w0 + kGroupWords <= W;              // uniform
+        const int64_t wl = w0 + lane * 2;
+#pragma unroll 1
+        for (int r0 = wave; r0 < N; r0 += kGroupWaves * kInFlight) {
+            u32x4 v[kInFlight];
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                v[u] = u32x4{0u, 0u, 0u, 0u};
+                const int r = r0 + u * kGroupWaves;
+                if (r < N) {                                    // uniform
+                    const uint64_t *src = p.packed + (int64_t)r * p.packed_stride + wl;
+                    if (whole || wl + 1 < W) {
+                        v[u] = packed_load2(src);
+                    } else if (wl < W) {
+                        const uint64_t word = stream_load(src);
+                        v[u].x = static_cast<uint32_t>(word);
+                        v[u].y = static_cast<uint32_t>(word >> 32);
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                const uint32_t w4[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    uint32_t c = w4[q];
+#pragma unroll
+                    for (int b = 0; b < kAcc; ++b) {
+                        const uint32_t carry = acc[b][q] & c;
+                        acc[b][q] ^= c;
+                        c = carry;
+                    }
+                }
+            }
+        }
+    }
+    // ---- this wave's line of the span
+    const int64_t t = span * kGroupWaves + wave;                // line index: words 16t .. 16t + 15
+    const int64_t c0 = t * kLineCoords;
+    const bool line_full = c0 + kLineCoords <= p.numel;         // uniform
+    {
+        uint32_t *mine = group_lds + wave * kAcc * 256 + lane * 4;
+#pragma unroll
+        for (int b = 0; b < kAcc; ++b)
+            *reinterpret_cast<u32x4 *>(mine + b * 256) = u32x4{acc[b][0], acc[b][1], acc[b][2], acc[b][3]};
+    }
+    __syncthreads();
+    f32x4 xv[kLineSubs];
+    if (kApply && line_full) {
+#pragma unroll
+        for (int s = 0; s < kLineSubs; ++s)
+            xv[s] = x_load4(p.x + c0 + s * kTile + lane * kVec);
+    }
+    const bool line_exists = c0 < p.numel;                      // uniform
+    if (!kEncode && !line_exists)
+        return;
+    const int half = lane >> 5, dw = lane & 31;
+    uint32_t pl[kPlanes];
+    {
+        const uint32_t *src = group_lds + (4 * half * kAcc) * 256 + wave * 32 + dw;
+        uint32_t a[4][kAcc];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int b = 0; b < kAcc; ++b)
+                a[k][b] = src[(k * kAcc + b) * 256];
+        uint32_t s01[kAcc + 1], s23[kAcc + 1], s4[kAcc + 2];
+        add_planes<kAcc>(a[0], a[1], s01);
+        add_planes<kAcc>(a[2], a[3], s23);
+        add_planes<kAcc + 1>(s01, s23, s4);
+        uint32_t carry = 0;                                     // waves 0..3 + waves 4..7
+#pragma unroll
+        for (int b = 0; b < kAcc + 2; ++b) {
+            const uint32_t other = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, s4[b]));
+            csa(carry, pl[b], s4[b], other, carry);
+        }
+        pl[kAcc + 2] = carry;
+    }
+    // from here on lane l holds, for dword l & 31 of the line, plane b = bit b of its 32 counts
+    uint32_t plus = 0, tie = 0;
+    if (h.mode == DLION_VOTE) {                                 // count > N/2; count == N/2 for even N
+        const uint32_t K = static_cast<uint32_t>(N) >> 1;
+        uint32_t eq = 0xFFFFFFFFu;
+#pragma unroll
+        for (int b = kPlanes - 1; b >= 0; --b) {
+            if ((K >> b) & 1u) {
+                eq &= pl[b];
+            } else {
+                plus |= eq & pl[b];
+                eq &= ~pl[b];
+            }
+        }
+        tie = (N & 1) ? 0u : eq;
+    }
+    if (kEncode) {
+        // The planes of the message go back through LDS, so that wave b can write plane b of the whole
+        // span with full-width stores (1 KB per instruction; a line per wave and plane reaches half the
+        // bandwidth).  Bits past d are zero; words past W do not exist.
+        uint32_t *stage = group_lds + kGroupWaves * kAcc * 256;    // [kPlanes][256 dwords of the span]
+        if (line_exists && half == 0) {
+            const int64_t left = p.numel - (c0 + 32 * dw);         // coordinates from this dword on
+            const uint32_t mask = left >= 32 ? 0xFFFFFFFFu : (left > 0 ? (1u << left) - 1u : 0u);
+            if (h.mode == DLION_VOTE) {
+                stage[wave * 32 + dw] = plus & mask;
+                stage[256 + wave * 32 + dw] = tie & mask;
+            } else {
+#pragma unroll
+                for (int b = 0; b < kPlanes; ++b)
+                    stage[b * 256 + wave * 32 + dw] = pl[b] & mask;
+            }
+        }
+        __syncthreads();
+        if (wave < out.n_planes) {
+            const u32x4 val = *reinterpret_cast<const u32x4 *>(stage + wave * 256 + lane * 4);
+            const int64_t wl = w0 + lane * 2;
+            uint64_t *dst = out.planes + (int64_t)wave * out.stride + wl;
+            if (wl + 1 < W) {
+                if (h.stream_counts)
+                    stream_store_b128(val, dst);
+                else
+                    *reinterpret_cast<words2_e *>(dst) = val;
+            } else if (wl < W) {
+                *dst = (static_cast<uint64_t>(val.y) << 32) | val.x;
+            }
+        }
+        return;
+    }
+    if (kApply) {
+        // lane l owns coordinates 4l..4l+3 of sub-tile s: nibble l & 7 of dword 8s + (l >> 3)
+        const int shift = (lane & 7) * 4;
+#pragma unroll
+        for (int s = 0; s < kLineSubs; ++s) {
+            const int from = (8 * s + (lane >> 3)) << 2;
+            const int64_t j = c0 + s * kTile + lane * kVec;
+            float Delta[4];
+            uint32_t bytes = 0;
+            if (h.mode == DLION_VOTE && !kCounts) {
+                const uint32_t pn = (static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(from, plus)) >> shift) & 0xFu;
+                const uint32_t tn = (static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(from, tie)) >> shift) & 0xFu;
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    Delta[k] = decode_vote((pn >> k) & 1u, (tn >> k) & 1u);
+            } else {
+                bytes = line_counts4<kPlanes>(pl, from, shift);
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    Delta[k] = aggregate_votes((bytes >> (8 * k)) & 0xFFu, h);
+            }
+            if (line_full) {
+                if (kCounts) {
+                    u16x4 c;
+                    c.x = static_cast<uint16_t>(bytes & 0xFFu);
+                    c.y = static_cast<uint16_t>((bytes >> 8) & 0xFFu);
+                    c.z = static_cast<uint16_t>((bytes >> 16) & 0xFFu);
+                    c.w = static_cast<uint16_t>(bytes >> 24);
+                    COUNTS_STORE4(c, p.counts + j);
+                }
+                xv[s].x = lion_apply(xv[s].x, Delta[0], h);
+                xv[s].y = lion_apply(xv[s].y, Delta[1], h);
+                xv[s].z = lion_apply(xv[s].z, Delta[2], h);
+                xv[s].w = lion_apply(xv[s].w, Delta[3], h);
+                x_store4(xv[s], p.x + j);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    if (j + k < p.numel)
+                        p.x[j + k] = lion_apply(p.x[j + k], Delta[k], h);
+                    if (kCounts && j + k < p.counts_end)
+                        p.counts[j + k] = static_cast<uint16_t>(j + k < p.numel ? (bytes >> (8 * k)) & 0xFFu : 0u);
+                }
+            }
+        }
+    } else if (kCounts) {
+        // counts only: lane l owns coordinates 8l..8l+7 of one half of the line, i.e. byte l & 3 of
+        // dword 16h + (l >> 2), and stores its eight counts with one 128-bit access
+        const int shift = (lane & 3) * 8;
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            const int from = (16 * hh + (lane >> 2)) << 2;
+            const uint32_t lo = line_counts4<kPlanes>(pl, from, shift);
+            const uint32_t up = line_counts4<kPlanes>(pl, from, shift + 4);
+            const int64_t j = c0 + hh * (kLineCoords / 2) + lane * 8;
+            if (line_full) {
+                u32x4 c;
+                c.x = (lo & 0xFFu) | ((lo & 0xFF00u) << 8);
+                c.y = ((lo >> 16) & 0xFFu) | ((lo >> 24) << 16);
+                c.z = (up & 0xFFu) | ((up & 0xFF00u) << 8);
+                c.w = ((up >> 16) & 0xFFu) | ((up >> 24) << 16);
+                counts_store8(c, p.counts + j, h.stream_counts);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (j + k < p.counts_end)
+                        p.counts[j + k] = static_cast<uint16_t>(j + k < p.numel ? ((k < 4 ? lo : up) >> (8 * (k & 3))) & 0xFFu : 0u);
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------- Global Lion (comparison scheme)
 // Appendix, "Global Lion Convergence": the workers' full-precision blends c_i are averaged and
 // x <- x - lr*(sign(mean_i c_i) + lambda*x); each worker's momentum moves as in Distributed

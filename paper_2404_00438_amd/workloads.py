@@ -163,9 +163,16 @@ def make_grads(w: Workload, step: int, device, numel: Optional[int] = None, tens
     return out
 
 
-def random_packed(N: int, W: int, device, seed: int = BASE_SEED, p: float = 0.5) -> torch.Tensor:
-    """``[N, W]`` int64 words whose 64 bits are iid Bernoulli(p) (p = 0.5: uniform random bits)."""
-    out = torch.empty((N, W), device=device, dtype=torch.int64)
+def padded_words(W: int) -> int:
+    """Row stride (uint64 words) that starts every row of packed words on a 1 KB boundary."""
+    return (W + 127) // 128 * 128
+
+
+def random_packed(N: int, W: int, device, seed: int = BASE_SEED, p: float = 0.5,
+                  row_stride: Optional[int] = None) -> torch.Tensor:
+    """``[N, W]`` int64 words whose 64 bits are iid Bernoulli(p) (p = 0.5: uniform random bits); a view of
+    rows ``row_stride`` words apart if given."""
+    out = torch.zeros((N, W if row_stride is None else row_stride), device=device, dtype=torch.int64)[:, :W]
     for i in range(N):
         gen = _gen(device, seed + i)
         if p == 0.5:

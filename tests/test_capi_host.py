@@ -214,7 +214,7 @@ def test_tuning_overrides_are_validated_and_restored(lib):
     """dlion_set_tuning: host-only state, every field -1 by default, out-of-range values refused."""
     t = binding.Tuning()
     lib.dlion_get_tuning(ctypes.byref(t))
-    assert [getattr(t, f) for f, _ in binding.Tuning._fields_] == [-1] * 9
+    assert [getattr(t, f) for f, _ in binding.Tuning._fields_] == [-1] * len(binding.Tuning._fields_)
     try:
         binding.dlion_set_tuning(pass_workers=3, block_tiles=5, unroll=4)
         now = binding.dlion_get_tuning()
@@ -226,7 +226,7 @@ def test_tuning_overrides_are_validated_and_restored(lib):
             assert lib.dlion_step_workspace_bytes(350_000_000, 32) == 0
         assert binding.dlion_get_tuning().pass_workers == 3
         for bad in (dict(unroll=3), dict(sliced_waves=4), dict(blocks_per_cu=-2), dict(step_quads=2),
-                    dict(block_tiles=-7), dict(pass_workers=-3)):
+                    dict(block_tiles=-7), dict(pass_workers=-3), dict(group_max_workers=121), dict(group_blocks=65)):
             with pytest.raises(binding.DlionError):
                 binding.dlion_set_tuning(**bad)
         assert binding.dlion_get_tuning().pass_workers == 3          # a refused struct changes nothing

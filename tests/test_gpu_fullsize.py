@@ -78,6 +78,8 @@ def gather_words(t: torch.Tensor, ranges) -> torch.Tensor:
 
 def popcount64_total(t: torch.Tensor) -> int:
     """Total number of set bits of an int64 tensor (SWAR, row by row to bound temporaries)."""
+    if t.dim() == 2 and not t.is_contiguous():              # padded rows: never flatten (that would copy)
+        return sum(popcount64_total(t[i]) for i in range(t.shape[0]))
     total = 0
     flat = t.reshape(-1)
     step = 1 << 26
@@ -302,7 +304,7 @@ def test_vote_only_256_streams_full_size():
     d, N = w.d, w.N
     W = dl.words_for(d)
     announce(w.name, "d", d, "N", N, "W", W)
-    packed = wl.random_packed(N, W, DEV, seed=w.seed)
+    packed = wl.random_packed(N, W, DEV, seed=w.seed, row_stride=wl.padded_words(W))   # as bench.py lays them out
     counts = torch.empty(d, dtype=torch.int16, device=DEV)
     dl.dlion_aggregate(packed, d, counts)
     torch.cuda.synchronize()

@@ -25,7 +25,7 @@ def random_words(rng, N, d, p_one):
 
 @pytest.mark.parametrize("waves", [1, 8, 16])
 def test_down_link_planes_match_oracle(waves, tune):
-    tune(sliced_waves=waves)                                  # workgroup size of the encoder, forced
+    tune(sliced_waves=waves, group_max_workers=0)              # the bit-sliced encoder, its workgroup size forced
     rng = np.random.default_rng(77)
     cases = [(1, 1), (2, 63), (3, 64), (4, 65), (5, 4096), (7, 8191), (8, 8193), (9, 300), (16, 10_000),
              (31, 5000), (32, 4097), (33, 129), (64, 20_000), (100, 9000), (255, 1000), (256, 70_001),

@@ -297,7 +297,7 @@ def test_many_worker_aggregate_matches_oracle(waves, tune):
     """The bit-sliced server-side kernel: counts bit-exact, apply within the bar.  At these sizes the
     library would pick one-wave workgroups (and the per-nibble kernel for the fused update), so the
     bit-sliced kernel and its workgroup size are forced."""
-    tune(sliced_min_workers=1, sliced_waves=waves)
+    tune(sliced_min_workers=1, sliced_waves=waves, group_max_workers=0)
     rng = np.random.default_rng(2024)
     cases = [(1, 300), (2, 8192), (3, 8193), (7, 70_001), (8, 129), (15, 5000),
              (16, 4096), (17, 4097), (31, 1), (32, 63), (33, 10_000), (64, 8192 + 5), (127, 4095),
@@ -337,6 +337,62 @@ def test_many_worker_aggregate_matches_oracle(waves, tune):
                 assert_f32_equal(to_np(x), xn, f"N={N} d={d} mode={mode}: x")
                 if mode == dl.AVG:
                     assert np.array_equal(to_np(counts2), want)
+
+
+def test_few_worker_kernel_matches_oracle(tune):
+    """Server side for few workers (eight waves share 8192 coordinates): counts, planes and x against
+    the oracle for every N the kernel takes a different path for (1 to 4 planes per wave, odd and even,
+    waves with no row or with a partly empty batch of rows), on sizes with whole spans, a ragged last span,
+    a ragged last line of 1024 coordinates and a ragged last word."""
+    tune(group_max_workers=120)
+    rng = np.random.default_rng(31337)
+    sizes = [1, 63, 1024, 1025, 8192, 8192 + 64, 3 * 8192 + 1000, 70_001]
+    workers = [1, 2, 3, 4, 7, 8, 9, 15, 16, 17, 24, 25, 31, 32, 33, 48, 56, 57, 63, 64, 65, 100, 119, 120]
+    for N in workers:
+        for d in sizes if N in (1, 2, 16, 31, 32, 64, 120) else (8192 + 64, 70_001):
+            W = dl.words_for(d)
+            for p_one in (0.5, 1.0):
+                announce("few workers", "N", N, "d", d, "p", p_one)
+                if p_one == 1.0:
+                    words = np.full((N, W), np.uint64(0xFFFFFFFFFFFFFFFF))
+                else:
+                    words = np.packbits(rng.random((N, W * 64)) < p_one, axis=1, bitorder="little").view("<u8")
+                    if N % 2 == 0:                       # exact ties on every coordinate of the first words
+                        words[N // 2:, : (W + 1) // 2] = ~words[: N // 2, : (W + 1) // 2]
+                tail = d - 64 * (W - 1)
+                if tail < 64:
+                    words[:, W - 1] &= np.uint64((1 << tail) - 1)
+                packed = strided_rows(N, W, W + (N + d) % 3, torch.int64, DEV)
+                packed.copy_(torch.from_numpy(words.view(np.int64)))
+                want = oracle.aggregate_packed(np.ascontiguousarray(words), d)
+                counts = torch.full((d + 5,), -1, dtype=torch.int16, device=DEV)
+                dl.dlion_aggregate(packed, d, counts[:d])
+                torch.cuda.synchronize()
+                assert np.array_equal(to_np(counts[:d]), want), f"N={N} d={d}: counts"
+                assert (counts[d:] == -1).all()
+                for mode in (dl.VOTE, dl.AVG):
+                    P = dl.dlion_delta_planes(N, mode)
+                    delta = strided_rows(P, W, W + 1, torch.int64, DEV)
+                    dl.dlion_aggregate_encode(packed, d, mode, delta)
+                    torch.cuda.synchronize()
+                    assert np.array_equal(to_np(delta), oracle.encode_delta(want, N, mode)), f"N={N} d={d} mode={mode}: planes"
+                    assert (delta._base[:, W:] == -1).all()
+                    xv = rng.normal(0, 0.02, d).astype(np.float32)
+                    xn = xv.copy()
+                    oracle.apply(xn, want, N, mode, 0.25, 0.5)
+                    for with_counts in (False, True):
+                        off = (N + d) % 2                # x not 16-byte aligned on every other case
+                        xbuf = torch.full((d + 2,), 7.0, dtype=torch.float32, device=DEV)
+                        x = xbuf[off:off + d]
+                        x.copy_(torch.from_numpy(xv))
+                        counts2 = torch.full((d + 5,), -1, dtype=torch.int16, device=DEV)
+                        dl.dlion_aggregate_apply(x, packed, mode, 0.25, 0.5, counts=counts2[:d] if with_counts else None)
+                        torch.cuda.synchronize()
+                        assert_f32_equal(to_np(x), xn, f"N={N} d={d} mode={mode} counts={with_counts}: x")
+                        assert (xbuf[off + d:] == 7.0).all()
+                        if with_counts:
+                            assert np.array_equal(to_np(counts2[:d]), want)
+                            assert (counts2[d:] == -1).all()
 
 
 def offset_view(shape, dtype, skip):
@@ -550,11 +606,13 @@ def test_workspace_sizes():
     assert dl.dlion_step_mt_workspace_bytes(78125, 16) == dl.dlion_step_workspace_bytes(20_000_000, 16)
 
 
-@pytest.mark.parametrize("sliced", [True, False], ids=["bit-sliced", "per-nibble"])
-def test_server_side_calls_cut_into_several_launches(sliced, tune):
+@pytest.mark.parametrize("kernel", ["bit-sliced", "per-nibble", "few-worker"])
+def test_server_side_calls_cut_into_several_launches(kernel, tune):
     """Large problems run the server-side and update kernels as several launches over blocks of
     coordinates; forced here at small sizes (8 tiles per launch; a bit-sliced workgroup is at least 32)."""
-    tune(block_tiles=8, sliced_min_workers=1 if sliced else 100000, sliced_waves=8 if sliced else -1)
+    sliced = kernel == "bit-sliced"
+    tune(block_tiles=8, sliced_min_workers=1 if sliced else 100000, sliced_waves=8 if sliced else -1,
+         group_max_workers=120 if kernel == "few-worker" else 0)
     rng = np.random.default_rng(616)
     for N, d in ((3, 5000), (8, 70_001), (33, 20_000), (300, 9000)):
         W = dl.words_for(d)
@@ -569,7 +627,7 @@ def test_server_side_calls_cut_into_several_launches(sliced, tune):
         torch.cuda.synchronize()
         assert np.array_equal(to_np(counts), want), f"N={N} d={d}: counts"
         for mode in (dl.VOTE, dl.AVG):
-            announce("several launches", "sliced" if sliced else "per-nibble", "N", N, "d", d, "mode", mode)
+            announce("several launches", kernel, "N", N, "d", d, "mode", mode)
             xv = rng.normal(0, 0.02, d).astype(np.float32)
             xn = xv.copy()
             oracle.apply(xn, want, N, mode, 0.25, 0.5)
