@@ -320,7 +320,8 @@ dlion_status dlion_apply_encoded(float *x, const uint64_t *delta, int64_t delta_
  * Algorithm 1).  beta1, beta2: DEVICE arrays of N floats; (1 - beta) is formed
  * in fp32 on the device.  beta1[i] == beta2[i] gives the sign-momentum worker
  * of the D-SIGNUM comparison (Section 5).  Everything else as in
- * dlion_worker_step / dlion_step.
+ * dlion_worker_step / dlion_step / dlion_step_ws (the workspace is sized by
+ * dlion_step_workspace_bytes and used in the same way).
  */
 dlion_status dlion_worker_step_pw(float *m, int64_t m_stride, const void *g, int64_t g_stride,
                                   dlion_dtype g_dtype, uint64_t *packed, int64_t packed_stride,
@@ -331,6 +332,12 @@ dlion_status dlion_step_pw(float *x, float *m, int64_t m_stride, const void *g, 
                            const float *beta1, const float *beta2, float lr, float lambda,
                            uint64_t *packed_or_null, int64_t packed_stride, uint16_t *counts_or_null,
                            void *stream);
+dlion_status dlion_step_pw_ws(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
+                              dlion_dtype g_dtype, int64_t d, int32_t N, dlion_mode mode,
+                              const float *beta1, const float *beta2, float lr, float lambda,
+                              uint64_t *packed_or_null, int64_t packed_stride,
+                              uint16_t *counts_or_null, void *workspace_or_null,
+                              int64_t workspace_bytes, void *stream);
 
 /*
  * Global Lion, the full-precision comparison scheme (Appendix, "Global Lion

@@ -28,7 +28,7 @@ EXPORTS = (
     "dlion_mt_layout", "dlion_worker_step_mt", "dlion_aggregate_mt", "dlion_apply_mt",
     "dlion_aggregate_apply_mt", "dlion_step_mt", "dlion_status_str", "dlion_version",
     "dlion_delta_planes", "dlion_aggregate_encode", "dlion_apply_encoded", "dlion_worker_step_pw",
-    "dlion_step_pw", "dlion_global_lion_step", "dlion_step_ws", "dlion_step_workspace_bytes",
+    "dlion_step_pw", "dlion_step_pw_ws", "dlion_global_lion_step", "dlion_step_ws", "dlion_step_workspace_bytes",
     "dlion_step_mt_ws", "dlion_step_mt_workspace_bytes", "dlion_tuning_defaults", "dlion_set_tuning",
     "dlion_get_tuning", "dlion_membench", "dlion_noalloc_init", "dlion_step_noalloc",
 )
@@ -96,6 +96,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "dlion_apply_encoded": [vp, vp, i64, i64, i32, ci, f32, f32, vp],
         "dlion_worker_step_pw": [vp, i64, vp, i64, ci, vp, i64, i64, i32, vp, vp, vp],
         "dlion_step_pw": [vp, vp, i64, vp, i64, ci, i64, i32, ci, vp, vp, f32, f32, vp, i64, vp, vp],
+        "dlion_step_pw_ws": [vp, vp, i64, vp, i64, ci, i64, i32, ci, vp, vp, f32, f32, vp, i64, vp, vp, i64, vp],
         "dlion_global_lion_step": [vp, vp, i64, vp, i64, ci, i64, i32, f32, f32, f32, f32, vp, vp],
     }
     for name, argtypes in protos.items():
@@ -470,11 +471,17 @@ def dlion_worker_step_pw(m, g, packed, beta1, beta2, stream=None):
                                                _stream(stream)), "dlion_worker_step_pw")
 
 
-def dlion_step_pw(x, m, g, mode, beta1, beta2, lr, lam, packed=None, counts=None, stream=None):
+def dlion_step_pw(x, m, g, mode, beta1, beta2, lr, lam, packed=None, counts=None, workspace=None, stream=None):
+    """``dlion_step_pw``; with a ``workspace`` tensor, ``dlion_step_pw_ws``."""
     xp, mp, ms, gp, gs, gt, d, N, pp, ps, cp = _step_args(x, m, g, packed, counts)
     b1, b2 = _betas(beta1, beta2, N)
-    _check(load_library().dlion_step_pw(xp, mp, ms, gp, gs, gt, d, N, mode, b1, b2, lr, lam,
-                                        pp, ps, cp, _stream(stream)), "dlion_step_pw")
+    if workspace is None:
+        _check(load_library().dlion_step_pw(xp, mp, ms, gp, gs, gt, d, N, mode, b1, b2, lr, lam,
+                                            pp, ps, cp, _stream(stream)), "dlion_step_pw")
+        return
+    wp, wb = _workspace(workspace)
+    _check(load_library().dlion_step_pw_ws(xp, mp, ms, gp, gs, gt, d, N, mode, b1, b2, lr, lam,
+                                           pp, ps, cp, wp, wb, _stream(stream)), "dlion_step_pw_ws")
 
 
 def dlion_global_lion_step(x, m, g, beta1, beta2, lr, lam, sign_bits=None, stream=None):

@@ -1178,28 +1178,38 @@ dlion_status dlion_worker_step_pw(float *m, int64_t m_stride, const void *g, int
     return launch_step<false>(a, h, g_dtype, true, false, static_cast<hipStream_t>(stream));
 }
 
-dlion_status dlion_step_pw(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
-                           dlion_dtype g_dtype, int64_t d, int32_t N, dlion_mode mode, const float *beta1,
-                           const float *beta2, float lr, float lambda, uint64_t *packed_or_null,
-                           int64_t packed_stride, uint16_t *counts_or_null, void *stream)
+dlion_status dlion_step_pw_ws(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
+                              dlion_dtype g_dtype, int64_t d, int32_t N, dlion_mode mode, const float *beta1,
+                              const float *beta2, float lr, float lambda, uint64_t *packed_or_null,
+                              int64_t packed_stride, uint16_t *counts_or_null, void *workspace_or_null,
+                              int64_t workspace_bytes, void *stream)
 {
-    DLION_TRY(check_common(d, N));
-    if (!dtype_ok(g_dtype) || !mode_ok(mode) || !x || !beta1 || !beta2)
+    DLION_TRY(check_step(x, m, m_stride, g, g_stride, g_dtype, d, N, mode, packed_or_null, packed_stride,
+                         counts_or_null));
+    if (!beta1 || !beta2 || workspace_bytes < 0 || (workspace_or_null == nullptr && workspace_bytes != 0))
         return DLION_EINVAL;
-    if (!aligned_to(x, 4) || !aligned_to(counts_or_null, 2) || !aligned_to(beta1, 4) || !aligned_to(beta2, 4))
+    if (!aligned_to(beta1, 4) || !aligned_to(beta2, 4) || !aligned_to(workspace_or_null, 16))
         return DLION_EALIGN;
-    DLION_TRY(check_rows(m, m_stride, d, N, 4));
-    DLION_TRY(check_rows(g, g_stride, d, N, grad_size(g_dtype)));
-    if (packed_or_null)
-        DLION_TRY(check_rows(packed_or_null, packed_stride, words_for(d), N, 8));
     Hyper h = make_hyper(N, mode, 0.0f, 0.0f, lr, lambda);
     h.beta1_pw = beta1;
     h.beta2_pw = beta2;
     h.stream_counts = counts_or_null ? counts_exceed_cache(d) : 0;
     h.xcd_quads = step_quads(rows_split_lines(m, m_stride, 4, N) || rows_split_lines(g, g_stride, grad_size(g_dtype), N));
     const FlatAddr a = flat_addr(x, m, m_stride, g, g_stride, d, packed_or_null, packed_stride, counts_or_null);
+    Workspace ws;
+    ws.base = workspace_or_null;
+    ws.bytes = workspace_bytes;
     return launch_step<true>(a, h, g_dtype, packed_or_null != nullptr, counts_or_null != nullptr,
-                             static_cast<hipStream_t>(stream));
+                             static_cast<hipStream_t>(stream), ws);
+}
+
+dlion_status dlion_step_pw(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,
+                           dlion_dtype g_dtype, int64_t d, int32_t N, dlion_mode mode, const float *beta1,
+                           const float *beta2, float lr, float lambda, uint64_t *packed_or_null,
+                           int64_t packed_stride, uint16_t *counts_or_null, void *stream)
+{
+    return dlion_step_pw_ws(x, m, m_stride, g, g_stride, g_dtype, d, N, mode, beta1, beta2, lr, lambda,
+                            packed_or_null, packed_stride, counts_or_null, nullptr, 0, stream);
 }
 
 dlion_status dlion_global_lion_step(float *x, float *m, int64_t m_stride, const void *g, int64_t g_stride,

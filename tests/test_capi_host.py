@@ -147,6 +147,11 @@ def test_wider_rows_validation(lib):
     spw = lib.dlion_step_pw
     assert spw(A, A, 128, A, 128, 0, 128, 4, 0, None, A, 1e-4, 0.1, None, 0, None, None) == EINVAL
     assert spw(None, A, 128, A, 128, 0, 128, 4, 0, A, A, 1e-4, 0.1, None, 0, None, None) == EINVAL
+    spww = lib.dlion_step_pw_ws
+    assert spww(A, A, 128, A, 128, 0, 128, 4, 0, A, None, 1e-4, 0.1, None, 0, None, None, 0, None) == EINVAL
+    assert spww(A, A, 128, A, 128, 0, 128, 4, 0, A, A, 1e-4, 0.1, None, 0, None, None, 64, None) == EINVAL
+    assert spww(A, A, 128, A, 128, 0, 128, 4, 0, A, A, 1e-4, 0.1, None, 0, None, A, -1, None) == EINVAL
+    assert spww(A, A, 128, A, 128, 0, 128, 4, 0, A, A, 1e-4, 0.1, None, 0, None, A + 8, 4096, None) == EALIGN
     gl = lib.dlion_global_lion_step
     assert gl(None, A, 128, A, 128, 0, 128, 4, 0.9, 0.99, 1e-4, 0.1, None, None) == EINVAL
     assert gl(A, A, 100, A, 128, 0, 128, 4, 0.9, 0.99, 1e-4, 0.1, None, None) == EINVAL

@@ -548,7 +548,7 @@ def test_per_nibble_server_kernel_on_flat_buffers(tune):
 
 @pytest.mark.parametrize("per,tiles", [(3, 3), (8, 0), (15, 2), (20, 0)])
 def test_step_with_votes_carried_in_a_workspace(per, tiles, tune):
-    """dlion_step_ws / dlion_step_mt_ws: the launches over a few workers hand the votes on through the
+    """dlion_step_ws / dlion_step_pw_ws / dlion_step_mt_ws: the launches over a few workers hand the votes on through the
     caller's workspace, block of tiles by block of tiles (forced at small sizes).  Up to 8 launches of at
     most 15 workers use planes of 4-bit partial counts, anything beyond a running uint16 count: the
     cases cover both, with and without a counts output."""
@@ -573,6 +573,17 @@ def test_step_with_votes_carried_in_a_workspace(per, tiles, tune):
             torch.cuda.synchronize()
             compare_all(f"d={d} N={N} step={step}", x, m, packed if want_packed else None,
                         counts if want_counts else None, xn, mn, pn, cn)
+        # each worker's own coefficients, same hand-over (dlion_step_pw_ws)
+        b1 = rng.choice(np.array([0.0, 0.5, 0.9, 0.95], np.float32), N)
+        b2 = rng.choice(np.array([0.25, 0.9, 0.99], np.float32), N)
+        xn, mn, gn = to_np(x), to_np(m), to_np(g)
+        pn = oracle.worker_step_pw(mn, gn, b1, b2)
+        cn = oracle.aggregate_packed(pn, d)
+        oracle.apply(xn, cn, N, mode, 3e-4, 0.1)
+        dl.dlion_step_pw(x, m, g, mode, torch.from_numpy(b1).to(DEV), torch.from_numpy(b2).to(DEV), 3e-4, 0.1,
+                         packed=packed, counts=counts, workspace=workspace)
+        torch.cuda.synchronize()
+        compare_all(f"step_pw_ws d={d} N={N}", x, m, packed, counts, xn, mn, pn, cn)
     # tensor list, ragged tensors included
     numels = [1000, 5, 64, 256, 257, 1, 2304 * 8, 63]
     for N, mode in ((5, dl.VOTE), (18, dl.AVG), (70, dl.VOTE)):
