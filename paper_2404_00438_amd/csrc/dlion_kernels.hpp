@@ -187,8 +187,9 @@ __device__ __forceinline__ int64_t quad_tile_index()
 // Plain numbering: workgroup b owns tile b.  Workgroups are handed to the 8 XCDs round-robin
 // (workgroup b runs on XCD b % 8), so all XCDs work inside the same narrow window of addresses.
 // That is what DRAM page locality wants: renumbering so that every XCD walks its own contiguous
-// eighth of the tiles costs 15 % of the bandwidth, and grouping 4 consecutive tiles per XCD (to
-// merge the 32-byte packed writes in one L2) changes nothing.
+// eighth of the tiles costs 15 % of the bandwidth.  Grouping 4 consecutive tiles per XCD
+// (quad_tile_index) costs the fused step 1-5 %; the worker step, whose tiles each write a quarter
+// line of every packed row, gains 1-2 % from it and is launched that way.
 __device__ __forceinline__ int64_t wave_tile_index()
 {
     return blockIdx.x;     // uniform across the wavefront: everything derived from it stays scalar
