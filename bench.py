@@ -257,6 +257,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--headline-only", action="store_true",
                     help="measure only --workload: no memory-rate ceilings, no short runs of the other workloads")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="with --headline-only: still measure the memory-rate ceilings")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of known size (1 GiB in, 1 GiB out, 5 times) so that "
                          "hardware counters collected over this run can be scaled against it")
@@ -297,6 +299,10 @@ def main() -> int:
         torch.cuda.synchronize()
         out["copy_calibration"] = {"bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "launches": 5}
         del src, dst
+    if args.headline_only and args.ceilings:
+        del rec
+        torch.cuda.empty_cache()
+        out["roofline"].update(memory_ceilings(dev))
     if not args.headline_only:
         out["roofline"].update(memory_ceilings(dev))
         # every other workload in a process of its own (a fresh address space: what the headline's

@@ -53,6 +53,8 @@ def main(argv=None) -> int:
     ap.add_argument("--trace-steps", type=int, required=True)
     ap.add_argument("--pmc-steps", type=int, required=True)
     ap.add_argument("--bench-args", default="", help="what followed bench.py on the kernel-trace command line")
+    ap.add_argument("--bench-log", help="stdout of the kernel-trace run: its JSON line gives the algorithmic bytes "
+                                        "and, if the run had --ceilings, the memory-rate ceilings")
     ap.add_argument("--out", required=True)
     a = ap.parse_args(argv)
 
@@ -72,7 +74,8 @@ def main(argv=None) -> int:
 
     L = [f"# rocprofv3 summary: {a.title}, workload `{a.workload}`\n",
          "Commands (run from /tmp with TMPDIR=/tmp, repository root = $R; each rocprofv3 run on its own):\n", "```",
-         f"rocprofv3 --kernel-trace --stats -d $T/stats -o stats -- {bench} {a.bench_args}".rstrip(),
+         (f"rocprofv3 --kernel-trace --stats -d $T/stats -o stats -- {bench} {a.bench_args}".rstrip() +
+          (" > $T/stats.log" if a.bench_log else "")),
          f"rocprofv3 --pmc FETCH_SIZE -d $T/fetch -o fetch -- {bench} --steps 5 --warmup 1",
          f"rocprofv3 --pmc WRITE_SIZE -d $T/write -o write -- {bench} --steps 5 --warmup 1"]
     if a.busy:
@@ -80,7 +83,8 @@ def main(argv=None) -> int:
     L.append(f"python3 -m paper_2404_00438_amd.profile_summary --workload {a.workload} --kernel {a.kernel} "
              f"--title \"{a.title}\" --stats $T/stats/stats_results.db --fetch $T/fetch/fetch_results.db "
              f"--write $T/write/write_results.db" + (" --busy $T/busy/busy_results.db" if a.busy else "") +
-             f" --trace-steps {a.trace_steps} --pmc-steps {a.pmc_steps} --out profiles/<this file>")
+             f" --trace-steps {a.trace_steps} --pmc-steps {a.pmc_steps}" +
+             (" --bench-log $T/stats.log" if a.bench_log else "") + " --out profiles/<this file>")
     L += ["```\n", "## Kernel trace (--kernel-trace --stats), top kernels by total time\n",
           "| kernel | calls | total ms | avg us | min us | max us | % |", "|---|---|---|---|---|---|---|"]
     for r in k[:6]:
@@ -112,6 +116,26 @@ def main(argv=None) -> int:
     L.append(f"- fetched per step: {fetch_bytes:.0f} B")
     L.append(f"- written per step: {write_bytes:.0f} B")
     L.append(f"- traffic_bytes_per_launch: {fetch_bytes + write_bytes:.0f}")
+    if a.bench_log:
+        import json
+
+        with open(a.bench_log) as fh:
+            line = next(ln for ln in reversed(fh.read().splitlines()) if ln.startswith("{"))
+        r = json.loads(line)["roofline"]
+        ms = sum(x[2] for x in ks) / a.trace_steps / 1e6
+        gbs = r["bytes_per_launch"] / ms / 1e6
+        L.append(f"- algorithmic bytes per step: {r['bytes_per_launch']} (traffic / algorithmic = "
+                 f"{(fetch_bytes + write_bytes) / r['bytes_per_launch']:.4f})")
+        L.append(f"- achieved (algorithmic bytes / kernel-trace time): {gbs:.1f} GB/s = {100 * gbs / 8000:.1f} % of the "
+                 f"8 TB/s peak")
+        keys = [("copy_ceiling_gbs", "plain copy"), ("read_ceiling_gbs", "read only (8 rows per wave)"),
+                ("mix16to1_ceiling_gbs", "16 rows read per row written (the byte mix of counting 256 streams)")]
+        if any(k in r for k, _ in keys):
+            L.append("\n## Memory-rate ceilings measured in the same run (dlion_membench: no arithmetic, best of several launch shapes)\n")
+            L += ["| probe | GB/s | % of peak | this kernel / probe |", "|---|---|---|---|"]
+            for k, label in keys:
+                if k in r:
+                    L.append(f"| {label} | {r[k]:.0f} | {100 * r[k] / 8000:.1f} | {gbs / r[k]:.3f} |")
     with open(a.out, "w") as fh:
         fh.write("\n".join(L) + "\n")
     print("\n".join(L))
