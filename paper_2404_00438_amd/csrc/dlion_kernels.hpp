@@ -18,6 +18,13 @@
 // All fp32 arithmetic goes through __fmul_rn/__fadd_rn/__fsub_rn so that no
 // multiply-add is ever fused (Section 3.2's expressions, each operation rounded
 // on its own); the sign is taken as !(c < 0), i.e. 0 votes +1.
+//
+// Kernels, in file order: step_kernel (worker step / fused step, also the launches of a step that
+// is cut by workers), aggregate_kernel (server side, per-nibble), aggregate_sliced_kernel and
+// aggregate_encode_kernel (server side and down-link message, bit-sliced, many workers),
+// apply_encoded_kernel (worker side of the down-link), aggregate_group_kernel (server side and
+// message, few workers), global_lion_kernel, apply_kernel, membench_kernel (memory-rate probe).
+// Loads of m, g, x and the packed rows are streaming (non-temporal) loads throughout.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -28,14 +35,6 @@
 #include "../../include/dlion.h"
 
 namespace dlion {
-
-// Compile-time switches (the defaults are the measured best on MI355X).
-#ifndef DLION_XCD_QUADS
-#define DLION_XCD_QUADS 1       // readers of packed rows: 4 consecutive tiles on one XCD
-#endif
-#ifndef DLION_NT_LOAD
-#define DLION_NT_LOAD 1         // streaming (non-temporal) loads of m and g
-#endif
 
 constexpr int kLanes = 64;                    // one-wave workgroups everywhere on the worker/fused path
 constexpr int kVec = 4;                       // coordinates per lane on the vector path
@@ -176,11 +175,9 @@ template <class Addr> __device__ __forceinline__ CarrySlot carry_slot(const Addr
 __device__ __forceinline__ int64_t quad_tile_index()
 {
     uint32_t block = blockIdx.x;
-#if DLION_XCD_QUADS
     const uint32_t group = block & ~31u;
     if (group + 32 <= gridDim.x)                           // whole group of 32 exists
         block = group + ((block & 7u) << 2) + ((block >> 3) & 3u);
-#endif
     return block;
 }
 
@@ -199,9 +196,6 @@ __device__ __forceinline__ int64_t wave_tile_index()
 // (non-temporal) accesses, +14 % on the apply kernel.  counts written by one call are read by
 // the next (aggregate -> apply) and up to ~250 MB of them stay in the memory-side cache, so
 // they use ordinary accesses unless the array is too large for that (h.stream_counts).
-#ifndef DLION_NT_X
-#define DLION_NT_X 1
-#endif
 // Streaming stores carry the device-scope bit next to the streaming hint: with one L2 per XCD a
 // device-scope store is written through to memory at once instead of waiting in the L2 for its
 // eviction, and the steadier stream of writes is worth 1 % of the HBM peak to the fused step
@@ -211,9 +205,7 @@ __device__ __forceinline__ int64_t wave_tile_index()
 // than 64 bits must not be followed at once by a vector-ALU write to the registers that hold its
 // data (the hardware reads them a cycle late); the compiler pads its own stores for that but
 // cannot see into this one, hence the two idle cycles after it.
-#ifndef DLION_STREAM_STORE_POLICY
 #define DLION_STREAM_STORE_POLICY "sc1 nt"
-#endif
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ void stream_store_b128(u32x4 v, void *p)
 {
@@ -226,11 +218,7 @@ __device__ __forceinline__ void stream_store_b64(u32x2 v, void *p)
 
 template <typename T> __device__ __forceinline__ T stream_load(const T *p)
 {
-#if DLION_NT_LOAD
     return __builtin_nontemporal_load(p);
-#else
-    return *p;
-#endif
 }
 // Four consecutive elements of a row, of x or of the counts, in one access.  The callers'
 // arrays are only promised the alignment of their element type (rows of a contiguous [N, d]
@@ -245,19 +233,11 @@ typedef u16x4 u16x4_e __attribute__((aligned(2)));
 
 __device__ __forceinline__ f32x4 row_load4(const float *p)
 {
-#if DLION_NT_LOAD
     return __builtin_nontemporal_load(reinterpret_cast<const f32x4_e *>(p));
-#else
-    return *reinterpret_cast<const f32x4_e *>(p);
-#endif
 }
 __device__ __forceinline__ u32x2 row_load4(const uint16_t *p)
 {
-#if DLION_NT_LOAD
     return __builtin_nontemporal_load(reinterpret_cast<const bf16x4_e *>(p));
-#else
-    return *reinterpret_cast<const bf16x4_e *>(p);
-#endif
 }
 __device__ __forceinline__ void row_store4(f32x4 v, float *p)
 {
@@ -265,11 +245,7 @@ __device__ __forceinline__ void row_store4(f32x4 v, float *p)
 }
 __device__ __forceinline__ f32x4 x_load4(const float *p)
 {
-#if DLION_NT_X
     return __builtin_nontemporal_load(reinterpret_cast<const f32x4_e *>(p));
-#else
-    return *reinterpret_cast<const f32x4_e *>(p);
-#endif
 }
 __device__ __forceinline__ void x_store4(f32x4 v, float *p)
 {
@@ -753,29 +729,18 @@ __global__ __launch_bounds__(kLanes) void aggregate_kernel(Addr addr, Hyper h)
 // are then staged through LDS so that the lanes can switch from "kWpl words each" to "eight
 // consecutive coordinates each" (counts) or "four consecutive coordinates each" (x) and write
 // with 128-bit accesses.
-#ifndef DLION_SLICED_WORDS_PER_LANE
-#define DLION_SLICED_WORDS_PER_LANE 2      // consecutive words of each stream a lane reads (1 or 2)
-#endif
-constexpr int kWpl = DLION_SLICED_WORDS_PER_LANE;
+constexpr int kWpl = 2;                                // consecutive words of each stream a lane reads
 constexpr int kSlices = 2 * kWpl;                      // 32-bit slices a lane carries
 constexpr int kSlicedWords = kLanes * kWpl;            // words per wave
 constexpr int kSlicedCoords = kSlicedWords * 64;
-#ifndef DLION_SLICED_IN_FLIGHT
-#define DLION_SLICED_IN_FLIGHT 4           // rows whose loads a wave has outstanding at once (2, 4, 8 or 16)
-#endif
-constexpr int kSlicedInFlight = DLION_SLICED_IN_FLIGHT;
-static_assert(kSlicedInFlight == 2 || kSlicedInFlight == 4 || kSlicedInFlight == 8 || kSlicedInFlight == 16, "rows in flight");
+constexpr int kSlicedInFlight = 4;                     // rows whose loads a wave has outstanding at once
 
 typedef u32x4 words2_e __attribute__((aligned(8)));
 
 // two consecutive packed words (only promised the alignment of one) in one 128-bit access
 __device__ __forceinline__ u32x4 packed_load2(const uint64_t *p)
 {
-#if DLION_NT_LOAD
     return __builtin_nontemporal_load(reinterpret_cast<const words2_e *>(p));
-#else
-    return *reinterpret_cast<const words2_e *>(p);
-#endif
 }
 
 // carry-save adder on 32 independent bit positions: a + b + c = 2*carry + sum.  gfx950 has a
@@ -799,7 +764,7 @@ __device__ __forceinline__ void sliced_count(const Problem &p, int N, int64_t w0
                                              Planes<kPlanes> &out)
 {
     static_assert(kPlanes >= 5 && kPlanes <= 16, "planes");
-    static_assert(kWpl == 1 || kWpl == 2, "words per lane");
+    static_assert(kWpl == 2, "a lane reads its two words of a row as one 128-bit load");
     const int64_t wl0 = w0 + (int64_t)lane * kWpl;              // first word of the lane
     // whole group inside the word range: full-width loads, no per-lane guards
     const bool fast = w0 + kSlicedWords <= W;
@@ -865,17 +830,11 @@ __device__ __forceinline__ void sliced_count(const Problem &p, int N, int64_t w0
                     v[k][q] = 0;
                 if (!decltype(guard_rows)::value || i + k0 + k < N) {        // uniform
                     const char *row = reinterpret_cast<const char *>(p.packed + (int64_t)(i + k0 + k) * p.packed_stride + w0);
-                    if (kWpl == 2) {
-                        const u32x4 r = packed_load2(reinterpret_cast<const uint64_t *>(row + lane_bytes));
-                        v[k][0] = r.x;
-                        v[k][1] = r.y;
-                        v[k][kSlices - 2] = r.z;
-                        v[k][kSlices - 1] = r.w;
-                    } else {
-                        const u32x2 r = stream_load(reinterpret_cast<const u32x2 *>(row + lane_bytes));
-                        v[k][0] = r.x;
-                        v[k][1] = r.y;
-                    }
+                    const u32x4 r = packed_load2(reinterpret_cast<const uint64_t *>(row + lane_bytes));
+                    v[k][0] = r.x;
+                    v[k][1] = r.y;
+                    v[k][2] = r.z;
+                    v[k][3] = r.w;
                 }
             }
 #pragma unroll
@@ -883,11 +842,9 @@ __device__ __forceinline__ void sliced_count(const Problem &p, int N, int64_t w0
 #pragma unroll
                 for (int q = 0; q < kSlices; ++q)
                     csa(t[(k0 + k) / 2][q], ones[q], ones[q], v[k][q], v[k + 1][q]);
-            if (kSlicedInFlight < 16) {
 #pragma unroll
-                for (int q = 0; q < kSlices; ++q)
-                    asm volatile("" : "+v"(ones[q]) : : "memory");
-            }
+            for (int q = 0; q < kSlices; ++q)
+                asm volatile("" : "+v"(ones[q]) : : "memory");
         }
         add_pairs(t);
     };
@@ -1196,13 +1153,13 @@ __global__ __launch_bounds__(kLanes * kWaves) void aggregate_encode_kernel(FlatA
                 word[q] &= left > 0 ? (static_cast<uint64_t>(1) << left) - 1 : 0;   // bits past d are zero
         }
         uint64_t *dst = out.planes + (int64_t)b * out.stride + wl0;
-        if (whole && kWpl == 2) {
+        if (whole) {
             // both words of the lane in one 128-bit store: 1 KB per instruction
             u32x4 v;
             v.x = static_cast<uint32_t>(word[0]);
             v.y = static_cast<uint32_t>(word[0] >> 32);
-            v.z = static_cast<uint32_t>(word[kWpl - 1]);
-            v.w = static_cast<uint32_t>(word[kWpl - 1] >> 32);
+            v.z = static_cast<uint32_t>(word[1]);
+            v.w = static_cast<uint32_t>(word[1] >> 32);
             if (h.stream_counts) {
                 stream_store_b128(v, dst);
             } else {
