@@ -473,7 +473,7 @@ constexpr int kSliced16MinWorkers = 128;
 // to the bit-sliced kernel: with 128-bit streaming count stores it beats the per-nibble kernel at
 // every N.  The exception is the fused update at small d: a bit-sliced wave owns 8192 coordinates
 // and walks their x in 32 dependent steps, which few waves cannot hide.  The per-nibble kernel also
-// serves the tensor lists' fused aggregate + update, whose x lives in separate tensors.
+// serves the tensor lists' fused aggregate + update beyond the few-worker kernel's N.
 constexpr int64_t kSlicedMinGroups = 4096;     // groups of 128 words: 33.5 M coordinates
 
 inline int64_t sliced_groups(int64_t numel) { return (words_for(numel) + kSlicedWords - 1) / kSlicedWords; }
@@ -609,7 +609,7 @@ inline int group_blocks(const Hyper &h, bool apply, bool encode)
 
 template <int kAcc>
 dlion_status launch_group_planes(const FlatAddr &addr, const Hyper &h, bool apply, bool counts, const DeltaOut *enc,
-                                 hipStream_t s)
+                                 const SegTab &tab, hipStream_t s)
 {
     const int64_t spans = (words_for(addr.p.numel) + kGroupWords - 1) / kGroupWords;
     const DeltaOut out = enc ? *enc : DeltaOut{nullptr, 0, 0};
@@ -621,25 +621,31 @@ dlion_status launch_group_planes(const FlatAddr &addr, const Hyper &h, bool appl
     return launch_in_blocks(addr, spans, kGroupCoords / kTile, bytes, false, [&](const FlatAddr &a, int64_t n) {
         const dim3 grid = grid_for(n), block(kLanes * kGroupWaves);
         if (enc)
-            return launch(aggregate_group_kernel<kAcc, 2, false, false, true>, grid, block, lds, s, a, h, out);
+            return launch(aggregate_group_kernel<kAcc, 2, false, false, true, false>, grid, block, lds, s, a, h, out, tab);
+        if (apply && tab.segs && counts)
+            return launch(aggregate_group_kernel<kAcc, 1, true, true, false, true>, grid, block, lds, s, a, h, out, tab);
+        if (apply && tab.segs)
+            return launch(aggregate_group_kernel<kAcc, 1, true, false, false, true>, grid, block, lds, s, a, h, out, tab);
         if (apply && counts)
-            return launch(aggregate_group_kernel<kAcc, 1, true, true, false>, grid, block, lds, s, a, h, out);
+            return launch(aggregate_group_kernel<kAcc, 1, true, true, false, false>, grid, block, lds, s, a, h, out, tab);
         if (apply)
-            return launch(aggregate_group_kernel<kAcc, 1, true, false, false>, grid, block, lds, s, a, h, out);
-        return launch(aggregate_group_kernel<kAcc, 2, false, true, false>, grid, block, lds, s, a, h, out);
+            return launch(aggregate_group_kernel<kAcc, 1, true, false, false, false>, grid, block, lds, s, a, h, out, tab);
+        return launch(aggregate_group_kernel<kAcc, 2, false, true, false, false>, grid, block, lds, s, a, h, out, tab);
     });
 }
 
-dlion_status launch_group(const FlatAddr &addr, const Hyper &h, bool apply, bool counts, const DeltaOut *enc, hipStream_t s)
+// tab: the tensor table behind a flat view of a tensor list (x is found through it), or {null, 0}
+dlion_status launch_group(const FlatAddr &addr, const Hyper &h, bool apply, bool counts, const DeltaOut *enc, hipStream_t s,
+                          const SegTab &tab = SegTab{nullptr, 0})
 {
     // planes a wave needs for its own rows: ceil(N / 8) < 2^kAcc
     if (h.N <= 8)
-        return launch_group_planes<1>(addr, h, apply, counts, enc, s);
+        return launch_group_planes<1>(addr, h, apply, counts, enc, tab, s);
     if (h.N <= 24)
-        return launch_group_planes<2>(addr, h, apply, counts, enc, s);
+        return launch_group_planes<2>(addr, h, apply, counts, enc, tab, s);
     if (h.N <= 56)
-        return launch_group_planes<3>(addr, h, apply, counts, enc, s);
-    return launch_group_planes<4>(addr, h, apply, counts, enc, s);
+        return launch_group_planes<3>(addr, h, apply, counts, enc, tab, s);
+    return launch_group_planes<4>(addr, h, apply, counts, enc, tab, s);
 }
 
 // The kernel serves N up to group_max_workers (never beyond kGroupMaxWorkers); a forced value also
@@ -1059,6 +1065,13 @@ dlion_status dlion_aggregate_apply_mt(const dlion_seg *segs_host, const dlion_se
     DLION_TRY(check_rows(packed, packed_stride, words, N, 8));
     Hyper h = make_hyper(N, mode, 0.0f, 0.0f, lr, lambda);
     h.stream_counts = counts_or_null ? counts_exceed_cache(64 * words) : 0;
+    if (use_group(N, kGroupApply)) {
+        // words and counts of the list are one flat layout; only x is found through the table
+        const FlatAddr f = flat_addr(nullptr, nullptr, 0, nullptr, 0, 64 * words, const_cast<uint64_t *>(packed),
+                                     packed_stride, counts_or_null);
+        return launch_group(f, h, true, counts_or_null != nullptr, nullptr, static_cast<hipStream_t>(stream),
+                            SegTab{segs_dev, K});
+    }
     const SegAddr a = seg_addr(segs_dev, K, tiles, const_cast<uint64_t *>(packed), packed_stride, counts_or_null);
     return launch_aggregate(a, h, true, counts_or_null != nullptr, static_cast<hipStream_t>(stream));
 }

@@ -1309,11 +1309,36 @@ template <int kPlanes> __device__ __forceinline__ uint32_t line_counts4(const ui
     return bytes;
 }
 
-// kAcc = planes a wave needs for its own rows, ceil(N / 8) < 2^kAcc; the count has kAcc + 3 planes.
-// kInFlight = rows whose loads a wave has outstanding at once (1 KB each).
-template <int kAcc, int kInFlight, bool kApply, bool kCounts, bool kEncode>
-__global__ __launch_bounds__(kLanes * kGroupWaves) void aggregate_group_kernel(FlatAddr addr, Hyper h, DeltaOut out)
+// Tensor list behind a flat view: packed words and counts of a list are one flat layout by word, only x
+// lives in the tensors.  The kernel then runs on the flat problem of 64 * total_words coordinates (x
+// null) and finds x through the table: a line of 1024 coordinates that lies in the whole words of one
+// tensor (a scalar search, the common case) is updated as in the flat case, any other line coordinate
+// by coordinate, every lane searching the owner of its word.
+struct SegTab {
+    const dlion_seg *segs;     // device table ordered by word_begin, or null (flat buffer)
+    int32_t K;
+};
+
+__device__ __forceinline__ int32_t seg_of_word(const SegTab &tab, int64_t word)
 {
+    int32_t lo = 0, hi = tab.K - 1;
+    while (lo < hi) {
+        const int32_t mid = (lo + hi + 1) >> 1;
+        if (tab.segs[mid].word_begin <= word)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    return lo;
+}
+
+// kAcc = planes a wave needs for its own rows, ceil(N / 8) < 2^kAcc; the count has kAcc + 3 planes.
+// kInFlight = rows whose loads a wave has outstanding at once (1 KB each).  kSeg: x through `tab`.
+template <int kAcc, int kInFlight, bool kApply, bool kCounts, bool kEncode, bool kSeg>
+__global__ __launch_bounds__(kLanes * kGroupWaves) void aggregate_group_kernel(FlatAddr addr, Hyper h, DeltaOut out,
+                                                                               SegTab tab)
+{
+    static_assert(!kSeg || (kApply && !kEncode), "the table is only needed to find x");
     static_assert(kAcc >= 1 && kAcc <= 4, "planes");           // counts up to 127 fit a byte
     constexpr int kPlanes = kAcc + 3;
     extern __shared__ uint32_t group_lds[];                     // [kGroupWaves][kAcc][256 dwords of the span]
@@ -1380,11 +1405,23 @@ __global__ __launch_bounds__(kLanes * kGroupWaves) void aggregate_group_kernel(F
             *reinterpret_cast<u32x4 *>(mine + b * 256) = u32x4{acc[b][0], acc[b][1], acc[b][2], acc[b][3]};
     }
     __syncthreads();
-    f32x4 xv[kLineSubs];
+    // x of the line's first coordinate if the line can be updated with full-width accesses
+    float *xline = nullptr;
     if (kApply && line_full) {
+        if (kSeg) {
+            const dlion_seg sg = tab.segs[seg_of_word(tab, t * kLineWords)];       // uniform
+            const int64_t local = (t * kLineWords - sg.word_begin) * 64;
+            if (local + kLineCoords <= sg.numel)
+                xline = sg.x + local;
+        } else {
+            xline = p.x + c0;
+        }
+    }
+    f32x4 xv[kLineSubs];
+    if (kApply && xline) {
 #pragma unroll
         for (int s = 0; s < kLineSubs; ++s)
-            xv[s] = x_load4(p.x + c0 + s * kTile + lane * kVec);
+            xv[s] = x_load4(xline + s * kTile + lane * kVec);
     }
     const bool line_exists = c0 < p.numel;                      // uniform
     if (!kEncode && !line_exists)
@@ -1481,7 +1518,7 @@ __global__ __launch_bounds__(kLanes * kGroupWaves) void aggregate_group_kernel(F
                 for (int k = 0; k < 4; ++k)
                     Delta[k] = aggregate_votes((bytes >> (8 * k)) & 0xFFu, h);
             }
-            if (line_full) {
+            if (xline) {
                 if (kCounts) {
                     u16x4 c;
                     c.x = static_cast<uint16_t>(bytes & 0xFFu);
@@ -1494,14 +1531,26 @@ __global__ __launch_bounds__(kLanes * kGroupWaves) void aggregate_group_kernel(F
                 xv[s].y = lion_apply(xv[s].y, Delta[1], h);
                 xv[s].z = lion_apply(xv[s].z, Delta[2], h);
                 xv[s].w = lion_apply(xv[s].w, Delta[3], h);
-                x_store4(xv[s], p.x + j);
+                x_store4(xv[s], xline + s * kTile + lane * kVec);
             } else {
+                // coordinate by coordinate; the lane's four coordinates share a word, hence an owner
+                float *xs = p.x;                                // flat: coordinate j is x[j]
+                int64_t local = j, numel = p.numel;
+                if (kSeg) {
+                    numel = 0;
+                    if (j < p.numel) {
+                        const dlion_seg sg = tab.segs[seg_of_word(tab, j >> 6)];
+                        xs = sg.x;
+                        local = j - sg.word_begin * 64;
+                        numel = sg.numel;
+                    }
+                }
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    if (j + k < p.numel)
-                        p.x[j + k] = lion_apply(p.x[j + k], Delta[k], h);
+                    if (local + k < numel)
+                        xs[local + k] = lion_apply(xs[local + k], Delta[k], h);
                     if (kCounts && j + k < p.counts_end)
-                        p.counts[j + k] = static_cast<uint16_t>(j + k < p.numel ? (bytes >> (8 * k)) & 0xFFu : 0u);
+                        p.counts[j + k] = static_cast<uint16_t>(local + k < numel ? (bytes >> (8 * k)) & 0xFFu : 0u);
                 }
             }
         }

@@ -249,6 +249,7 @@ def test_vit_b16_tensor_list_full_size():
         if last:
             x_full, m_full, g_full = [to_np(t_) for t_ in xs], [to_np(t_) for t_ in ms], [to_np(t_) for t_ in gs]
             xs_u, ms_u = [t_.clone() for t_ in xs], [t_.clone() for t_ in ms]
+            xs_a = [t_.clone() for t_ in xs]
             packed = torch.empty((N, Wt), dtype=torch.int64, device=DEV)
             counts = torch.empty(64 * Wt, dtype=torch.int16, device=DEV)
             dl.dlion_step_mt(table, N, *hyp, packed=packed, counts=counts, workspace=workspace)
@@ -278,7 +279,14 @@ def test_vit_b16_tensor_list_full_size():
     assert torch.equal(packed_u, packed) and torch.equal(counts_u, counts)
     for k in range(len(numels)):
         assert same_bits(ms_u[k], ms[k]) and same_bits(xs_u[k], xs[k]), f"tensor {k}: fused and unfused state differ"
-    print("  fused step == worker_step + aggregate + apply over all tensors", flush=True)
+    # the fused aggregate + update on the same packed words: a fourth kernel, whole arrays again
+    counts_a = torch.empty(64 * Wt, dtype=torch.int16, device=DEV)
+    dl.dlion_aggregate_apply_mt(dl.SegTable(xs_a, None, None), packed_u, w.mode, w.lr, w.lam, counts=counts_a)
+    torch.cuda.synchronize()
+    assert torch.equal(counts_a, counts)
+    for k in range(len(numels)):
+        assert same_bits(xs_a[k], xs[k]), f"tensor {k}: aggregate_apply_mt and the fused step differ"
+    print("  fused step == worker_step + aggregate + apply == worker_step + aggregate_apply over all tensors", flush=True)
     # ... and against the oracle over all 148 tensors in full
     threads = min(len(os.sched_getaffinity(0)), 16)
     p_full, c_full = oracle.step_mt(x_full, m_full, g_full, *hyp, threads=threads)

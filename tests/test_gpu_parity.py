@@ -248,6 +248,9 @@ def test_tensor_list_matches_oracle(g_dtype, mode):
             xs_a = [t.clone() for t in xs]
             tab_a = dl.SegTable(xs_a, None, None)
             dl.dlion_aggregate_apply_mt(tab_a, packed_u, mode, hyp["lr"], hyp["lam"])
+            xs_b = [t.clone() for t in xs]
+            counts_b = torch.full((64 * Wt,), -1, dtype=torch.int16, device=DEV)
+            dl.dlion_aggregate_apply_mt(dl.SegTable(xs_b, None, None), packed_u, mode, hyp["lr"], hyp["lam"], counts=counts_b)
             # fused in place
             dl.dlion_step_mt(table, N, mode, hyp["beta1"], hyp["beta2"], hyp["lr"], hyp["lam"],
                              packed=packed, counts=counts)
@@ -264,6 +267,8 @@ def test_tensor_list_matches_oracle(g_dtype, mode):
                     assert_f32_equal(to_np(M[k]), mn[k], f"{tag}: m[{k}]")
             for k in range(len(numels)):
                 assert_f32_equal(to_np(xs_a[k]), xn[k], f"aggregate_apply_mt: x[{k}]")
+                assert_f32_equal(to_np(xs_b[k]), xn[k], f"aggregate_apply_mt with counts: x[{k}]")
+            assert np.array_equal(to_np(counts_b), to_np(counts_u)), "aggregate_apply_mt: counts (padding included)"
 
 
 def test_tiny_config_full_run():
