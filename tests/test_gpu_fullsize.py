@@ -132,6 +132,7 @@ def run_flat_workload(w: wl.Workload, n_chunks: int = 24, steps=None, padded=Tru
         if last:
             # copies for the unfused pipeline and (optionally) the oracle over the whole arrays
             x_u, m_u = x.clone(), m.clone()
+            x_a = x.clone()
             if full_oracle_step:
                 x_full, m_full, g_full = to_np(x), to_np(m), to_np(g)
             # the instrumented variant on the last step: packed words and counts at full size
@@ -158,8 +159,25 @@ def run_flat_workload(w: wl.Workload, n_chunks: int = 24, steps=None, padded=Tru
     assert same_bits(counts_u, counts), f"{w.name}: fused and unfused counts differ somewhere"
     assert same_bits(m_u, m), f"{w.name}: fused and unfused momentum differ somewhere"
     assert same_bits(x_u, x), f"{w.name}: fused and unfused weights differ somewhere"
-    del packed_u, counts_u, m_u, x_u
+    del counts_u, m_u
     print("  fused step == worker_step + aggregate + apply over the whole arrays", flush=True)
+    # ... and the two other ways from the packed words to the weights: the fused aggregate + update (with its
+    # counts), and the down-link message applied to the weights
+    x_u.copy_(x_a)
+    counts_a = torch.empty(d, dtype=torch.int16, device=DEV)
+    dl.dlion_aggregate_apply(x_u, packed_u, w.mode, w.lr, w.lam, counts=counts_a)
+    torch.cuda.synchronize()
+    assert same_bits(counts_a, counts), f"{w.name}: counts of aggregate_apply differ somewhere"
+    assert same_bits(x_u, x), f"{w.name}: aggregate_apply and the fused step differ somewhere"
+    del counts_a
+    delta = torch.empty((dl.dlion_delta_planes(N, w.mode), wl.padded_words(W)), dtype=torch.int64, device=DEV)[:, :W]
+    dl.dlion_aggregate_encode(packed_u, d, w.mode, delta)
+    dl.dlion_apply_encoded(x_a, delta, N, w.mode, w.lr, w.lam)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(gather_words(delta, ranges)), oracle.encode_delta(ch, N, w.mode)), f"{w.name}: planes"
+    assert same_bits(x_a, x), f"{w.name}: the down-link message and the fused step differ somewhere"
+    del packed_u, x_u, x_a, delta
+    print("  fused step == aggregate_apply == aggregate_encode + apply_encoded over the whole arrays", flush=True)
     if full_oracle_step:
         threads = min(len(os.sched_getaffinity(0)), 16)
         p_full, c_full = oracle.step(x_full, m_full, g_full, *hyp, threads=threads)
