@@ -26,6 +26,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, vendor figure
 HEADLINE = "gpt350m_vote32"
+# A process that allocates tens of GB while the memory a process before it freed is still on its way back to
+# the driver's pool runs 4 % slower for its whole life (measured: started at once after a 67 GB process
+# 18.5 ms per step, started 3 s or more later 17.8 ms, and 17.8 ms for 600 steps on end).  Every
+# measuring process therefore waits this long before it allocates.
+SETTLE_S = 4.0
 
 
 def algorithmic_bytes_per_step(d: int, N: int, g_bytes: int) -> int:
@@ -277,6 +282,7 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
+    time.sleep(SETTLE_S)
     dev = "cuda:0"
     torch.cuda.set_device(0)
     dl.load_library()
