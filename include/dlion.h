@@ -14,8 +14,10 @@
  * Memory.   Every pointer is a DEVICE pointer unless its comment says "host".
  *           The caller owns all memory; the library allocates nothing and keeps
  *           no state between calls other than the launch-shape overrides of
- *           dlion_set_tuning (by default: none); calls are re-entrant across
- *           streams.
+ *           dlion_set_tuning (by default: none) and the address of its static
+ *           scratch array per device (dlion_step_noalloc); calls are re-entrant
+ *           across streams, except that calls of dlion_step_noalloc share that
+ *           array.
  * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default
  *           stream).  Calls only enqueue work and return; they never synchronise.
  * Types.    x and m are fp32.  g is fp32 or bf16 (`g_dtype`); bf16 is widened
@@ -30,7 +32,8 @@
  *           >= d (>= W for packed).  Any stride is accepted: bases and strides
  *           need only the alignment of the element type.  Fastest when every row
  *           starts on a 1 KB boundary (m, g strides that are multiples of 256
- *           elements): a wave then moves whole cache lines that no other wave touches.
+ *           elements, packed strides that are multiples of 128 words): a wave
+ *           then moves whole cache lines that no other wave touches.
  * Sign.     The worker's sign maps 0 (and -0, and NaN) to +1, so that delta is
  *           one bit:  bit = !(c < 0).
  * Packing.  W = ceil(d/64) uint64 words per worker; bit (j % 64) of word (j / 64),
