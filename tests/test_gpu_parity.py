@@ -400,6 +400,37 @@ def test_few_worker_kernel_matches_oracle(tune):
                             assert (counts2[d:] == -1).all()
 
 
+def test_server_side_kernel_choice_at_its_boundaries():
+    """The library's own choice between the few-worker, bit-sliced and per-nibble kernels (no override), on
+    both sides of every N at which it changes: counts, planes and x against the oracle."""
+    rng = np.random.default_rng(4242)
+    for N in (8, 9, 11, 12, 24, 25, 56, 57, 64, 65, 100, 101, 120, 121):
+        for d in (9000, 70_001):
+            announce("kernel choice", "N", N, "d", d)
+            W = dl.words_for(d)
+            bits = rng.random((N, W * 64)) < 0.5
+            bits[:, d:] = False
+            words = np.packbits(bits, axis=1, bitorder="little").view("<u8")
+            want = oracle.aggregate_packed(np.ascontiguousarray(words), d)
+            packed = strided_rows(N, W, W + 2, torch.int64, DEV)
+            packed.copy_(torch.from_numpy(words.view(np.int64)))
+            counts = torch.full((d,), -1, dtype=torch.int16, device=DEV)
+            dl.dlion_aggregate(packed, d, counts)
+            torch.cuda.synchronize()
+            assert np.array_equal(to_np(counts), want), f"N={N} d={d}: counts"
+            for mode in (dl.VOTE, dl.AVG):
+                xv = rng.normal(0, 0.02, d).astype(np.float32)
+                xn = xv.copy()
+                oracle.apply(xn, want, N, mode, 0.25, 0.5)
+                x = torch.from_numpy(xv).to(DEV)
+                dl.dlion_aggregate_apply(x, packed, mode, 0.25, 0.5)
+                delta = torch.full((dl.dlion_delta_planes(N, mode), W), -1, dtype=torch.int64, device=DEV)
+                dl.dlion_aggregate_encode(packed, d, mode, delta)
+                torch.cuda.synchronize()
+                assert_f32_equal(to_np(x), xn, f"N={N} d={d} mode={mode}: x")
+                assert np.array_equal(to_np(delta), oracle.encode_delta(want, N, mode)), f"N={N} d={d} mode={mode}: planes"
+
+
 def offset_view(shape, dtype, skip):
     """Tensor of the given shape that starts `skip` elements into its allocation (allocations are
     256-byte aligned, so skip = 1 leaves only the element's own alignment)."""
