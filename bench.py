@@ -91,7 +91,7 @@ def cpu_baseline(w, x, m, g):
     }
 
 
-def recorded_traffic(workload: str):
+def recorded_traffic(workload: str, entry: str = "step"):
     """HBM bytes per step from the committed rocprofv3 --pmc summary of this workload, if there is one.
 
     The counters cannot be read from inside this process; the figure is the one
@@ -102,7 +102,8 @@ def recorded_traffic(workload: str):
     import glob
     import re
 
-    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", f"*_{workload}.md"))):
+    prefix = "dlion_aggregate" if workload == "packed256_1b" and entry == "step" else f"dlion_{entry}"
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", f"{prefix}_{workload}.md"))):
         try:
             with open(path) as f:
                 m = re.search(r"traffic_bytes_per_launch:\s*(\d+)", f.read())
@@ -166,8 +167,12 @@ def memory_ceilings(dev):
     return out
 
 
-def run_workload(name, steps, warmup, dev, with_cpu_baseline=False):
-    """Measure one workload; returns the record for the JSON line."""
+ENTRIES = ("step", "worker_step", "aggregate", "apply", "aggregate_apply", "aggregate_encode", "apply_encoded")
+
+
+def run_workload(name, steps, warmup, dev, with_cpu_baseline=False, entry="step"):
+    """Measure one workload; returns the record for the JSON line.  entry != "step": one of the unfused
+    calls on the same state instead of the fused step (flat workloads with gradients only)."""
     import torch
 
     import paper_2404_00438_amd as dl
@@ -215,6 +220,35 @@ def run_workload(name, steps, warmup, dev, with_cpu_baseline=False):
 
         def step():
             dl.dlion_step_ws(x, m, g, w.mode, w.beta1, w.beta2, w.lr, w.lam, workspace)
+
+        if entry != "step":
+            # the unfused calls, on packed words / counts / planes that the library's own calls produced
+            W = dl.words_for(w.d)
+            packed = torch.zeros((w.N, wl.padded_words(W)), dtype=torch.int64, device=dev)[:, :W]
+            counts = torch.empty(w.d, dtype=torch.int16, device=dev)
+            planes = dl.dlion_delta_planes(w.N, w.mode)
+            delta = torch.zeros((planes, wl.padded_words(W)), dtype=torch.int64, device=dev)[:, :W]
+            dl.dlion_worker_step(m, g, packed, w.beta1, w.beta2)
+            dl.dlion_aggregate(packed, w.d, counts)
+            dl.dlion_aggregate_encode(packed, w.d, w.mode, delta)
+            calls = {
+                "worker_step": (lambda: dl.dlion_worker_step(m, g, packed, w.beta1, w.beta2),
+                                w.d * w.N * (8 + g_bytes) + w.N * W * 8),
+                "aggregate": (lambda: dl.dlion_aggregate(packed, w.d, counts), w.N * W * 8 + 2 * w.d),
+                "apply": (lambda: dl.dlion_apply(x, counts, w.N, w.mode, w.lr, w.lam), 10 * w.d),
+                "aggregate_apply": (lambda: dl.dlion_aggregate_apply(x, packed, w.mode, w.lr, w.lam),
+                                    w.N * W * 8 + 8 * w.d),
+                "aggregate_encode": (lambda: dl.dlion_aggregate_encode(packed, w.d, w.mode, delta),
+                                     w.N * W * 8 + planes * W * 8),
+                "apply_encoded": (lambda: dl.dlion_apply_encoded(x, delta, w.N, w.mode, w.lr, w.lam),
+                                  8 * w.d + planes * W * 8),
+            }
+            step, bytes_per_step = calls[entry]
+            kernel = f"dlion_{entry} (packed rows and planes on 1 KB boundaries"
+            ws_bytes = 0
+            if entry != "worker_step":
+                metric = f"coordinates/s (d per call of dlion_{entry})"
+                units = w.d
     if w.g_dist != "packed_bernoulli":
         kernel += (f"; launches over 8 workers each, votes handed on in a {ws_bytes >> 20} MiB workspace)"
                    if ws_bytes else ")")
@@ -222,7 +256,7 @@ def run_workload(name, steps, warmup, dev, with_cpu_baseline=False):
 
     kernel_ms, wall = timed(step, steps, warmup)
     achieved = bytes_per_step / (kernel_ms * 1e-3) / 1e9
-    traffic, source = recorded_traffic(w.name)
+    traffic, source = recorded_traffic(w.name, entry)
     rec = {
         "metric": metric,
         "value": units * steps / wall,
@@ -259,6 +293,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default=HEADLINE)
+    ap.add_argument("--entry", default="step", choices=ENTRIES,
+                    help="measure one of the unfused calls on the workload's state instead of the fused step "
+                         "(flat workloads with gradients; implies --headline-only --no-cpu-baseline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--headline-only", action="store_true",
                     help="measure only --workload: no memory-rate ceilings, no short runs of the other workloads")
@@ -287,7 +324,14 @@ def main() -> int:
     torch.cuda.set_device(0)
     dl.load_library()
 
-    rec = run_workload(args.workload, args.steps, args.warmup, dev, with_cpu_baseline=not args.no_cpu_baseline)
+    if args.entry != "step":
+        cfg = wl.CONFIGS[args.workload]
+        if cfg.shapes is not None or cfg.g_dist == "packed_bernoulli":
+            print("--entry other than step needs a flat workload with gradients", file=sys.stderr)
+            return 2
+        args.headline_only = args.no_cpu_baseline = True
+    rec = run_workload(args.workload, args.steps, args.warmup, dev, with_cpu_baseline=not args.no_cpu_baseline,
+                       entry=args.entry)
     torch.cuda.empty_cache()
     out = {
         "metric": rec["metric"], "value": rec["value"], "unit": rec["unit"], "n_gpus": 1,

@@ -8,7 +8,7 @@ Usage (after the rocprofv3 runs named in the summary it writes)::
 
 ``S.db`` comes from ``rocprofv3 --kernel-trace --stats``, ``F.db`` / ``W.db`` from ``--pmc FETCH_SIZE`` /
 ``--pmc WRITE_SIZE`` and ``B.db`` from ``--pmc MeanOccupancyPerCU VALUBusy``, each over
-``bench.py --workload W --headline-only --no-cpu-baseline --copy-calibration``.  The counters are scaled
+``bench.py --workload W [--entry E] --headline-only --no-cpu-baseline --copy-calibration``.  The counters are scaled
 against the 1 GiB device copies that ``--copy-calibration`` adds to the run.  ``--trace-steps`` /
 ``--pmc-steps`` are steps + warm-up steps of the respective runs, i.e. how many steps' launches the
 databases hold.  Only reads the databases; nothing here runs on a GPU.
@@ -44,6 +44,7 @@ def counters(db):
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--workload", required=True)
+    ap.add_argument("--entry", default="step", help="what bench.py measured (its --entry)")
     ap.add_argument("--kernel", required=True, help="substring of the kernel name(s) the summary is about")
     ap.add_argument("--title", required=True)
     ap.add_argument("--stats", required=True)
@@ -70,7 +71,8 @@ def main(argv=None) -> int:
     write_bytes = sum(r[2] * r[3] for r in wks) / a.pmc_steps * w_scale * 1024
     launches = sum(r[2] for r in fks) / a.pmc_steps
     ks = [r for r in k if a.kernel in r[0]]
-    bench = f"python3 $R/bench.py --workload {a.workload} --headline-only --no-cpu-baseline --copy-calibration"
+    bench = (f"python3 $R/bench.py --workload {a.workload}" + (f" --entry {a.entry}" if a.entry != "step" else "") +
+             " --headline-only --no-cpu-baseline --copy-calibration")
 
     L = [f"# rocprofv3 summary: {a.title}, workload `{a.workload}`\n",
          "Commands (run from /tmp with TMPDIR=/tmp, repository root = $R; each rocprofv3 run on its own):\n", "```",
@@ -80,17 +82,19 @@ def main(argv=None) -> int:
          f"rocprofv3 --pmc WRITE_SIZE -d $T/write -o write -- {bench} --steps 5 --warmup 1"]
     if a.busy:
         L.append(f"rocprofv3 --pmc MeanOccupancyPerCU VALUBusy -d $T/busy -o busy -- {bench} --steps 5 --warmup 1")
-    L.append(f"python3 -m paper_2404_00438_amd.profile_summary --workload {a.workload} --kernel {a.kernel} "
+    L.append(f"python3 -m paper_2404_00438_amd.profile_summary --workload {a.workload} "
+             + (f"--entry {a.entry} " if a.entry != "step" else "") + f"--kernel {a.kernel} "
              f"--title \"{a.title}\" --stats $T/stats/stats_results.db --fetch $T/fetch/fetch_results.db "
              f"--write $T/write/write_results.db" + (" --busy $T/busy/busy_results.db" if a.busy else "") +
              f" --trace-steps {a.trace_steps} --pmc-steps {a.pmc_steps}" +
              (" --bench-log $T/stats.log" if a.bench_log else "") + " --out profiles/<this file>")
-    L += ["```\n", "## Kernel trace (--kernel-trace --stats), top kernels by total time\n",
+    L += ["```\n", "## Kernel trace (--kernel-trace --stats): the kernel in question, then the top kernels by total time\n",
           "| kernel | calls | total ms | avg us | min us | max us | % |", "|---|---|---|---|---|---|---|"]
-    for r in k[:6]:
+    for r in ks + [r for r in k if r not in ks][:6]:
         L.append(f"| `{r[0][:110]}` | {r[1]} | {r[2] / 1e6:.3f} | {r[3] / 1e3:.2f} | {r[4] / 1e3:.2f} | "
                  f"{r[5] / 1e3:.2f} | {100 * r[2] / total:.1f} |")
-    L.append("\nRows other than the library's kernels are input generation (torch random draws) and the calibration copy.\n")
+    L.append("\nRows other than the library's kernels are input generation (torch random draws) and the calibration copy; "
+             "membench_kernel is the memory-rate probe behind the ceilings below.\n")
     L.append("## Launch shape (from the counter run's dispatch records)\n")
     for r in fks:
         L.append(f"- `{r[0][:100]}`: grid up to {r[11]} work-items, workgroup {r[10]}, VGPRs {r[6]}, AGPRs {r[7]}, "
