@@ -533,6 +533,9 @@ inline int32_t delta_planes(int32_t N, int mode)
     return (N % 2 == 0) ? 2 : 1;
 }
 
+constexpr int kEncodeBlocks = 16;
+constexpr int kGroupEncodeMinWorkers = 12;     // below: the bit-sliced encoder (see the few-worker kernel's launch)
+
 template <int kPlanes, int kWaves>
 dlion_status launch_encode_shape(const FlatAddr &addr, const Hyper &h, const DeltaOut &out, hipStream_t s)
 {
@@ -541,7 +544,9 @@ dlion_status launch_encode_shape(const FlatAddr &addr, const Hyper &h, const Del
     return launch_in_blocks(addr, (groups + kWaves - 1) / kWaves, kWaves * (kSlicedWords / kWordsPerTile),
                             h.N / 8 + 1 + out.n_planes / 8, kWaves > 1, [&](FlatAddr a, int64_t n) {
         a.first_tile *= kWaves;
-        return launch(aggregate_encode_kernel<kPlanes, kWaves>, grid_for(n), dim3(kLanes * kWaves), 0, s, a, h, out);
+        // one-wave workgroups: at most 16 resident per compute unit (the kernel itself uses no LDS)
+        const size_t lds = kWaves == 1 ? lds_reservation(kEncodeBlocks) : 0;
+        return launch(aggregate_encode_kernel<kPlanes, kWaves>, grid_for(n), dim3(kLanes * kWaves), lds, s, a, h, out);
     });
 }
 
@@ -550,9 +555,12 @@ dlion_status launch_encode_planes(const FlatAddr &addr, const Hyper &h, const De
 {
     const int env_waves = tuning().sliced_waves;
     // 16 waves from N = 64 on (N = 256, d = 1 G: vote 5.15 -> 5.03 ms, average 6.00 -> 5.49 ms; N = 64:
-    // 1.48 -> 1.44 and 1.69 -> 1.60 ms; at N = 32 and below 8 waves are the better size)
+    // 1.48 -> 1.44 and 1.69 -> 1.60 ms).  The very few workers that the few-worker kernel leaves to this
+    // one (N < 12: a message of 30-300 us) run as one-wave workgroups, 16 to a compute unit: packed rows on
+    // 1 KB boundaries, N = 8, d = 124 M 62-66 -> 72-73 % of peak, d = 1.3 G 74-77 -> 79-81 %.
     const int waves = env_waves > 0 ? env_waves
-                      : (sliced_groups(addr.p.numel) < kSlicedMinGroups ? 1 : (h.N >= 64 ? 16 : kSlicedWaves));
+                      : (sliced_groups(addr.p.numel) < kSlicedMinGroups || h.N < kGroupEncodeMinWorkers
+                             ? 1 : (h.N >= 64 ? 16 : kSlicedWaves));
     if (waves >= 16 && kPlanes <= 9)
         return launch_encode_shape<kPlanes, kPlanes <= 9 ? 16 : 8>(addr, h, out, s);
     if (waves >= 8)
@@ -592,7 +600,6 @@ constexpr int kGroupMaxWorkers = 120;          // counts up to 127 fit the kerne
 constexpr int kGroupApplyMaxWorkers = 120;     // fused update: ahead of the bit-sliced kernel up to the limit
 constexpr int kGroupCountsMaxWorkers = 100;    // counts only: level with it at N = 120
 constexpr int kGroupEncodeMaxWorkers = 64;
-constexpr int kGroupEncodeMinWorkers = 12;
 
 // resident workgroups (of 8 waves) per compute unit; 0 = as many as fit (4)
 inline int group_blocks(const Hyper &h, bool apply, bool encode)
