@@ -412,8 +412,12 @@ dlion_status launch_in_blocks(const Addr &addr, int64_t units, int64_t tiles_per
 {
     const int64_t forced = tuning().block_tiles;           // 0 = all in one launch
     int64_t tiles = (sliced ? kSlicedBlockBytes : kBlockBytes) / (kTile * bytes_per_coord);
-    if (sliced && tiles < kSlicedBlockTiles)
-        tiles = kSlicedBlockTiles;
+    if (sliced) {
+        // whole rounds only: a launch of 1.2 rounds runs as long as one of 2
+        tiles = (tiles + kSlicedBlockTiles / 2) / kSlicedBlockTiles * kSlicedBlockTiles;
+        if (tiles < kSlicedBlockTiles)
+            tiles = kSlicedBlockTiles;
+    }
     int64_t block = forced > 0 ? forced / tiles_per_unit : (forced == 0 ? units : tiles / tiles_per_unit);
     if (block < 1)
         block = 1;
@@ -441,12 +445,15 @@ dlion_status launch_aggregate(const Addr &addr, const Hyper &h, bool apply, bool
 
 // Bit-sliced counting (flat buffers): planes = bits needed for a count 0..N; waves per
 // workgroup is 1, or as many (up to 16) as fit the 160 KB of LDS with one region per wave.
+constexpr int kSlicedOneWaveBlocks = 16;
 template <int kPlanes, int kWaves>
 dlion_status launch_sliced_shape(const FlatAddr &addr, const Hyper &h, bool apply, bool counts, hipStream_t s)
 {
     const int64_t W = words_for(addr.p.numel);
     const int64_t groups = (W + kSlicedWords - 1) / kSlicedWords;
-    const size_t lds = static_cast<size_t>(kWaves) * kPlanes * kSlicedLdsPerPlane * sizeof(uint32_t);
+    size_t lds = static_cast<size_t>(kWaves) * kPlanes * kSlicedLdsPerPlane * sizeof(uint32_t);
+    if (kWaves == 1 && lds_reservation(kSlicedOneWaveBlocks) > lds)
+        lds = lds_reservation(kSlicedOneWaveBlocks);          // at most 16 one-wave workgroups per compute unit
     // a word group of kSlicedWords words is kSlicedWords / kWordsPerTile tiles; a workgroup takes kWaves groups
     const int64_t bytes = h.N / 8 + 1 + (apply ? 8 : 0) + (counts ? 2 : 0);
     return launch_in_blocks(addr, (groups + kWaves - 1) / kWaves, kWaves * (kSlicedWords / kWordsPerTile), bytes,
@@ -461,38 +468,47 @@ dlion_status launch_sliced_shape(const FlatAddr &addr, const Hyper &h, bool appl
     });
 }
 
-// Waves per workgroup of the bit-sliced kernels (they walk the streams in lockstep and write
-// together).  Measured with streaming count stores, N = 16 / 32 / 64 / 256 (d = 350 M, 350 M,
-// 1 G, 1 G), counts only: 1 wave 0.261 / 0.379 / 1.82 / 6.43 ms, 8 waves 0.249 / 0.367 / 1.75 /
-// 5.67 ms, 16 waves 0.270 / 0.395 / 1.74 / 5.45 ms; with the weight update fused 16 waves lose
-// below N = 128 (N = 64: 3.03 against 2.86 ms).
+// Waves per workgroup of the bit-sliced kernels.  Workgroups of 8 or 16 waves walk the streams in
+// lockstep and write together; with launches of whole rounds they run at 74-86 % of peak for every
+// N from 65 to 1000 (d = 124 M to 1 G; a launch of 1.2 rounds, which the byte rule alone gave at
+// N = 192 or 512, ran at 60-67 %).  One-wave workgroups (16 to a compute unit, two rows in flight)
+// are level with them for the counts and 2-6 % behind for the fused update and the message at large
+// d, and well behind when d is small and N large (N = 2000, d = 16 M: 71 against 85 %; N = 65535,
+// d = 1 M: 3 against 8 %); they are kept for problems of a few dozen groups of 128 words.  16 waves
+// need a workgroup for every compute unit (N = 130, d = 16 M: 8 waves 72-79 %, 16 waves 50-57 %).
 constexpr int kSlicedWaves = 8;
 constexpr int kSliced16MinWorkers = 128;
-
-// Flat buffers with more workers than the few-worker kernel takes (aggregate_group_kernel, below) go
-// to the bit-sliced kernel: with 128-bit streaming count stores it beats the per-nibble kernel at
-// every N.  The exception is the fused update at small d: a bit-sliced wave owns 8192 coordinates
-// and walks their x in 32 dependent steps, which few waves cannot hide.  The per-nibble kernel also
-// serves the tensor lists' fused aggregate + update beyond the few-worker kernel's N.
-constexpr int64_t kSlicedMinGroups = 4096;     // groups of 128 words: 33.5 M coordinates
+constexpr int64_t kSlicedMinGroups = 4096;     // groups of 128 words for 16-wave workgroups: 33.5 M coordinates
+constexpr int64_t kSlicedMinGroups8 = 64;      // ... and for 8-wave workgroups
 
 inline int64_t sliced_groups(int64_t numel) { return (words_for(numel) + kSlicedWords - 1) / kSlicedWords; }
 
-inline bool use_sliced(int32_t N, int64_t numel, bool apply)
+// waves per workgroup when `wanted` (8 or 16) lockstep waves suit N
+inline int sliced_waves_for(int64_t numel, int wanted)
+{
+    const int forced = tuning().sliced_waves;              // 1, 8 or 16
+    if (forced > 0)
+        return forced;
+    const int64_t groups = sliced_groups(numel);
+    if (wanted >= 16 && groups >= kSlicedMinGroups)
+        return 16;
+    return groups >= kSlicedMinGroups8 ? 8 : 1;
+}
+
+// Flat buffers with more workers than the few-worker kernel takes (aggregate_group_kernel, below) go
+// to the bit-sliced kernel at every N and d (the per-nibble kernel, which reads 32 bytes of a row per
+// wave, runs the fused update at N = 4096, d = 33 M at 18 % of peak); the per-nibble kernel serves the
+// tensor lists' fused aggregate + update beyond the few-worker kernel's N.
+inline bool use_sliced(int32_t N)
 {
     const int forced = tuning().sliced_min_workers;       // per-nibble kernel below this N
-    if (forced >= 0)
-        return N >= forced;
-    return !apply || sliced_groups(numel) >= kSlicedMinGroups;
+    return forced < 0 || N >= forced;
 }
 
 template <int kPlanes, bool kAllow16>
 dlion_status launch_sliced_planes(const FlatAddr &addr, const Hyper &h, bool apply, bool counts, hipStream_t s)
 {
-    const int env_waves = tuning().sliced_waves;            // forced: 1, 8 or 16
-    // few groups: one-wave workgroups spread them over more compute units (d = 4 M, N = 32: 7.6 against 12.1 us)
-    const bool small = sliced_groups(addr.p.numel) < kSlicedMinGroups;
-    const int waves = env_waves > 0 ? env_waves : (small ? 1 : (h.N >= kSliced16MinWorkers ? 16 : kSlicedWaves));
+    const int waves = sliced_waves_for(addr.p.numel, h.N >= kSliced16MinWorkers ? 16 : kSlicedWaves);
     if (waves >= 16 && kAllow16)
         return launch_sliced_shape<kPlanes, kAllow16 ? 16 : 8>(addr, h, apply, counts, s);
     if (waves >= 8)
@@ -533,7 +549,6 @@ inline int32_t delta_planes(int32_t N, int mode)
     return (N % 2 == 0) ? 2 : 1;
 }
 
-constexpr int kEncodeBlocks = 16;
 constexpr int kGroupEncodeMinWorkers = 12;     // below: the bit-sliced encoder (see the few-worker kernel's launch)
 
 template <int kPlanes, int kWaves>
@@ -545,7 +560,7 @@ dlion_status launch_encode_shape(const FlatAddr &addr, const Hyper &h, const Del
                             h.N / 8 + 1 + out.n_planes / 8, kWaves > 1, [&](FlatAddr a, int64_t n) {
         a.first_tile *= kWaves;
         // one-wave workgroups: at most 16 resident per compute unit (the kernel itself uses no LDS)
-        const size_t lds = kWaves == 1 ? lds_reservation(kEncodeBlocks) : 0;
+        const size_t lds = kWaves == 1 ? lds_reservation(kSlicedOneWaveBlocks) : 0;
         return launch(aggregate_encode_kernel<kPlanes, kWaves>, grid_for(n), dim3(kLanes * kWaves), lds, s, a, h, out);
     });
 }
@@ -553,14 +568,12 @@ dlion_status launch_encode_shape(const FlatAddr &addr, const Hyper &h, const Del
 template <int kPlanes>
 dlion_status launch_encode_planes(const FlatAddr &addr, const Hyper &h, const DeltaOut &out, hipStream_t s)
 {
-    const int env_waves = tuning().sliced_waves;
     // 16 waves from N = 64 on (N = 256, d = 1 G: vote 5.15 -> 5.03 ms, average 6.00 -> 5.49 ms; N = 64:
     // 1.48 -> 1.44 and 1.69 -> 1.60 ms).  The very few workers that the few-worker kernel leaves to this
     // one (N < 12: a message of 30-300 us) run as one-wave workgroups, 16 to a compute unit: packed rows on
     // 1 KB boundaries, N = 8, d = 124 M 62-66 -> 72-73 % of peak, d = 1.3 G 74-77 -> 79-81 %.
-    const int waves = env_waves > 0 ? env_waves
-                      : (sliced_groups(addr.p.numel) < kSlicedMinGroups || h.N < kGroupEncodeMinWorkers
-                             ? 1 : (h.N >= 64 ? 16 : kSlicedWaves));
+    const int waves = h.N < kGroupEncodeMinWorkers && tuning().sliced_waves <= 0
+                          ? 1 : sliced_waves_for(addr.p.numel, h.N >= 64 ? 16 : kSlicedWaves);
     if (waves >= 16 && kPlanes <= 9)
         return launch_encode_shape<kPlanes, kPlanes <= 9 ? 16 : 8>(addr, h, out, s);
     if (waves >= 8)
@@ -598,7 +611,7 @@ dlion_status launch_encode(const FlatAddr &addr, const Hyper &h, const DeltaOut 
 // cost either kernel 3-8 % (a wave's 1 KB piece of a row then shares lines with its neighbours').
 constexpr int kGroupMaxWorkers = 120;          // counts up to 127 fit the kernel's byte lanes
 constexpr int kGroupApplyMaxWorkers = 120;     // fused update: ahead of the bit-sliced kernel up to the limit
-constexpr int kGroupCountsMaxWorkers = 100;    // counts only: level with it at N = 120
+constexpr int kGroupCountsMaxWorkers = 64;     // counts only: behind it from N = 65 on (69 against 76 %)
 constexpr int kGroupEncodeMaxWorkers = 64;
 
 // resident workgroups (of 8 waves) per compute unit; 0 = as many as fit (4)
@@ -858,7 +871,7 @@ dlion_status dlion_aggregate(const uint64_t *packed, int64_t packed_stride, int6
                                  packed_stride, counts);
     if (use_group(N, kGroupCounts))
         return launch_group(a, h, false, true, nullptr, static_cast<hipStream_t>(stream));
-    if (use_sliced(N, d, false))
+    if (use_sliced(N))
         return launch_sliced(a, h, false, true, static_cast<hipStream_t>(stream));
     return launch_aggregate(a, h, false, true, static_cast<hipStream_t>(stream));
 }
@@ -892,7 +905,7 @@ dlion_status dlion_aggregate_apply(float *x, const uint64_t *packed, int64_t pac
                                  counts_or_null);
     if (use_group(N, kGroupApply))
         return launch_group(a, h, true, counts_or_null != nullptr, nullptr, static_cast<hipStream_t>(stream));
-    if (use_sliced(N, d, true))
+    if (use_sliced(N))
         return launch_sliced(a, h, true, counts_or_null != nullptr, static_cast<hipStream_t>(stream));
     return launch_aggregate(a, h, true, counts_or_null != nullptr, static_cast<hipStream_t>(stream));
 }
@@ -1030,7 +1043,7 @@ dlion_status dlion_aggregate_mt(const dlion_seg *segs_host, const dlion_seg *seg
         return DLION_EALIGN;
     Hyper h = make_hyper(N, DLION_VOTE, 0.0f, 0.0f, 0.0f, 0.0f);
     h.stream_counts = counts_exceed_cache(64 * words);
-    if (use_group(N, kGroupCounts) || use_sliced(N, 64 * words, false)) {
+    if (use_group(N, kGroupCounts) || use_sliced(N)) {
         // packed words and counts of a tensor list are laid out by word, the padding bits of every
         // tensor's last word are zero: counting is the flat problem over 64 * words coordinates
         const FlatAddr f = flat_addr(nullptr, nullptr, 0, nullptr, 0, 64 * words, const_cast<uint64_t *>(packed),

@@ -733,7 +733,6 @@ constexpr int kWpl = 2;                                // consecutive words of e
 constexpr int kSlices = 2 * kWpl;                      // 32-bit slices a lane carries
 constexpr int kSlicedWords = kLanes * kWpl;            // words per wave
 constexpr int kSlicedCoords = kSlicedWords * 64;
-constexpr int kSlicedInFlight = 4;                     // rows whose loads a wave has outstanding at once
 
 typedef u32x4 words2_e __attribute__((aligned(8)));
 
@@ -765,6 +764,10 @@ __device__ __forceinline__ void sliced_count(const Problem &p, int N, int64_t w0
 {
     static_assert(kPlanes >= 5 && kPlanes <= 16, "planes");
     static_assert(kWpl == 2, "a lane reads its two words of a row as one 128-bit load");
+    // rows whose loads a wave has outstanding at once: one-wave workgroups, 16 or so to a compute unit,
+    // want two (32 KB per compute unit) unless the rows are few (N < 32: four, for fewer round trips); the
+    // 8 or 16 waves of a lockstep workgroup four
+    constexpr int kSlicedInFlight = (kWaves == 1 && kPlanes > 5) ? 2 : 4;
     const int64_t wl0 = w0 + (int64_t)lane * kWpl;              // first word of the lane
     // whole group inside the word range: full-width loads, no per-lane guards
     const bool fast = w0 + kSlicedWords <= W;

@@ -299,9 +299,9 @@ def test_tiny_config_full_run():
 
 @pytest.mark.parametrize("waves", [1, 8, 16])
 def test_many_worker_aggregate_matches_oracle(waves, tune):
-    """The bit-sliced server-side kernel: counts bit-exact, apply within the bar.  At these sizes the
-    library would pick one-wave workgroups (and the per-nibble kernel for the fused update), so the
-    bit-sliced kernel and its workgroup size are forced."""
+    """The bit-sliced server-side kernel: counts bit-exact, apply within the bar.  The library would give
+    the smaller N to the few-worker kernel and pick the workgroup size from N and d, so the bit-sliced
+    kernel and each of its workgroup sizes are forced."""
     tune(sliced_min_workers=1, sliced_waves=waves, group_max_workers=0)
     rng = np.random.default_rng(2024)
     cases = [(1, 300), (2, 8192), (3, 8193), (7, 70_001), (8, 129), (15, 5000),
