@@ -1284,11 +1284,6 @@ constexpr int kGroupWords = 128;                        // words per workgroup
 constexpr int kGroupCoords = kGroupWords * 64;          // 8192
 constexpr int kLineWords = kLineSubs * kWordsPerTile;   // 16 words = 1024 coordinates per wave
 
-__device__ __forceinline__ void stream_store_b32(uint32_t v, void *p)
-{
-    asm volatile("global_store_dword %0, %1, off " DLION_STREAM_STORE_POLICY : : "v"(p), "v"(v) : "memory");
-}
-
 // bit-sliced a + b on kIn planes -> kIn + 1 planes
 template <int kIn>
 __device__ __forceinline__ void add_planes(const uint32_t (&a)[kIn], const uint32_t (&b)[kIn], uint32_t (&sum)[kIn + 1])
