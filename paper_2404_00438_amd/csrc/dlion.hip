@@ -224,12 +224,12 @@ dlion_status launch_step_unroll(const Addr &addr, const Hyper &h, bool packed, b
     if (tuning().blocks_per_cu < 0) {
         if (problem_tiles <= kResidentWaves)
             shape.blocks_per_cu = 0;
-        else if (role == kWholeStep && shape.blocks_per_cu > 0 && std::is_same<Addr, SegAddr>::value)
-            shape.blocks_per_cu += 1;
-        else if (role == kWholeStep && shape.blocks_per_cu > 0 && h.beta1_pw)
-            // per-worker coefficients: a wave starts by fetching them and has nothing else in flight
-            // meanwhile; the next cap up makes up for it (bf16, N = 8: 12 -> 14 waves, d = 124 M
-            // 78.9 -> 81.3 % of peak, d = 1.3 G 77.9 -> 80.9 %)
+        else if (role == kWholeStep && shape.blocks_per_cu > 0 && (std::is_same<Addr, SegAddr>::value || h.beta1_pw))
+            // a tensor list's waves start with a table lookup, those of a step with per-worker
+            // coefficients by fetching them, and have nothing else in flight meanwhile; the next cap
+            // up makes up for it (per-worker coefficients, bf16, N = 8: 12 -> 14 waves, d = 124 M
+            // 78.9 -> 81.3 % of peak, d = 1.3 G 77.9 -> 80.9 %; the ViT list with bf16 gradients and
+            // N = 8: 79.3 -> 81.1 %, with fp32 gradients 11 -> 12 waves)
             shape.blocks_per_cu = next_cap(shape.blocks_per_cu);
     }
     const size_t lds = lds_reservation(shape.blocks_per_cu);
