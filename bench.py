@@ -26,11 +26,14 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, vendor figure
 HEADLINE = "gpt350m_vote32"
-# A process that allocates tens of GB while the memory a process before it freed is still on its way back to
-# the driver's pool runs 4 % slower for its whole life (measured: started at once after a 67 GB process
-# 18.5 ms per step, started 3 s or more later 17.8 ms, and 17.8 ms for 600 steps on end).  Every
-# measuring process therefore waits this long before it allocates.
-SETTLE_S = 4.0
+# A process that allocates tens of GB soon after another large process has exited runs 4 % slower for its
+# whole life (measured: started at once after a 67 GB process 18.5 ms per step, started 3 s or more later
+# 17.8 ms, and 17.8 ms for 600 steps on end; after a 250 GB process 4 s are not enough, 8 s are).  The
+# device reports all of its memory as free at once, so the wait cannot be replaced by a check.  Every
+# measuring process therefore waits before it allocates: this long when it does not know what ran before
+# it, SETTLE_CHILD_S in the processes this script starts itself (their predecessor held 70 GB at most).
+SETTLE_S = 12.0
+SETTLE_CHILD_S = 4.0
 
 
 def algorithmic_bytes_per_step(d: int, N: int, g_bytes: int) -> int:
@@ -296,6 +299,8 @@ def main() -> int:
     ap.add_argument("--entry", default="step", choices=ENTRIES,
                     help="measure one of the unfused calls on the workload's state instead of the fused step "
                          "(flat workloads with gradients; implies --headline-only --no-cpu-baseline)")
+    ap.add_argument("--settle", type=float, default=SETTLE_S,
+                    help="seconds to wait before the first allocation (see SETTLE_S)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--headline-only", action="store_true",
                     help="measure only --workload: no memory-rate ceilings, no short runs of the other workloads")
@@ -319,7 +324,7 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
-    time.sleep(SETTLE_S)
+    time.sleep(max(0.0, args.settle))
     dev = "cuda:0"
     torch.cuda.set_device(0)
     dl.load_library()
@@ -368,7 +373,8 @@ def main() -> int:
             # about 0.1-0.2 s of timed work each
             n_steps = {"tiny": 2000, "gpt2s_avg8": 80, "vitb16_vote16": 50}.get(name, 8)
             cmd = [sys.executable, os.path.abspath(__file__), "--workload", name, "--headline-only",
-                   "--no-cpu-baseline", "--steps", str(n_steps), "--warmup", str(max(2, n_steps // 10))]
+                   "--no-cpu-baseline", "--settle", str(SETTLE_CHILD_S), "--steps", str(n_steps),
+                   "--warmup", str(max(2, n_steps // 10))]
             res = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
             line = next((ln for ln in reversed(res.stdout.splitlines()) if ln.startswith("{")), None)
             if res.returncode != 0 or line is None:
