@@ -223,7 +223,7 @@ def test_tensor_list_matches_oracle(g_dtype, mode):
     rng = np.random.default_rng(777)
     numels = [1000, 5, 64, 256, 768, 257, 1, 2304 * 8, 4097, 63]
     hyp = dict(beta1=0.9, beta2=0.99, lr=1e-4, lam=10.0)
-    for N in (1, 4, 16, 5):
+    for N in (1, 4, 16, 5, 130):              # 130: beyond the few-worker kernel, the per-nibble one takes the list
         announce("tensor list", g_dtype, mode, "N", N)
         xs, ms, gs = make_list(rng, numels, N, g_dtype)
         table = dl.SegTable(xs, ms, gs)
